@@ -1,0 +1,111 @@
+"""Oracle (test infrastructure): Binary Block Matrix, run index, sparse block list, packed mask bits.
+
+Definitions (paper Sec. 4 "Binary Block Masking", "Dense Binary Block Masking"; Appendix A, the block-sum
+formulation) with the readings this build fixes where the paper is silent:
+
+* the mask is zero-padded to nbr*Br x nbc*Bc with nbr = ceil(N/Br), nbc = ceil(N/Bc) (the paper assumes
+  divisibility); a block that contains padding can therefore never be "filled with ones";
+* cnt[i][j]  = number of non-zero elements of block (i, j);   BinBlkMat[i][j] = (cnt > 0);
+* class[i][j] = 0 if cnt == 0, 2 if cnt == Br*Bc, else 1;
+* total_ones[i], offset[i] = length and first block of the LONGEST run of consecutive class-2 blocks in
+  block row i (leftmost on ties; (0, 0) if none) -- "blocks filled with ones" is read as all-ones blocks,
+  which is what lets the attention step skip the element mask inside the run;
+* nz_lo / nz_hi / nz_cnt = first non-zero block, one past the last, and their number ((0,0,0) if none);
+* sparse list: row_ptr[i+1]-row_ptr[i] = nz_cnt[i]; col_idx ascending, bit 31 set iff the block is class 2;
+  plane m of col_idx starts at m*nbr*nbc (fixed capacity), row_ptr is per plane and starts at 0;
+* packed[m][w][r] bit t (little-endian in a uint64) = (mask[m][r][64*w + t] != 0), zero beyond column N.
+"""
+import numpy as np
+
+
+def block_counts(mask, Br, Bc):
+    """mask [Mb,N,N] -> int64 [Mb,nbr,nbc] non-zero counts per block of the zero-padded mask."""
+    Mb, N, _ = mask.shape
+    nbr, nbc = -(-N // Br), -(-N // Bc)
+    out = np.zeros((Mb, nbr, nbc), dtype=np.int64)
+    for m in range(Mb):
+        pad = np.zeros((nbr * Br, nbc * Bc), dtype=np.uint8)
+        pad[:N, :N] = mask[m] != 0
+        out[m] = pad.reshape(nbr, Br, nbc, Bc).sum(axis=(1, 3), dtype=np.int64)
+    return out
+
+
+def block_class(mask, Br, Bc):
+    cnt = block_counts(mask, Br, Bc)
+    cls = np.ones(cnt.shape, dtype=np.uint8)
+    cls[cnt == 0] = 0
+    cls[cnt == Br * Bc] = 2
+    return cls
+
+
+def bin_blk_mat(mask, Br, Bc):
+    """The paper's BinBlkMat via its 'any element non-zero' wording (not via the counts)."""
+    Mb, N, _ = mask.shape
+    nbr, nbc = -(-N // Br), -(-N // Bc)
+    out = np.zeros((Mb, nbr, nbc), dtype=np.uint8)
+    for m in range(Mb):
+        for i in range(nbr):
+            for j in range(nbc):
+                out[m, i, j] = 1 if np.any(mask[m, i * Br:(i + 1) * Br, j * Bc:(j + 1) * Bc]) else 0
+    return out
+
+
+def run_index(cls):
+    """cls uint8 [Mb,nbr,nbc] -> dict of int32 [Mb,nbr] arrays: offset, total_ones, nz_lo, nz_hi, nz_cnt."""
+    Mb, nbr, nbc = cls.shape
+    res = {k: np.zeros((Mb, nbr), dtype=np.int32) for k in ("offset", "total_ones", "nz_lo", "nz_hi", "nz_cnt")}
+    for m in range(Mb):
+        for i in range(nbr):
+            row = cls[m, i]
+            best_len, best_start, j = 0, 0, 0
+            while j < nbc:
+                if row[j] == 2:
+                    s = j
+                    while j < nbc and row[j] == 2:
+                        j += 1
+                    if j - s > best_len:
+                        best_len, best_start = j - s, s
+                else:
+                    j += 1
+            res["offset"][m, i], res["total_ones"][m, i] = best_start, best_len
+            nz = [j for j in range(nbc) if row[j] != 0]
+            if nz:
+                res["nz_lo"][m, i], res["nz_hi"][m, i], res["nz_cnt"][m, i] = nz[0], nz[-1] + 1, len(nz)
+    return res
+
+
+def sparse_index(cls):
+    """cls [Mb,nbr,nbc] -> row_ptr int32 [Mb,nbr+1], col_idx uint32 [Mb*nbr*nbc] (unused tail entries = 0)."""
+    Mb, nbr, nbc = cls.shape
+    row_ptr = np.zeros((Mb, nbr + 1), dtype=np.int32)
+    col_idx = np.zeros(Mb * nbr * nbc, dtype=np.uint32)
+    for m in range(Mb):
+        p = 0
+        for i in range(nbr):
+            for j in range(nbc):
+                c = cls[m, i, j]
+                if c != 0:
+                    col_idx[m * nbr * nbc + p] = j | (0x80000000 if c == 2 else 0)
+                    p += 1
+            row_ptr[m, i + 1] = p
+    return row_ptr, col_idx
+
+
+def packed_bits(mask):
+    """mask [Mb,N,N] -> uint64 [Mb, ceil(N/64), N]: word-column major, bit t of word (w, r) = mask[r][64w+t] != 0."""
+    Mb, N, _ = mask.shape
+    W = -(-N // 64)
+    out = np.zeros((Mb, W, N), dtype=np.uint64)
+    for m in range(Mb):
+        nzr, nzc = np.nonzero(mask[m])
+        np.bitwise_or.at(out[m], (nzc // 64, nzr), np.uint64(1) << (nzc % 64).astype(np.uint64))
+    return out
+
+
+def block_index(mask, Br, Bc):
+    """Everything the preprocessing stage produces, as a dict."""
+    cls = block_class(mask, Br, Bc)
+    idx = dict(cls=cls, bin_blk_mat=(cls != 0).astype(np.uint8))
+    idx.update(run_index(cls))
+    idx["row_ptr"], idx["col_idx"] = sparse_index(cls)
+    return idx

@@ -1,0 +1,46 @@
+"""Oracle pins (test infrastructure): scalar-loop brute force for tiny inputs.
+
+Independent second formulations used only to pin the vectorised oracle: attention iterates explicitly over
+the allowed key set with math.exp / math.log; block counts use four nested loops over the zero-padded mask.
+"""
+import math
+import numpy as np
+
+
+def brute_attention(q, k, v, mask, scale):
+    """q,k,v float arrays [B,H,N,d]; mask [Mb,N,N]; pure Python loops.  Returns (O, lse) as float64 arrays."""
+    B, H, N, d = q.shape
+    Mb = mask.shape[0]
+    O = np.zeros((B, H, N, d))
+    lse = np.full((B, H, N), -math.inf)
+    for b in range(B):
+        mb = mask[b if Mb == B else 0]
+        for h in range(H):
+            for i in range(N):
+                A = [j for j in range(N) if mb[i, j] != 0]
+                if not A:
+                    continue
+                s = [scale * sum(float(q[b, h, i, c]) * float(k[b, h, j, c]) for c in range(d)) for j in A]
+                mx = max(s)
+                w = [math.exp(x - mx) for x in s]
+                tot = sum(w)
+                for c in range(d):
+                    O[b, h, i, c] = sum(wj * float(v[b, h, j, c]) for wj, j in zip(w, A)) / tot
+                lse[b, h, i] = mx + math.log(tot)
+    return O, lse
+
+
+def brute_block_counts(mask2d, Br, Bc):
+    """Count of non-zero elements in every Br x Bc block of one N x N mask, zero-padded; 4 nested loops."""
+    N = mask2d.shape[0]
+    nbr, nbc = -(-N // Br), -(-N // Bc)
+    cnt = [[0] * nbc for _ in range(nbr)]
+    for bi in range(nbr):
+        for bj in range(nbc):
+            c = 0
+            for r in range(bi * Br, min(N, (bi + 1) * Br)):
+                for s in range(bj * Bc, min(N, (bj + 1) * Bc)):
+                    if mask2d[r, s] != 0:
+                        c += 1
+            cnt[bi][bj] = c
+    return np.asarray(cnt, dtype=np.int64)

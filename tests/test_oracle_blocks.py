@@ -1,0 +1,159 @@
+"""Pins for oracle/blocks.py: brute force, the paper's two formulations, closed forms, pooling (CPU only)."""
+import os
+import numpy as np
+import pytest
+
+import oracle
+from workloads import masks
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return [tuple(int(x) for x in ln.split()) for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def _rand_mask(seed, N, Mb=1):
+    m = masks.random_blocks(128 * ((N + 127) // 128), seed, blk=16, p_empty=0.35, p_full=0.35)[0][:N, :N]
+    out = np.stack([np.roll(m, 5 * i, axis=1) for i in range(Mb)])
+    return (out * np.random.default_rng(seed).integers(1, 255, out.shape, dtype=np.uint8)).astype(np.uint8)
+
+
+@pytest.mark.parametrize("N,Br,Bc", [(64, 16, 16), (96, 32, 16), (50, 16, 32), (200, 64, 64), (37, 8, 16)])
+def test_counts_match_four_loop_brute_force(N, Br, Bc):
+    mask = _rand_mask(N, N, Mb=2)
+    cnt = oracle.block_counts(mask, Br, Bc)
+    for m in range(2):
+        assert np.array_equal(cnt[m], oracle.brute_block_counts(mask[m], Br, Bc))
+    assert cnt.sum() == np.count_nonzero(mask)
+
+
+@pytest.mark.parametrize("N,Br,Bc", [(64, 16, 16), (200, 64, 32), (50, 16, 32)])
+def test_any_formulation_equals_sum_formulation(N, Br, Bc):
+    """Sec. 4 defines BinBlkMat by 'any non-zero'; Appendix A's kernel by 'block sum > 0'."""
+    mask = _rand_mask(N + 1, N)
+    assert np.array_equal(oracle.bin_blk_mat(mask, Br, Bc), (oracle.block_counts(mask, Br, Bc) > 0).astype(np.uint8))
+    cls = oracle.block_class(mask, Br, Bc)
+    assert np.array_equal(cls != 0, oracle.bin_blk_mat(mask, Br, Bc) != 0)
+
+
+def test_shape_follows_paper():
+    for N, BI, BJ, r, c in _rows("bin_blk_mat_shape.txt"):
+        assert (N // BI, N // BJ) == (r, c)
+        m = np.zeros((1, N, N), dtype=np.uint8)
+        assert oracle.block_class(m, BI, BJ).shape == (1, r, c)
+    assert oracle.bin_blk_mat(np.zeros((1, 256, 256), dtype=np.uint8), 128, 32).shape == (1, 2, 8)
+
+
+def test_padded_tail_block_is_never_full():
+    mask = np.ones((1, 200, 200), dtype=np.uint8)
+    cls = oracle.block_class(mask, 64, 64)[0]
+    assert cls.shape == (4, 4)
+    assert np.all(cls[:3, :3] == 2) and np.all(cls[3, :] == 1) and np.all(cls[:, 3] == 1)
+    r = oracle.run_index(cls[None])
+    assert list(r["total_ones"][0]) == [3, 3, 3, 0] and list(r["offset"][0]) == [0, 0, 0, 0]
+
+
+def test_or_pooling_consistency():
+    mask = _rand_mask(3, 256)
+    fine = oracle.bin_blk_mat(mask, 16, 16)[0]
+    coarse = oracle.bin_blk_mat(mask, 32, 32)[0]
+    pooled = fine.reshape(8, 2, 8, 2).max(axis=(1, 3))
+    assert np.array_equal(coarse, pooled)
+    cf, cc = oracle.block_class(mask, 16, 16)[0], oracle.block_class(mask, 32, 32)[0]
+    assert np.array_equal(cc == 2, (cf.reshape(8, 2, 8, 2) == 2).all(axis=(1, 3)))
+
+
+def test_all_ones_closed_form():
+    idx = oracle.block_index(masks.all_ones(256), 64, 32)
+    assert np.all(idx["cls"] == 2) and np.all(idx["bin_blk_mat"] == 1)
+    assert np.all(idx["offset"] == 0) and np.all(idx["total_ones"] == 8)
+    assert np.all(idx["nz_lo"] == 0) and np.all(idx["nz_hi"] == 8) and np.all(idx["nz_cnt"] == 8)
+    assert list(idx["row_ptr"][0]) == [0, 8, 16, 24, 32]
+    assert np.array_equal(idx["col_idx"], np.tile(np.arange(8, dtype=np.uint32) | np.uint32(0x80000000), 4))
+
+
+def test_causal_closed_form_square_tiles():
+    idx = oracle.block_index(masks.causal(512), 64, 64)
+    for i in range(8):
+        assert list(idx["cls"][0, i]) == [2] * i + [1] + [0] * (7 - i)
+        assert (idx["offset"][0, i], idx["total_ones"][0, i]) == (0, i)
+        assert (idx["nz_lo"][0, i], idx["nz_hi"][0, i], idx["nz_cnt"][0, i]) == (0, i + 1, i + 1)
+
+
+def test_causal_closed_form_paper_tile_128x32():
+    idx = oracle.block_index(masks.causal(1024), 128, 32)
+    for i in range(8):
+        assert idx["total_ones"][0, i] == 4 * i and idx["offset"][0, i] == 0
+        assert idx["nz_cnt"][0, i] == 4 * i + 4
+        assert list(idx["cls"][0, i, 4 * i:4 * i + 4]) == [1, 1, 1, 1]
+
+
+def test_sliding_window_closed_form():
+    # |i-j| <= 64 with 32x32 tiles: block (i,j) is full iff |i-j| <= 1, partial iff |i-j| in {2, 3}... derive:
+    # full iff max |r-c| over the block = 32|i-j| + 31 <= 64 -> |i-j| <= 1; non-empty iff 32|i-j| - 31 <= 64 -> |i-j| <= 2
+    N, w = 512, 64
+    idx = oracle.block_index(masks.sliding_window(N, w), 32, 32)
+    nb = N // 32
+    for i in range(nb):
+        lo, hi = max(0, i - 2), min(nb, i + 3)
+        assert (idx["nz_lo"][0, i], idx["nz_hi"][0, i]) == (lo, hi)
+        flo, fhi = max(0, i - 1), min(nb, i + 2)
+        assert (idx["offset"][0, i], idx["total_ones"][0, i]) == (flo, fhi - flo)
+
+
+def test_longest_run_leftmost_tie_and_noncontiguous_rows():
+    cls = np.array([[[2, 2, 0, 2, 2, 1, 0],
+                     [1, 2, 0, 2, 2, 2, 0],
+                     [0, 0, 0, 0, 0, 0, 0],
+                     [0, 1, 0, 0, 0, 2, 0]]], dtype=np.uint8)
+    r = oracle.run_index(cls)
+    assert list(r["offset"][0]) == [0, 3, 0, 5]
+    assert list(r["total_ones"][0]) == [2, 3, 0, 1]
+    assert list(r["nz_lo"][0]) == [0, 0, 0, 1]
+    assert list(r["nz_hi"][0]) == [6, 6, 0, 6]
+    assert list(r["nz_cnt"][0]) == [5, 5, 0, 2]
+    rp, ci = oracle.sparse_index(cls)
+    assert list(rp[0]) == [0, 5, 10, 10, 12]
+    F = 0x80000000
+    assert list(ci[:12]) == [0 | F, 1 | F, 3 | F, 4 | F, 5, 0, 1 | F, 3 | F, 4 | F, 5 | F, 1, 5 | F]
+
+
+def test_sparse_index_planes_have_fixed_capacity():
+    cls = np.zeros((2, 2, 3), dtype=np.uint8)
+    cls[0, 1, 2] = 1
+    cls[1, 0, 0] = 2
+    cls[1, 1, 1] = 1
+    rp, ci = oracle.sparse_index(cls)
+    assert rp.tolist() == [[0, 0, 1], [0, 1, 2]]
+    assert ci[0] == 2 and ci[6] == 0x80000000 and ci[7] == 1 and ci.size == 12
+
+
+@pytest.mark.parametrize("N", [64, 200, 130])
+def test_packed_bits_roundtrip(N):
+    mask = _rand_mask(N + 7, N, Mb=2)
+    pk = oracle.packed_bits(mask)
+    W = -(-N // 64)
+    assert pk.shape == (2, W, N) and pk.dtype == np.uint64
+    # independent unpacking route: bytes -> bits, little-endian
+    by = pk.view(np.uint8).reshape(2, W, N, 8)
+    bits = np.unpackbits(by, axis=-1, bitorder="little")              # [Mb, W, N, 64]
+    full = bits.transpose(0, 2, 1, 3).reshape(2, N, W * 64)
+    assert np.array_equal(full[:, :, :N], (mask != 0).astype(np.uint8))
+    assert not full[:, :, N:].any()
+
+
+def test_skip_rule_matches_paper_wording():
+    """Sec. 4: the element mask is read only for visited blocks before `offset` or past the run of
+    `total_ones` blocks; every block inside [offset, offset+total_ones) must be all ones."""
+    mask = masks.packed_sequences(512, 1, 5, mu=4.0, hi=128)
+    idx = oracle.block_index(mask, 32, 32)
+    cnt = oracle.block_counts(mask, 32, 32)
+    for i in range(16):
+        o, t = idx["offset"][0, i], idx["total_ones"][0, i]
+        assert np.all(cnt[0, i, o:o + t] == 32 * 32)
+        for j in range(16):
+            inside = o <= j < o + t
+            if idx["bin_blk_mat"][0, i, j] and not inside and idx["cls"][0, i, j] == 2:
+                assert t >= 1            # a full block outside the run exists only if a longer/equal run was kept
