@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the Binary Block Masking forward path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch: mask -> block classes / BinBlkMat / packed bits
+-> run index -> sparse block list -> fused masked attention forward.  Inputs are synthetic, seeded and already
+resident in HBM when the timed region starts.  The headline workload is the packed-sequence mask
+(B=4, H=16, N=4096, d=64, one mask per batch entry); the other mask families are timed as extra rows.
+
+Prints ONE JSON line.  `value` = visited-tile TFLOP/s of the whole step (4*Br*Bc*d flops per visited tile per
+(batch, head)); `roofline` prices the attention kernel against the bf16 MFMA peak; `cpu_baseline` times the
+fp64 CPU oracle on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+HBM_PEAK_GBS = 8000.0              # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--Br", type=int, default=128)
+    ap.add_argument("--masks", default="C2,C3,C4,C5,C0d,C0c,C0d128,C0c128",
+                    help="comma list of extra per-mask rows (empty string = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-kernel", default="", help="profile helper: run only 'attn' or 'preprocess' launches")
+    return ap.parse_args()
+
+
+def time_gpu(fn, warmup, steps):
+    """Mean milliseconds per call, HIP events on the current stream around `steps` back-to-back calls."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def visited_tiles(idx, B, H):
+    """Sum over (batch, head, block row) of the number of tiles the schedule visits."""
+    per_plane = idx.nz_cnt.sum(dim=1).cpu().numpy().astype(np.int64)     # [Mb]
+    per_batch = per_plane if idx.Mb == B else np.repeat(per_plane, B)
+    return int(per_batch.sum()) * H
+
+
+def measure_mask(bbm, name, Br, warmup, steps, torch):
+    from workloads import make_config
+    cfg = make_config(name)
+    B, H, N, d, Mb = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["Mb"]
+    mask = torch.from_numpy(cfg["mask"]).cuda()
+    q, k, v = (bbm.bf16_from_bits(cfg[x]) for x in "qkv")
+    idx = bbm.build_index(mask, Br, 64)
+    out = torch.empty_like(q)
+    lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    tiles = visited_tiles(idx, B, H)
+    cls = idx.blk_class
+    census = dict(empty=int((cls == 0).sum()), partial=int((cls == 1).sum()), full=int((cls == 2).sum()))
+    flops = 4.0 * Br * 64 * d * tiles
+    dense_flops = 4.0 * N * N * d * B * H
+    useful_flops = 4.0 * float(np.count_nonzero(cfg["mask"])) * (B // Mb) * d * H
+
+    def step():
+        bbm.bbm_build_block_mask(mask, Br, 64, idx=idx)
+        bbm.bbm_build_runs(idx)
+        bbm.bbm_build_sparse_index(idx)
+        bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse)
+
+    res = dict(workload=name, B=B, H=H, N=N, d=d, Mb=Mb, Br=Br, Bc=64, visited_tiles=tiles, blocks=census,
+               visited_tflop=flops / 1e12, dense_tflop=dense_flops / 1e12, useful_tflop=useful_flops / 1e12)
+    res["step_ms"] = time_gpu(step, warmup, steps)
+    for mode_name in ("LIST", "RUNS", "BITMAP"):
+        mode = getattr(bbm, "BBM_MODE_" + mode_name)
+        ms = time_gpu(lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=mode, out=out, lse=lse), warmup, steps)
+        res[f"attn_{mode_name.lower()}_ms"] = ms
+    res["attn_ms"] = res["attn_list_ms"]
+    res["attn_tflops_visited"] = flops / (res["attn_ms"] * 1e-3) / 1e12
+    res["attn_mfma_frac"] = res["attn_tflops_visited"] / MFMA_BF16_PEAK_TFLOPS
+    dense_steps = max(3, min(steps, int(2000.0 / max(1.0, dense_flops / 1e12 / 0.1))))
+    res["dense_tile_ms"] = time_gpu(
+        lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_DENSE_BASELINE, out=out, lse=lse), 2, dense_steps)
+    res["dense_tile_tflops"] = dense_flops / (res["dense_tile_ms"] * 1e-3) / 1e12
+    res["speedup_vs_dense_tile"] = res["dense_tile_ms"] / res["attn_ms"]
+    pre_ms = time_gpu(lambda: bbm.bbm_build_block_mask(mask, Br, 64, idx=idx), warmup, steps)
+    pre_bytes = Mb * N * N * (1.0 + 1.0 / 8.0) + 2.0 * Mb * idx.nbr * idx.nbc
+    res["preprocess_ms"] = pre_ms
+    res["preprocess_gbs"] = pre_bytes / (pre_ms * 1e-3) / 1e9
+    res["preprocess_hbm_frac"] = res["preprocess_gbs"] / HBM_PEAK_GBS
+    res["index_ms"] = time_gpu(lambda: (bbm.bbm_build_runs(idx), bbm.bbm_build_sparse_index(idx)), warmup, steps)
+    # algorithmic HBM bytes of the attention kernel: Q, K, V read once, O written once, lse, packed words of partial tiles
+    res["attn_algo_bytes"] = 4.0 * B * H * N * d * 2 + 4.0 * B * H * N + census["partial"] * (B // Mb) * Br * 8.0
+    del mask, q, k, v, idx, out, lse
+    torch.cuda.empty_cache()
+    return res, cfg
+
+
+def cpu_baseline(cfg, Br, budget_s=20.0):
+    """The fp64 oracle, as it stands, on a bounded sample of the headline workload: (batch 0, first heads)."""
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    N, d, H = cfg["N"], cfg["d"], cfg["H"]
+    q, k, v, mask = cfg["q"][:1], cfg["k"][:1], cfg["v"][:1], cfg["mask"][:1]
+    t0 = time.perf_counter()
+    idx = oracle.block_index(mask, Br, 64)
+    t_idx = time.perf_counter() - t0
+    tiles_per_head = int(idx["nz_cnt"].sum())
+    heads, t_attn = 0, 0.0
+    while heads < H and t_attn < budget_s:
+        t0 = time.perf_counter()
+        oracle.masked_attention(q[:, heads:heads + 1], k[:, heads:heads + 1], v[:, heads:heads + 1], mask)
+        t_attn += time.perf_counter() - t0
+        heads += 1
+    flops = 4.0 * Br * 64 * d * tiles_per_head * heads
+    return dict(value=flops / (t_idx + t_attn) / 1e12, unit="TFLOP/s (visited tiles)", cores=int(threads), kind="oracle",
+                sample=f"batch entry 0, {heads} of {H} heads of {cfg['name']} (N={N}, d={d}): block index once "
+                       f"({t_idx:.2f} s) + dense fp64 masked attention ({t_attn:.2f} s)",
+                seconds=t_idx + t_attn, host_cpus=os.cpu_count())
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (no sharding, no collectives); got --gpus {a.gpus}",
+              file=sys.stderr)
+        return 2
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    import paper_2409_15097_amd as bbm
+
+    if a.only_kernel:                      # helper for rocprofv3 runs: a plain loop of one kernel
+        from workloads import make_config
+            cfg = make_config(a.workload)
+        mask = torch.from_numpy(cfg["mask"]).cuda()
+        idx = bbm.build_index(mask, a.Br, 64)
+        q, k, v = (bbm.bf16_from_bits(cfg[x]) for x in "qkv")
+        for _ in range(a.warmup + a.steps):
+            if a.only_kernel == "attn":
+                bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO)
+            else:
+                bbm.bbm_build_block_mask(mask, a.Br, 64, idx=idx)
+        torch.cuda.synchronize()
+        return 0
+
+    main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch)
+    rows = [main_res]
+    for name in [m for m in a.masks.split(",") if m and m != a.workload]:
+        r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch)
+        rows.append(r)
+
+    flops = main_res["visited_tflop"] * 1e12
+    step_ms = main_res["step_ms"]
+    out = {
+        "metric": "masked attn fwd ms + TFLOP/s on visited tiles vs dense-tile kernel, per mask",
+        "value": flops / (step_ms * 1e-3) / 1e12,
+        "unit": "TFLOP/s (visited tiles, whole step: preprocess + index + attention)",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": step_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: packed-sequence mask B=4 H=16 N=4096 d=64 Mb=4" if a.workload == "C2" else a.workload,
+                   "Br": a.Br, "Bc": 64, "mode": "AUTO(LIST)"},
+        "attn_ms": main_res["attn_ms"], "attn_tflops_visited": main_res["attn_tflops_visited"],
+        "dense_tile_ms": main_res["dense_tile_ms"], "dense_tile_tflops": main_res["dense_tile_tflops"],
+        "preprocess_ms": main_res["preprocess_ms"], "preprocess_gbs": main_res["preprocess_gbs"],
+        "roofline": {"bound": "mfma", "kernel": "attn_fwd_kernel", "achieved": main_res["attn_tflops_visited"],
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": main_res["attn_tflops_visited"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "algo_bytes": main_res["attn_algo_bytes"],
+                     "hbm_frac_of_algo_bytes": main_res["attn_algo_bytes"] / (main_res["attn_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "per_mask": rows,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(main_cfg, a.Br)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

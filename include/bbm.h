@@ -1,0 +1,162 @@
+/*
+ * bbm.h -- C ABI of libbbm: Binary Block Masking flash-attention forward for AMD MI355X (gfx950).
+ *
+ * The library implements the two stages of the paper "Efficiently Dispatching Flash Attention For Partially
+ * Filled Attention Masks" (Sec. 4, Method): (1) reduce an N x N binary attention mask to a block matrix at
+ * the attention kernel's Br x Bc tile size, plus the run index of the "Dense" variant and a compact per-row
+ * list of non-zero blocks; (2) a fused attention forward that visits only non-zero key/value tiles and
+ * applies the element mask only on partially filled tiles.
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller (the only host pointer is the `bbm_index*`
+ *     struct itself).  The library never allocates, frees or retains caller memory and never synchronises:
+ *     all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Return value: BBM_OK (0) or a negative error code; bbm_last_error() gives a thread-local message.
+ *     Arguments are validated on the host BEFORE any GPU call, so invalid arguments never reach a kernel.
+ *     On error the outputs are unspecified.
+ *   - Mb is the number of mask planes: 1 (one mask shared by the whole batch) or B (one per batch entry).
+ *     A mask is always shared by all heads (paper Sec. 1, insight (2); Sec. 4).
+ *   - nbr = ceil(N / Br), nbc = ceil(N / Bc).  The mask is treated as zero-padded to nbr*Br x nbc*Bc (the
+ *     paper assumes N divisible by the block size); a block that contains padding is never "full".
+ */
+#ifndef BBM_H
+#define BBM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BBM_OK 0
+#define BBM_EINVAL (-1)       /* NULL / misaligned pointer, non-positive size, inconsistent arguments */
+#define BBM_EUNSUPPORTED (-2) /* no kernel instance for this (d, Br, Bc) or block size               */
+#define BBM_EWORKSPACE (-3)   /* workspace smaller than bbm_attn_fwd_workspace_bytes()               */
+#define BBM_EHIP (-4)         /* the HIP runtime reported a launch failure                            */
+
+/* Block classes written by bbm_build_block_mask (paper Appendix A: the block sum decides both outputs). */
+#define BBM_BLOCK_EMPTY 0   /* every element of the block is zero        */
+#define BBM_BLOCK_PARTIAL 1 /* some, not all, elements are non-zero      */
+#define BBM_BLOCK_FULL 2    /* all Br*Bc elements are non-zero           */
+
+/* Tile schedules of bbm_attn_fwd. */
+#define BBM_MODE_BITMAP 0         /* paper Sec. 4 "Binary Block Masking": visit block (i,j) iff BinBlkMat[i][j]; element
+                                     mask applied on every visited block                                               */
+#define BBM_MODE_RUNS 1           /* paper Sec. 4 "Dense Binary Block Masking": scan [nz_lo, nz_hi), visit iff BinBlkMat,
+                                     skip the element mask inside [offset, offset + total_ones)                        */
+#define BBM_MODE_LIST 2           /* walk the compact per-row list of non-zero blocks; element mask skipped on blocks
+                                     flagged full                                                                      */
+#define BBM_MODE_DENSE_BASELINE 3 /* paper Sec. 3 "naive masking": visit every block, apply the element mask everywhere */
+#define BBM_MODE_AUTO 4           /* LIST if the index carries a list, else RUNS, else BITMAP                          */
+
+/* Device pointers produced by the build functions, gathered for bbm_attn_fwd.  The struct lives in host
+ * memory; unused members may be NULL (which ones are needed depends on `mode`, see bbm_attn_fwd). */
+typedef struct bbm_index {
+  int32_t Br, Bc;             /* tile size the index was built for                                   */
+  int64_t Mb, nbr, nbc;       /* planes, block rows, block columns                                   */
+  const uint8_t* blk_class;   /* [Mb, nbr, nbc] BBM_BLOCK_*                                          */
+  const uint8_t* bin_blk_mat; /* [Mb, nbr, nbc] 0/1, the paper's BinBlkMat                           */
+  const int32_t* offset;      /* [Mb, nbr] first block of the longest run of full blocks             */
+  const int32_t* total_ones;  /* [Mb, nbr] length of that run                                        */
+  const int32_t* nz_lo;       /* [Mb, nbr] first non-zero block                                      */
+  const int32_t* nz_hi;       /* [Mb, nbr] one past the last non-zero block                          */
+  const int32_t* nz_cnt;      /* [Mb, nbr] number of non-zero blocks                                 */
+  const int32_t* row_ptr;     /* [Mb, nbr + 1] list offsets within a plane, row_ptr[m][0] = 0        */
+  const uint32_t* col_idx;    /* [Mb * nbr * nbc]; plane m starts at m*nbr*nbc; bit 31 = block full  */
+} bbm_index;
+
+/* Thread-local description of the last error returned on this thread ("" if none). */
+const char* bbm_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int bbm_version(void);
+
+/*
+ * Stage 1a -- block reduction (paper Sec. 4 "Binary Block Masking": entry (i,j) of BinBlkMat is 1 iff any
+ * element of mask block (i,j) is non-zero; Appendix A, block-based summation kernel).
+ *
+ *   mask             device, uint8 [Mb][N][row_stride_bytes]; element (m, r, c) at
+ *                    mask + (m*N + r)*row_stride_bytes + c; any non-zero byte means "query r may attend key c".
+ *                    row_stride_bytes >= N.  The fast path needs mask and row_stride_bytes 16-byte aligned;
+ *                    other alignments take a slower byte-wise path with identical results.
+ *   Br, Bc           block size; 1 <= Br <= 256; Bc in {16, 32, 64, 128, 256}.
+ *   blk_class        device out, uint8 [Mb][nbr][nbc], BBM_BLOCK_* (required).
+ *   bin_blk_mat      device out, uint8 [Mb][nbr][nbc], 0/1; may be NULL.
+ *   packed_mask      device out, uint64 [Mb][W][N] with W = ceil(N/64), word-column major: bit t of word
+ *                    (m, w, r) is (mask[m][r][64*w + t] != 0), bits for columns >= N are zero; may be NULL.
+ *                    Must be 8-byte aligned.  This is the form in which bbm_attn_fwd reads the element mask.
+ * Errors: BBM_EINVAL (NULL mask/blk_class, Mb/N < 1, stride < N, misaligned packed_mask),
+ *         BBM_EUNSUPPORTED (block size outside the ranges above), BBM_EHIP.
+ */
+int bbm_build_block_mask(const uint8_t* mask, int64_t Mb, int64_t N, int64_t row_stride_bytes, int Br, int Bc,
+                         uint8_t* blk_class, uint8_t* bin_blk_mat, uint64_t* packed_mask, void* stream);
+
+/*
+ * Stage 1b -- contiguous-run index (paper Sec. 4 "Dense Binary Block Masking": per block row, total_ones =
+ * number of consecutive blocks filled with ones, offset = position of the first such block).
+ * Reading fixed here: "filled with ones" = BBM_BLOCK_FULL; if a row has several runs the longest is kept,
+ * the leftmost on ties; no full block gives (offset, total_ones) = (0, 0).  In addition the span of
+ * non-zero blocks is reported: nz_lo = first non-zero block, nz_hi = one past the last, nz_cnt = how many
+ * ((0,0,0) for an empty row); the row's non-zero blocks are contiguous iff nz_cnt == nz_hi - nz_lo.
+ *
+ *   blk_class        device in, uint8 [Mb][nbr][nbc] from bbm_build_block_mask.
+ *   offset, total_ones, nz_lo, nz_hi, nz_cnt   device out, int32 [Mb][nbr] each (all required).
+ * Errors: BBM_EINVAL (NULL pointer, non-positive size), BBM_EHIP.
+ */
+int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset,
+                   int32_t* total_ones, int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt, void* stream);
+
+/*
+ * Stage 1c -- compact per-row list of non-zero blocks, for very sparse masks (the abstract's second
+ * refinement; the list layout is this library's: CSR over block rows).
+ *
+ *   blk_class        device in, uint8 [Mb][nbr][nbc].
+ *   row_ptr          device out, int32 [Mb][nbr + 1]; row_ptr[m][0] = 0, row_ptr[m][i+1] - row_ptr[m][i] =
+ *                    number of non-zero blocks of block row i.
+ *   col_idx          device out, uint32, capacity Mb*nbr*nbc entries; the list of plane m starts at entry
+ *                    m*nbr*nbc; block columns ascending within a row; bit 31 set iff the block is full.
+ *                    Entries past row_ptr[m][nbr] are left untouched.
+ * Requires nbr*nbc < 2^31.  Errors: BBM_EINVAL, BBM_EHIP.
+ */
+int bbm_build_sparse_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* row_ptr,
+                           uint32_t* col_idx, void* stream);
+
+/*
+ * Bytes of device workspace bbm_attn_fwd needs for this problem (0 if none).  Negative sizes return 0.
+ */
+size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int Br, int Bc, int mode);
+
+/*
+ * Stage 2 -- fused masked attention forward (paper Sec. 3 "Standard Attention"/"Flash Attention", Sec. 4):
+ * for every batch b, head h and query i with allowed key set A_i = { j : mask[m(b)][i][j] != 0 },
+ *     O[b,h,i,:] = sum_{j in A_i} softmax_{j in A_i}(softmax_scale * <q_i, k_j>) * v_j
+ *     lse[b,h,i] = log sum_{j in A_i} exp(softmax_scale * <q_i, k_j>)
+ * computed tile by tile with an online softmax; only blocks the index marks non-zero are visited and the
+ * element mask is applied only where the schedule says a block may be partial.  A query with A_i empty
+ * gets O = 0 and lse = -inf.  m(b) = b if Mb == B, else 0.
+ *
+ *   q, k, v          device in, bf16 [B][H][N][d] contiguous, 16-byte aligned.
+ *   o                device out, bf16 [B][H][N][d] contiguous (round-to-nearest-even), 16-byte aligned.
+ *   lse              device out, fp32 [B][H][N] natural-log-sum-exp; may be NULL.
+ *   d                head dimension: 64 or 128.
+ *   softmax_scale    finite and > 0 (1/sqrt(d) is the usual choice; the paper does not name one).
+ *   packed_mask      device in, uint64 [Mb][ceil(N/64)][N] from bbm_build_block_mask.
+ *   idx              host pointer; idx->Bc must be 64 and idx->Br one of 64, 128, 256; idx->Mb == Mb;
+ *                    idx->nbr/nbc must equal ceil(N/Br), ceil(N/Bc).  Members needed per mode:
+ *                    BITMAP: bin_blk_mat;  RUNS: bin_blk_mat, offset, total_ones, nz_lo, nz_hi;
+ *                    LIST: row_ptr, col_idx;  DENSE_BASELINE: none.
+ *   mode             BBM_MODE_*.
+ *   workspace        device scratch of at least bbm_attn_fwd_workspace_bytes(...) bytes (may be NULL if 0).
+ * Arithmetic: QK^T and PV on bf16 MFMA with fp32 accumulation; softmax statistics in fp32; P rounded to
+ * bf16 before PV.  Deterministic: the same inputs give bit-identical outputs.
+ * Errors: BBM_EINVAL, BBM_EUNSUPPORTED (d / Br / Bc without a kernel instance), BBM_EWORKSPACE, BBM_EHIP.
+ */
+int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t N,
+                 int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask, const bbm_index* idx, int mode,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BBM_H */

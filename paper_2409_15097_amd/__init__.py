@@ -1,0 +1,13 @@
+"""Binary Block Masking flash-attention forward for AMD MI355X: thin Python binding over libbbm.so.
+
+The functions below carry the names of the C ABI (include/bbm.h) and only marshal arguments: device memory
+and the stream come from PyTorch, every computation runs in the library's HIP kernels.  There is no CPU
+fallback: if the library is not built, importing the binding raises.
+"""
+from .binding import (  # noqa: F401
+    BBM_MODE_BITMAP, BBM_MODE_RUNS, BBM_MODE_LIST, BBM_MODE_DENSE_BASELINE, BBM_MODE_AUTO,
+    BBM_OK, BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EWORKSPACE, BBM_EHIP,
+    BbmError, BlockIndex, lib, library_path,
+    bbm_last_error, bbm_version, bbm_build_block_mask, bbm_build_runs, bbm_build_sparse_index,
+    bbm_attn_fwd_workspace_bytes, bbm_attn_fwd, build_index, bf16_from_bits,
+)

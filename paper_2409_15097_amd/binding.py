@@ -1,0 +1,193 @@
+"""ctypes binding of libbbm.so.  Argument marshalling only; see include/bbm.h for the contract."""
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+BBM_OK, BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EWORKSPACE, BBM_EHIP = 0, -1, -2, -3, -4
+BBM_MODE_BITMAP, BBM_MODE_RUNS, BBM_MODE_LIST, BBM_MODE_DENSE_BASELINE, BBM_MODE_AUTO = 0, 1, 2, 3, 4
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbbm.so")
+
+
+class BbmError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libbbm error {code}: {msg}")
+        self.code = code
+
+
+class _CIndex(C.Structure):
+    _fields_ = [("Br", C.c_int32), ("Bc", C.c_int32), ("Mb", C.c_int64), ("nbr", C.c_int64), ("nbc", C.c_int64),
+                ("blk_class", C.c_void_p), ("bin_blk_mat", C.c_void_p), ("offset", C.c_void_p),
+                ("total_ones", C.c_void_p), ("nz_lo", C.c_void_p), ("nz_hi", C.c_void_p), ("nz_cnt", C.c_void_p),
+                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it first (python -m paper_2409_15097_amd.build); "
+                          "there is no fallback path")
+    L = C.CDLL(_LIB_PATH)
+    i64, vp, ci = C.c_int64, C.c_void_p, C.c_int
+    L.bbm_last_error.restype = C.c_char_p
+    L.bbm_last_error.argtypes = []
+    L.bbm_version.restype = ci
+    L.bbm_version.argtypes = []
+    L.bbm_build_block_mask.restype = ci
+    L.bbm_build_block_mask.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp, vp]
+    L.bbm_build_runs.restype = ci
+    L.bbm_build_runs.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
+    L.bbm_build_sparse_index.restype = ci
+    L.bbm_build_sparse_index.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    L.bbm_attn_fwd_workspace_bytes.restype = C.c_size_t
+    L.bbm_attn_fwd_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ci]
+    L.bbm_attn_fwd.restype = ci
+    L.bbm_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, C.c_float, i64, vp, C.POINTER(_CIndex), ci,
+                               vp, C.c_size_t, vp]
+    return L
+
+
+lib = _load()
+
+
+def bbm_last_error() -> str:
+    return lib.bbm_last_error().decode()
+
+
+def bbm_version() -> int:
+    return lib.bbm_version()
+
+
+def _check(rc: int):
+    if rc != BBM_OK:
+        raise BbmError(rc, bbm_last_error())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _cdiv(a, b):
+    return -(-a // b)
+
+
+@dataclass
+class BlockIndex:
+    """Device tensors of one preprocessed mask (all optional except the tile size and extents)."""
+    Br: int
+    Bc: int
+    Mb: int
+    nbr: int
+    nbc: int
+    N: int
+    blk_class: Optional[torch.Tensor] = None
+    bin_blk_mat: Optional[torch.Tensor] = None
+    packed_mask: Optional[torch.Tensor] = None
+    offset: Optional[torch.Tensor] = None
+    total_ones: Optional[torch.Tensor] = None
+    nz_lo: Optional[torch.Tensor] = None
+    nz_hi: Optional[torch.Tensor] = None
+    nz_cnt: Optional[torch.Tensor] = None
+    row_ptr: Optional[torch.Tensor] = None
+    col_idx: Optional[torch.Tensor] = None
+
+    def c_struct(self) -> _CIndex:
+        g = lambda t: None if t is None else t.data_ptr()
+        return _CIndex(self.Br, self.Bc, self.Mb, self.nbr, self.nbc, g(self.blk_class), g(self.bin_blk_mat),
+                       g(self.offset), g(self.total_ones), g(self.nz_lo), g(self.nz_hi), g(self.nz_cnt),
+                       g(self.row_ptr), g(self.col_idx))
+
+
+def bbm_build_block_mask(mask: torch.Tensor, Br: int, Bc: int, idx: Optional[BlockIndex] = None,
+                         want_bin: bool = True, want_packed: bool = True, stream=None) -> BlockIndex:
+    """mask: uint8 CUDA tensor [Mb,N,N] (row stride may exceed N).  Writes class / BinBlkMat / packed bits into
+    idx's tensors (allocated here when idx is None) and returns idx."""
+    assert mask.is_cuda and mask.dtype == torch.uint8 and mask.dim() == 3 and mask.stride(2) == 1
+    Mb, N, _ = mask.shape
+    assert mask.shape[2] == N and (Mb == 1 or mask.stride(0) == N * mask.stride(1))
+    nbr, nbc = _cdiv(N, Br), _cdiv(N, Bc)
+    if idx is None:
+        dev = mask.device
+        idx = BlockIndex(Br, Bc, Mb, nbr, nbc, N)
+        idx.blk_class = torch.empty((Mb, nbr, nbc), dtype=torch.uint8, device=dev)
+        if want_bin:
+            idx.bin_blk_mat = torch.empty((Mb, nbr, nbc), dtype=torch.uint8, device=dev)
+        if want_packed:
+            idx.packed_mask = torch.empty((Mb, _cdiv(N, 64), N), dtype=torch.int64, device=dev)
+    _check(lib.bbm_build_block_mask(_ptr(mask), Mb, N, mask.stride(1), Br, Bc, _ptr(idx.blk_class),
+                                    _ptr(idx.bin_blk_mat), _ptr(idx.packed_mask), _stream(stream)))
+    return idx
+
+
+def bbm_build_runs(idx: BlockIndex, stream=None) -> BlockIndex:
+    dev = idx.blk_class.device
+    for name in ("offset", "total_ones", "nz_lo", "nz_hi", "nz_cnt"):
+        if getattr(idx, name) is None:
+            setattr(idx, name, torch.empty((idx.Mb, idx.nbr), dtype=torch.int32, device=dev))
+    _check(lib.bbm_build_runs(_ptr(idx.blk_class), idx.Mb, idx.nbr, idx.nbc, _ptr(idx.offset), _ptr(idx.total_ones),
+                              _ptr(idx.nz_lo), _ptr(idx.nz_hi), _ptr(idx.nz_cnt), _stream(stream)))
+    return idx
+
+
+def bbm_build_sparse_index(idx: BlockIndex, stream=None) -> BlockIndex:
+    dev = idx.blk_class.device
+    if idx.row_ptr is None:
+        idx.row_ptr = torch.empty((idx.Mb, idx.nbr + 1), dtype=torch.int32, device=dev)
+    if idx.col_idx is None:
+        idx.col_idx = torch.zeros(idx.Mb * idx.nbr * idx.nbc, dtype=torch.int32, device=dev)
+    _check(lib.bbm_build_sparse_index(_ptr(idx.blk_class), idx.Mb, idx.nbr, idx.nbc, _ptr(idx.row_ptr),
+                                      _ptr(idx.col_idx), _stream(stream)))
+    return idx
+
+
+def build_index(mask: torch.Tensor, Br: int, Bc: int = 64, idx: Optional[BlockIndex] = None, stream=None) -> BlockIndex:
+    """The whole preprocessing stage: the three build calls in order."""
+    idx = bbm_build_block_mask(mask, Br, Bc, idx=idx, stream=stream)
+    bbm_build_runs(idx, stream=stream)
+    bbm_build_sparse_index(idx, stream=stream)
+    return idx
+
+
+def bf16_from_bits(bits) -> torch.Tensor:
+    """numpy uint16 array of bf16 bit patterns -> bf16 CUDA tensor with the identical bits."""
+    import numpy as np
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bbm_attn_fwd_workspace_bytes(B, H, N, d, Br, Bc, mode) -> int:
+    return int(lib.bbm_attn_fwd_workspace_bytes(B, H, N, d, Br, Bc, mode))
+
+
+def bbm_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIndex, mode: int = BBM_MODE_AUTO,
+                 softmax_scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
+                 lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """q, k, v: bf16 CUDA tensors [B,H,N,d], contiguous.  Returns (O bf16 [B,H,N,d], lse fp32 [B,H,N])."""
+    assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    assert k.shape == q.shape and v.shape == q.shape and k.dtype == q.dtype and v.dtype == q.dtype
+    B, H, N, d = q.shape
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx.Br, idx.Bc, mode)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    cs = idx.c_struct()
+    _check(lib.bbm_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, N, d, softmax_scale, idx.Mb,
+                            _ptr(idx.packed_mask), C.byref(cs), mode, _ptr(workspace),
+                            0 if workspace is None else workspace.numel(), _stream(stream)))
+    return out, lse

@@ -1,0 +1,18 @@
+// Error reporting and version of libbbm.
+#include "bbm_internal.h"
+
+namespace bbm {
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+void clear_error() { g_err[0] = '\0'; }
+}  // namespace bbm
+
+extern "C" __attribute__((visibility("default"))) const char* bbm_last_error(void) { return bbm::g_err; }
+extern "C" __attribute__((visibility("default"))) int bbm_version(void) { return 100; }

@@ -1,0 +1,64 @@
+"""Helpers for the GPU parity tests: move seeded numpy inputs to the device and bring results back."""
+import numpy as np
+import torch
+
+import oracle
+
+
+def bf16_tensor(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> bf16 CUDA tensor holding the identical bits."""
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bf16_result_to_f64(t: torch.Tensor) -> np.ndarray:
+    bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return oracle.bf16_bits_to_f64(bits)
+
+
+def index_to_numpy(idx):
+    out = {}
+    for name in ("blk_class", "bin_blk_mat", "offset", "total_ones", "nz_lo", "nz_hi", "nz_cnt", "row_ptr"):
+        t = getattr(idx, name)
+        out[name] = None if t is None else t.cpu().numpy()
+    out["col_idx"] = None if idx.col_idx is None else idx.col_idx.cpu().numpy().view(np.uint32)
+    out["packed_mask"] = None if idx.packed_mask is None else idx.packed_mask.cpu().numpy().view(np.uint64)
+    return out
+
+
+def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
+    """Bit-exact comparison of everything the preprocessing stage wrote against the oracle."""
+    want = oracle.block_index(mask, Br, Bc)
+    assert np.array_equal(got["blk_class"], want["cls"])
+    if got["bin_blk_mat"] is not None:
+        assert np.array_equal(got["bin_blk_mat"], want["bin_blk_mat"])
+    for name in ("offset", "total_ones", "nz_lo", "nz_hi", "nz_cnt"):
+        if got[name] is not None:
+            assert np.array_equal(got[name], want[name]), name
+    if got["row_ptr"] is not None:
+        assert np.array_equal(got["row_ptr"], want["row_ptr"])
+        Mb, nbr, nbc = want["cls"].shape
+        for m in range(Mb):
+            n = int(want["row_ptr"][m, -1])
+            lo = m * nbr * nbc
+            assert np.array_equal(got["col_idx"][lo:lo + n], want["col_idx"][lo:lo + n])
+    if got["packed_mask"] is not None:
+        assert np.array_equal(got["packed_mask"], oracle.packed_bits(mask))
+
+
+# Tolerances for bf16 inputs/outputs against the fp64 oracle (max-abs, mean-abs on O; max-abs on finite lse).
+O_MAX_ABS, O_MEAN_ABS, LSE_MAX_ABS = 2e-2, 2e-3, 5e-3
+
+
+def assert_attention_close(o_gpu: torch.Tensor, lse_gpu: torch.Tensor, O_ref: np.ndarray, lse_ref: np.ndarray):
+    o = bf16_result_to_f64(o_gpu)
+    l = lse_gpu.cpu().numpy().astype(np.float64)
+    assert not np.isnan(o).any() and not np.isnan(l).any()
+    err = np.abs(o - O_ref)
+    assert err.max() <= O_MAX_ABS, f"max-abs {err.max()}"
+    assert err.mean() <= O_MEAN_ABS, f"mean-abs {err.mean()}"
+    fin = np.isfinite(lse_ref)
+    assert np.array_equal(np.isfinite(l), fin)
+    assert np.all(l[~fin] == -np.inf)
+    if fin.any():
+        assert np.abs(l[fin] - lse_ref[fin]).max() <= LSE_MAX_ABS
+    return err.max(), err.mean()

@@ -1,0 +1,101 @@
+"""CPU-only checks of the boundary: the library loads, exports every declared symbol, and rejects bad
+arguments on the host before touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def bbm():
+    import paper_2409_15097_amd as m
+    return m
+
+
+def test_every_declared_symbol_is_exported(bbm):
+    hdr = open(os.path.join(ROOT, "include", "bbm.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(bbm_[a-z_]+)\s*\(", hdr))
+    assert names == {"bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs",
+                     "bbm_build_sparse_index", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"}
+    raw = C.CDLL(bbm.library_path())
+    for n in names:
+        assert getattr(raw, n) is not None
+    assert bbm.bbm_version() >= 100
+
+
+def test_binding_has_the_same_names(bbm):
+    for n in ("bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs", "bbm_build_sparse_index",
+              "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"):
+        assert callable(getattr(bbm, n))
+
+
+FAKE = C.c_void_p(0x1000)      # never dereferenced: validation fails first
+
+
+def test_build_block_mask_rejects_bad_arguments(bbm):
+    L = bbm.lib
+    assert L.bbm_build_block_mask(None, 1, 64, 64, 64, 64, FAKE, None, None, None) == bbm.BBM_EINVAL
+    assert "NULL" in bbm.bbm_last_error()
+    assert L.bbm_build_block_mask(FAKE, 1, 64, 64, 64, 64, None, None, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_block_mask(FAKE, 0, 64, 64, 64, 64, FAKE, None, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_block_mask(FAKE, 1, 0, 64, 64, 64, FAKE, None, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_block_mask(FAKE, 1, 64, 63, 64, 64, FAKE, None, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_block_mask(FAKE, 1, 64, 64, 0, 64, FAKE, None, None, None) == bbm.BBM_EUNSUPPORTED
+    assert L.bbm_build_block_mask(FAKE, 1, 64, 64, 257, 64, FAKE, None, None, None) == bbm.BBM_EUNSUPPORTED
+    assert L.bbm_build_block_mask(FAKE, 1, 64, 64, 64, 48, FAKE, None, None, None) == bbm.BBM_EUNSUPPORTED
+    assert L.bbm_build_block_mask(FAKE, 1, 64, 64, 64, 64, FAKE, None, C.c_void_p(0x1004), None) == bbm.BBM_EINVAL
+
+
+def test_index_builders_reject_bad_arguments(bbm):
+    L = bbm.lib
+    assert L.bbm_build_runs(None, 1, 4, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_runs(FAKE, 1, 4, 4, FAKE, None, FAKE, FAKE, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_runs(FAKE, 1, 0, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_sparse_index(FAKE, 1, 4, 4, None, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_sparse_index(FAKE, 1, 4, 0, FAKE, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_sparse_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None) == bbm.BBM_EUNSUPPORTED
+
+
+def _idx(bbm, Br=128, Bc=64, Mb=1, N=256, **ptrs):
+    from paper_2409_15097_amd.binding import _CIndex
+    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), *([None] * 9))
+    for k, v in ptrs.items():
+        setattr(s, k, v)
+    return s
+
+
+def _attn(bbm, idx, q=FAKE, k=FAKE, v=FAKE, o=FAKE, B=1, H=1, N=256, d=64, scale=0.125, Mb=1, packed=FAKE, mode=None,
+          ws_bytes=0):
+    mode = bbm.BBM_MODE_DENSE_BASELINE if mode is None else mode
+    return bbm.lib.bbm_attn_fwd(q, k, v, o, None, B, H, N, d, scale, Mb, packed, C.byref(idx) if idx else None, mode,
+                                None, ws_bytes, None)
+
+
+def test_attn_fwd_rejects_bad_arguments(bbm):
+    idx = _idx(bbm)
+    assert _attn(bbm, idx, q=None) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, o=C.c_void_p(0x1008)) == bbm.BBM_EINVAL and "aligned" in bbm.bbm_last_error()
+    assert _attn(bbm, idx, B=0) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, scale=0.0) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, scale=float("nan")) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, scale=float("inf")) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, B=4, Mb=2) == bbm.BBM_EINVAL
+    assert _attn(bbm, None) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, packed=None) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, d=96) == bbm.BBM_EUNSUPPORTED
+    assert _attn(bbm, _idx(bbm, Bc=32)) == bbm.BBM_EUNSUPPORTED
+    assert _attn(bbm, _idx(bbm, Br=32)) == bbm.BBM_EUNSUPPORTED
+    assert _attn(bbm, _idx(bbm, N=512)) == bbm.BBM_EINVAL and "does not match" in bbm.bbm_last_error()
+    assert _attn(bbm, idx, mode=17) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, mode=bbm.BBM_MODE_BITMAP) == bbm.BBM_EINVAL and "bin_blk_mat" in bbm.bbm_last_error()
+    assert _attn(bbm, idx, mode=bbm.BBM_MODE_RUNS) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, mode=bbm.BBM_MODE_LIST) == bbm.BBM_EINVAL
+    assert _attn(bbm, idx, mode=bbm.BBM_MODE_AUTO) == bbm.BBM_EINVAL          # AUTO falls back to BITMAP, which needs bin_blk_mat
+
+
+def test_workspace_query(bbm):
+    assert bbm.bbm_attn_fwd_workspace_bytes(4, 16, 4096, 64, 128, 64, bbm.BBM_MODE_LIST) >= 0

@@ -1,0 +1,153 @@
+"""GPU parity: fused masked attention forward against the fp64 oracle (O within 2e-2 max-abs / 2e-3 mean-abs)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import masks, make_qkv, small_variant, make_config
+from gpu_util import bf16_tensor, bf16_result_to_f64, assert_attention_close, O_MAX_ABS, O_MEAN_ABS, LSE_MAX_ABS
+
+pytestmark = pytest.mark.gpu
+
+
+def _bbm():
+    import paper_2409_15097_amd as bbm
+    return bbm
+
+
+MODES = ["BITMAP", "RUNS", "LIST", "DENSE_BASELINE", "AUTO"]
+
+
+def _mode(bbm, name):
+    return getattr(bbm, "BBM_MODE_" + name)
+
+
+def _gpu_attn(cfg, Br, mode, scale=None):
+    bbm = _bbm()
+    mask = torch.from_numpy(cfg["mask"]).cuda()
+    idx = bbm.build_index(mask, Br, 64)
+    q, k, v = (bf16_tensor(cfg[x]) for x in "qkv")
+    o, lse = bbm.bbm_attn_fwd(q, k, v, idx, mode=_mode(bbm, mode), softmax_scale=scale)
+    torch.cuda.synchronize()
+    return o, lse
+
+
+SMALL = [("C1", 256, 1, 2), ("C2", 1024, 2, 2), ("C3", 640, 1, 2), ("C4", 2048, 1, 2), ("C5", 2048, 1, 2),
+         ("C0d", 512, 1, 2), ("C0c", 512, 1, 2)]
+
+
+@pytest.mark.parametrize("name,N,B,H", SMALL)
+@pytest.mark.parametrize("Br", [64, 128, 256])
+def test_small_variants_all_modes(name, N, B, H, Br):
+    cfg = small_variant(name, N=N, B=B, H=H)
+    O_ref, lse_ref = oracle.masked_attention(cfg["q"], cfg["k"], cfg["v"], cfg["mask"])
+    outs = {}
+    for mode in MODES:
+        print(f"case {name} N={N} Br={Br} mode={mode}", flush=True)
+        o, lse = _gpu_attn(cfg, Br, mode)
+        assert_attention_close(o, lse, O_ref, lse_ref)
+        outs[mode] = (o, lse)
+    # same tile visit order and same arithmetic in every schedule that skips only all-masked tiles
+    for mode in ("RUNS", "LIST", "AUTO"):
+        assert torch.equal(outs[mode][0].view(torch.int16), outs["BITMAP"][0].view(torch.int16)), mode
+
+
+@pytest.mark.parametrize("N", [200, 333, 77, 1, 65, 1000])
+@pytest.mark.parametrize("d", [64, 128])
+def test_ragged_sizes_with_empty_rows(N, d):
+    B, H = 2, 3
+    q, k, v = make_qkv(B, H, N, d, seed=N + d)
+    rng = np.random.default_rng(N)
+    m = masks.random_blocks(64 * (-(-N // 64)), N + 1, blk=32, p_empty=0.4, p_full=0.3)[0][:N, :N].copy()
+    m[rng.integers(0, N, size=max(1, N // 10))] = 0        # fully masked rows
+    cfg = dict(q=q, k=k, v=v, mask=np.stack([m, np.roll(m, 3, axis=1)]))
+    O_ref, lse_ref = oracle.masked_attention(q, k, v, cfg["mask"])
+    for Br in (64, 128):
+        for mode in MODES:
+            print(f"ragged N={N} d={d} Br={Br} mode={mode}", flush=True)
+            o, lse = _gpu_attn(cfg, Br, mode)
+            assert_attention_close(o, lse, O_ref, lse_ref)
+            rows = np.flatnonzero(~np.isfinite(lse_ref[0, 0]))
+            assert torch.all(o[0, :, rows] == 0)
+
+
+def test_d128_small_tree_and_custom_scale():
+    cfg = small_variant("C3", N=640, B=2, H=2)
+    for scale in (None, 0.05, 0.3):
+        O_ref, lse_ref = oracle.masked_attention(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], scale=scale)
+        for mode in MODES:
+            o, lse = _gpu_attn(cfg, 128, mode, scale=scale)
+            assert_attention_close(o, lse, O_ref, lse_ref)
+
+
+def test_key_permutation_changes_blocks_but_not_output():
+    """Permuting keys/values together with the mask columns scrambles the block matrix; O must not move."""
+    cfg = small_variant("C2", N=1024, B=1, H=2)
+    pi = np.random.default_rng(0).permutation(1024)
+    cfg2 = dict(q=cfg["q"], k=cfg["k"][:, :, pi].copy(), v=cfg["v"][:, :, pi].copy(), mask=cfg["mask"][:, :, pi].copy())
+    o1, _ = _gpu_attn(cfg, 128, "LIST")
+    o2, _ = _gpu_attn(cfg2, 128, "LIST")
+    a, b = bf16_result_to_f64(o1), bf16_result_to_f64(o2)
+    assert np.abs(a - b).max() <= O_MAX_ABS
+    O_ref, lse_ref = oracle.masked_attention(cfg["q"], cfg["k"], cfg["v"], cfg["mask"])
+    assert np.abs(b - O_ref).max() <= O_MAX_ABS and np.abs(b - O_ref).mean() <= O_MEAN_ABS
+
+
+def test_single_allowed_key_returns_value_bits_exactly():
+    B, H, N, d = 1, 2, 320, 64
+    q, k, v = make_qkv(B, H, N, d, seed=3)
+    pi = np.random.default_rng(3).permutation(N)
+    mask = np.zeros((1, N, N), dtype=np.uint8)
+    mask[0, np.arange(N), pi] = 1
+    o, lse = _gpu_attn(dict(q=q, k=k, v=v, mask=mask), 64, "LIST")
+    got = o.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, v[:, :, pi])
+    _, lse_ref = oracle.masked_attention(q, k, v, mask)
+    assert np.abs(lse.cpu().numpy() - lse_ref).max() <= LSE_MAX_ABS
+
+
+def test_deterministic():
+    cfg = small_variant("C4", N=2048, B=1, H=2)
+    o1, l1 = _gpu_attn(cfg, 128, "LIST")
+    o2, l2 = _gpu_attn(cfg, 128, "LIST")
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(l1, l2)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_sampled_rows(name):
+    """At the benchmark sizes the oracle evaluates sampled query rows one by one (same launch configuration as bench.py)."""
+    bbm = _bbm()
+    cfg = make_config(name)
+    B, H, N, d = cfg["B"], cfg["H"], cfg["N"], cfg["d"]
+    rng = np.random.default_rng(7)
+    rows = [(int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(N))) for _ in range(192)]
+    empty = np.flatnonzero(cfg["mask"][0].sum(axis=1) == 0)
+    rows += [(0, 0, int(r)) for r in empty[:4]]
+    rows += [(B - 1, H - 1, N - 1), (0, 0, 0), (B - 1, 0, N // 2)]
+    rows.sort()
+    O_ref, lse_ref = oracle.masked_attention_rows(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], rows)
+    mask = torch.from_numpy(cfg["mask"]).cuda()
+    q, k, v = (bf16_tensor(cfg[x]) for x in "qkv")
+    ref_bits = None
+    for Br, mode in ((128, "AUTO"), (128, "RUNS"), (128, "BITMAP"), (64, "LIST")):
+        print(f"full {name} Br={Br} mode={mode}", flush=True)
+        idx = bbm.build_index(mask, Br, 64)
+        o, lse = bbm.bbm_attn_fwd(q, k, v, idx, mode=_mode(bbm, mode))
+        torch.cuda.synchronize()
+        bi, hi, ri = (torch.tensor(x, device="cuda") for x in zip(*rows))
+        got = bf16_result_to_f64(o[bi, hi, ri])
+        lg = lse[bi, hi, ri].cpu().numpy().astype(np.float64)
+        err = np.abs(got - O_ref)
+        assert err.max() <= O_MAX_ABS and err.mean() <= O_MEAN_ABS
+        fin = np.isfinite(lse_ref)
+        assert np.array_equal(np.isfinite(lg), fin) and np.abs(lg[fin] - lse_ref[fin]).max() <= LSE_MAX_ABS
+        assert not torch.isnan(o.float()).any()
+        if Br == 128:
+            bits = o.view(torch.int16)
+            if ref_bits is None:
+                ref_bits = bits.clone()
+            else:
+                assert torch.equal(bits, ref_bits)
+        # properties that hold at any size: fully masked rows are exactly zero
+        if empty.size:
+            assert torch.all(o[0, :, torch.from_numpy(empty).cuda()] == 0)
