@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--masks", default="C2,C3,C4,C5,C0d,C0c,C0d128,C0c128",
                     help="comma list of extra per-mask rows (empty string = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only-kernel", default="", help="profile helper: run only 'attn' or 'preprocess' launches")
+    ap.add_argument("--only-kernel", default="", help="profile helper: run only 'attn', 'preprocess' or 'copy' (256 MiB device copy) launches")
     return ap.parse_args()
 
 
@@ -153,15 +153,24 @@ def main():
 
     if a.only_kernel:                      # helper for rocprofv3 runs: a plain loop of one kernel
         from workloads import make_config
-            cfg = make_config(a.workload)
+        cfg = make_config(a.workload)
         mask = torch.from_numpy(cfg["mask"]).cuda()
         idx = bbm.build_index(mask, a.Br, 64)
         q, k, v = (bbm.bf16_from_bits(cfg[x]) for x in "qkv")
+        out = torch.empty_like(q)
+        lse = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+        src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda").fill_(1)     # 256 MiB copy for counter calibration
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
         for _ in range(a.warmup + a.steps):
             if a.only_kernel == "attn":
-                bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO)
-            else:
+                bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse)
+            elif a.only_kernel == "preprocess":
                 bbm.bbm_build_block_mask(mask, a.Br, 64, idx=idx)
+            elif a.only_kernel == "copy":
+                dst.copy_(src)
+            else:
+                raise SystemExit(f"unknown --only-kernel {a.only_kernel}")
         torch.cuda.synchronize()
         return 0
 

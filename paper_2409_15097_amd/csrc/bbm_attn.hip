@@ -25,6 +25,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kBc = 64;
 constexpr int kPad = 8;  // bf16 elements of padding per LDS row (16 bytes)
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazy = 8.0f;  // log2 headroom before the running maximum is moved
 
 struct AttnParams {
   const __bf16* q;
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       }
     }
 
-    // ---- element mask (only where the schedule cannot rule out zeros)
+    // ---- element mask (only where the schedule cannot rule out zeros): keep s where the bit is set, else -inf
     if (need_mask) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
@@ -241,7 +242,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int bit = 8 * (e / 4) + (e % 4);
-          s[kb][e] = ((w >> bit) & 1u) ? s[kb][e] : -INFINITY;
+          const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);  // all ones iff the bit is set
+          s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
         }
       }
     }
@@ -252,10 +254,19 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     for (int kb = 0; kb < 2; ++kb)
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
     mx = partner_max(mx);
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c);
-    const float msc = m_use * c;
+    // The reference maximum m_run only moves when some row's maximum grew by more than kLazy (in log2 units):
+    // softmax is invariant to the reference, probabilities stay <= 2^kLazy, and the rescale of O is skipped.
+    if (__any((mx * c > m_run * c + kLazy) ? 1 : 0)) {
+      const float m_new = fmaxf(m_run, mx);
+      const float m_fin = (m_new == -INFINITY) ? 0.0f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_fin) * c);
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+    }
+    const float msc = ((m_run == -INFINITY) ? 0.0f : m_run) * c;
     float rs = 0.0f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -264,11 +275,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
         s[kb][e] = p;
         rs += p;
       }
-    l_run = l_run * alpha + rs;
-    m_run = m_new;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-      for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+    l_run += rs;
 
     // ---- O^T += V^T P^T
 #pragma unroll
