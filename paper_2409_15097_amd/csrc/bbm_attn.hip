@@ -19,11 +19,11 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kBc = 64;
-constexpr int kPad = 8;  // bf16 elements of padding per LDS row (16 bytes)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazy = 8.0f;  // log2 headroom before the running maximum is moved
 
@@ -48,76 +48,6 @@ struct AttnParams {
   float scale;
 };
 
-// Wave-uniform iterator over the tiles a block row visits, in ascending key order.
-struct TileIter {
-  int mode;
-  int j, j_end;          // DENSE: next block / end.  BITMAP, RUNS: scan window [chunk base .. j_end)
-  int base;              // BITMAP, RUNS: first block of the current 64-block chunk
-  uint64_t nz;           // BITMAP, RUNS: unvisited non-zero blocks of the current chunk
-  const uint8_t* row;    // BITMAP, RUNS: BinBlkMat row
-  int run_lo, run_hi;    // RUNS: [offset, offset + total_ones)
-  const uint32_t* list;  // LIST
-  int p, p_end;
-
-  __device__ __forceinline__ void load_chunk(int lane) {
-    const int jj = base + lane;
-    const uint8_t b = (jj >= j && jj < j_end) ? row[jj] : (uint8_t)0;
-    nz = __ballot(b != 0);
-  }
-
-  __device__ __forceinline__ void init(const AttnParams& P, int m, int i, int lane) {
-    mode = P.mode;
-    const int64_t r = (int64_t)m * P.nbr + i;
-    if (mode == BBM_MODE_DENSE_BASELINE) {
-      j = 0;
-      j_end = P.nbc;
-    } else if (mode == BBM_MODE_LIST) {
-      const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
-      p = __builtin_amdgcn_readfirstlane(rp[0]);
-      p_end = __builtin_amdgcn_readfirstlane(rp[1]);
-      list = P.col_idx + (int64_t)m * P.nbr * P.nbc;
-    } else {
-      row = P.bin_blk_mat + r * P.nbc;
-      j = 0;
-      j_end = P.nbc;
-      run_lo = run_hi = 0;
-      if (mode == BBM_MODE_RUNS) {
-        j = __builtin_amdgcn_readfirstlane(P.nz_lo[r]);
-        j_end = __builtin_amdgcn_readfirstlane(P.nz_hi[r]);
-        run_lo = __builtin_amdgcn_readfirstlane(P.offset[r]);
-        run_hi = run_lo + __builtin_amdgcn_readfirstlane(P.total_ones[r]);
-      }
-      base = j & ~63;
-      nz = 0;
-      if (j < j_end) load_chunk(lane);
-    }
-  }
-
-  // Returns the next visited block column (or -1) and whether the element mask must be applied there.
-  __device__ __forceinline__ int next(int lane, bool& need_mask) {
-    need_mask = true;
-    if (mode == BBM_MODE_DENSE_BASELINE) {
-      return j < j_end ? j++ : -1;
-    }
-    if (mode == BBM_MODE_LIST) {
-      if (p >= p_end) return -1;
-      const uint32_t e = __builtin_amdgcn_readfirstlane(list[p]);
-      ++p;
-      need_mask = (e >> 31) == 0;
-      return (int)(e & 0x7fffffffu);
-    }
-    while (nz == 0) {
-      base += 64;
-      if (base >= j_end) return -1;
-      load_chunk(lane);
-    }
-    const int jj = base + __builtin_ctzll(nz);
-    nz &= nz - 1;
-    if (mode == BBM_MODE_RUNS) need_mask = !(jj >= run_lo && jj < run_hi);
-    return jj;
-  }
-};
-
 __device__ __forceinline__ float partner_max(float x) {
   // lanes l and l^32 exchange: swap(x, x) gives {x[l%32], x[l%32 + 32]} in some order on every lane
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -128,19 +58,114 @@ __device__ __forceinline__ float partner_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int D, int NW>
+constexpr int kWin = 1024;               // tiles per schedule window (block columns, or list entries)
+constexpr uint32_t kNoTile = 0xffffffffu;  // sentinel after the last entry of a window
+
+// Builds, in LDS, the ascending list of tiles one block row visits inside one schedule window; entry =
+// block column | (1 << 31 if the element mask can be skipped there).  Returns the number of entries (uniform).
+// `win` counts windows of kWin block columns (BITMAP, RUNS, DENSE_BASELINE) or of kWin list entries (LIST).
+template <int NW>
+__device__ __forceinline__ int build_window(const AttnParams& P, int m, int i, int win, uint32_t* tiles_s, int* cnt_s) {
+  constexpr int NT = NW * 64;
+  constexpr int CH = kWin / 64;  // 64-column chunks per window
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t r = (int64_t)m * P.nbr + i;
+  int count;
+  if (P.mode == BBM_MODE_LIST) {
+    const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
+    const int p0 = rp[0] + win * kWin;
+    count = min(kWin, rp[1] - p0);
+    const uint32_t* list = P.col_idx + (int64_t)m * P.nbr * P.nbc + p0;
+    for (int t = tid; t < count; t += NT) tiles_s[t] = list[t];
+  } else if (P.mode == BBM_MODE_DENSE_BASELINE) {
+    const int j0 = win * kWin;
+    count = min(kWin, P.nbc - j0);
+    for (int t = tid; t < count; t += NT) tiles_s[t] = (uint32_t)(j0 + t);
+  } else {
+    int lo = 0, hi = P.nbc, run_lo = 0, run_hi = 0;
+    if (P.mode == BBM_MODE_RUNS) {
+      lo = P.nz_lo[r];
+      hi = P.nz_hi[r];
+      run_lo = P.offset[r];
+      run_hi = run_lo + P.total_ones[r];
+    }
+    const int j0 = (lo & ~63) + win * kWin;
+    const uint8_t* row = P.bin_blk_mat + r * P.nbc;
+    uint64_t nz[(CH + NW - 1) / NW];
+#pragma unroll
+    for (int n = 0; n < (CH + NW - 1) / NW; ++n) {
+      const int ch = wave + n * NW;
+      const int j = j0 + 64 * ch + lane;
+      const uint8_t v = (ch < CH && j >= lo && j < hi) ? row[j] : (uint8_t)0;
+      nz[n] = __ballot(v != 0);
+      if (ch < CH && lane == 0) cnt_s[ch] = __popcll(nz[n]);
+    }
+    __syncthreads();
+    int total = 0, before = 0;
+    for (int ch = 0; ch < CH; ++ch) {
+      const int cn = cnt_s[ch];
+      total += cn;
+    }
+    count = total;
+#pragma unroll
+    for (int n = 0; n < (CH + NW - 1) / NW; ++n) {
+      const int ch = wave + n * NW;
+      if (ch < CH) {
+        before = 0;
+        for (int c2 = 0; c2 < ch; ++c2) before += cnt_s[c2];
+        if ((nz[n] >> lane) & 1ull) {
+          const int j = j0 + 64 * ch + lane;
+          const bool in_run = (P.mode == BBM_MODE_RUNS) && j >= run_lo && j < run_hi;
+          tiles_s[before + __popcll(nz[n] & ((1ull << lane) - 1ull))] = (uint32_t)j | (in_run ? 0x80000000u : 0u);
+        }
+      }
+    }
+  }
+  count = __builtin_amdgcn_readfirstlane(count);
+  if (tid < 3) tiles_s[count + tid] = kNoTile;
+  __syncthreads();
+  return count;
+}
+
+// Number of schedule windows of one block row (uniform).
+__device__ __forceinline__ int num_windows(const AttnParams& P, int m, int i) {
+  if (P.mode == BBM_MODE_LIST) {
+    const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
+    return (rp[1] - rp[0] + kWin - 1) / kWin;
+  }
+  if (P.mode == BBM_MODE_RUNS) {
+    const int64_t r = (int64_t)m * P.nbr + i;
+    const int lo = P.nz_lo[r] & ~63, hi = P.nz_hi[r];
+    return (hi - lo + kWin - 1) / kWin;
+  }
+  return (P.nbc + kWin - 1) / kWin;
+}
+
+template <int V>
+struct IntC {
+  static constexpr int value = V;
+};
+
+// PIPE = true: software-pipelined -- the scores of tile t+1 (matrix pipe) are issued next to the exponentials of
+// tile t (vector pipe) inside one wave; costs a second set of score registers.  PIPE = false: each iteration
+// computes and consumes its own scores and relies on the other waves of the SIMD for overlap.
+template <int D, int NW, bool PIPE>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NT = NW * 64;
   constexpr int BR = NW * 32;
-  constexpr int LD = D + kPad;                 // LDS row stride in elements
-  constexpr int CHUNKS = kBc * D / 8;          // 16-byte chunks per K (or V) tile
-  constexpr int CPT = CHUNKS / NT;             // chunks per thread
+  constexpr int LD = D;                        // LDS row stride in elements (rows are not padded, chunks are swizzled)
+  constexpr int RC = D / 8;                    // 16-byte chunks per row
+  constexpr int CHUNKS = kBc * RC;             // 16-byte chunks per K (or V) tile
+  constexpr int LPW = CHUNKS / NT;             // direct-to-LDS load instructions per wave and tile
   static_assert(CHUNKS % NT == 0, "tile must split evenly over the work-group");
   constexpr int KS = D / 16;                   // MFMA k-steps of the first product
   constexpr int DB = D / 32;                   // 32-wide output-column blocks of the second product
+  constexpr int TILE = kBc * LD;               // elements per LDS tile buffer
 
-  __shared__ __attribute__((aligned(16))) __bf16 k_s[2][kBc * LD];
-  __shared__ __attribute__((aligned(16))) __bf16 v_s[2][kBc * LD];
+  __shared__ __attribute__((aligned(16))) __bf16 k_s[2 * TILE];
+  __shared__ __attribute__((aligned(16))) __bf16 v_s[2 * TILE];
+  __shared__ uint32_t tiles_s[kWin + 4];
+  __shared__ int cnt_s[kWin / 64];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31, hh = lane >> 5;
@@ -162,6 +187,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   const __bf16* __restrict__ Vg = P.v + head_off;
   const int64_t qrow = (int64_t)i * BR + wave * 32 + lq;
   const bool q_ok = qrow < N;
+  // packed mask words of this lane's query row (rows past N borrow row 0: their results are never stored)
+  const uint64_t* __restrict__ mrow = P.packed + (int64_t)m * P.W * N + (q_ok ? qrow : 0);
 
   bf16x8 qf[KS];
 #pragma unroll
@@ -179,49 +206,48 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   float m_run = -INFINITY, l_run = 0.0f;
   const float c = P.scale * kLog2e;
 
-  TileIter it;
-  it.init(P, m, i, lane);
+  // ---- LDS tile layout: row r (one key) holds its RC 16-byte chunks permuted, chunk ch at position ch ^ swz(r),
+  // so that the 16-byte row reads of the first product and the transposing reads of the second both spread over
+  // all banks.  Every address below is "one per-lane register + a compile-time constant".
+  auto swz = [](int r) { return D == 64 ? ((r >> 1) & 7) : (r & 15); };
 
-  uint4 kreg[CPT], vreg[CPT];
-  auto load_tile = [&](int jt) {
+  // Asynchronous global -> LDS copy (no registers in between).  One instruction moves 1 KiB per wave: lane l lands at
+  // LDS base + 16*l, so each lane fetches the chunk that belongs at its slot.  goff[n] is this lane's element
+  // offset inside a tile for its n-th instruction.
+  int goff[LPW];
 #pragma unroll
-    for (int n = 0; n < CPT; ++n) {
-      const int ch = tid + n * NT;
-      const int r = ch / (D / 8), cc = ch % (D / 8);
-      const int64_t key = (int64_t)jt * kBc + r;
-      if (key < N) {
-        kreg[n] = *reinterpret_cast<const uint4*>(Kg + key * D + cc * 8);
-        vreg[n] = *reinterpret_cast<const uint4*>(Vg + key * D + cc * 8);
-      } else {  // keys past N: zeros, so that 0-probability times V stays 0
-        kreg[n] = make_uint4(0, 0, 0, 0);
-        vreg[n] = make_uint4(0, 0, 0, 0);
+  for (int n = 0; n < LPW; ++n) {
+    const int sl = (n * NW + wave) * 64 + lane;
+    const int r = sl / RC, pos = sl % RC;
+    goff[n] = r * D + ((pos ^ swz(r)) * 8);
+  }
+  auto load_tile_async = [&](const __bf16* __restrict__ src, int jt, __bf16* dst) {
+    const int64_t key0 = (int64_t)jt * kBc;
+    if (key0 + kBc <= N) {
+      const __bf16* __restrict__ base = src + key0 * D;
+#pragma unroll
+      for (int n = 0; n < LPW; ++n)
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(base + goff[n]),
+                                         (void __attribute__((address_space(3)))*)(dst + (n * NW + wave) * 512), 16, 0, 0);
+    } else {
+      // Last tile of a ragged N.  Rows past N re-read row N-1: such keys sit in a tile that is never "full", the
+      // element mask gives them probability exactly 0, and a finite duplicate row then adds nothing.
+#pragma unroll
+      for (int n = 0; n < LPW; ++n) {
+        const int r = goff[n] / D;
+        const int64_t key = min(key0 + r, N - 1);
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src + key * D + (goff[n] - r * D)),
+                                         (void __attribute__((address_space(3)))*)(dst + (n * NW + wave) * 512), 16, 0, 0);
       }
     }
   };
-  auto store_tile = [&](int buf) {
+
+  // K fragment of MFMA k-step t, key block kb: row 32*kb + lq, chunk 2t + hh.  swz(32*kb + lq) = swz(lq).
+  int kaddr[KS];
 #pragma unroll
-    for (int n = 0; n < CPT; ++n) {
-      const int ch = tid + n * NT;
-      const int r = ch / (D / 8), cc = ch % (D / 8);
-      *reinterpret_cast<uint4*>(&k_s[buf][r * LD + cc * 8]) = kreg[n];
-      *reinterpret_cast<uint4*>(&v_s[buf][r * LD + cc * 8]) = vreg[n];
-    }
-  };
-
-  bool need_mask = true, need_mask_next = true;
-  int jt = it.next(lane, need_mask);
-  if (jt >= 0) load_tile(jt);
-  int buf = 0;
-  while (jt >= 0) {
-    const int jn = it.next(lane, need_mask_next);
-    store_tile(buf);
-    uint64_t mword = 0;
-    if (need_mask && q_ok) mword = P.packed[((int64_t)m * P.W + jt) * N + qrow];
-    __syncthreads();  // tile jt is in LDS; every wave is done with the other buffer's previous tile
-    if (jn >= 0) load_tile(jn);
-
-    // ---- S^T = K Q^T for 64 keys x 32 queries
-    f32x16 s[2];
+  for (int t = 0; t < KS; ++t) kaddr[t] = lq * LD + (((2 * t + hh) ^ swz(lq)) * 8);
+  // S^T = K Q^T for the 64 keys of one LDS tile x this wave's 32 queries
+  auto qk = [&](const __bf16* ks, f32x16 (&s)[2]) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
       for (int e = 0; e < 16; ++e) s[kb][e] = 0.0f;
@@ -229,30 +255,83 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     for (int t = 0; t < KS; ++t) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&k_s[buf][(32 * kb + lq) * LD + 16 * t + 8 * hh]);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + kaddr[t] + kb * 32 * LD);
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s[kb], 0, 0, 0);
       }
     }
+  };
+
+  // V fragment (transposing read) of 16-key step u, half a, column block db: the lane addresses row
+  // vr = 16u + 8a + 4hh + y (y = (lane%16)/4), 16-byte chunk vch = 4db + 2g + x (g = (lane/16)%2, x = (lane%4)/2),
+  // elements 4*(lane%2).. of it, and receives keys 16u + 8a + 4hh + 0..3 of column 32db + lane%32 -- the key
+  // order of the bf16 probabilities taken straight from the S^T accumulators.  u, a and the high bits of db only
+  // add constants; what depends on the lane is one register (two for d = 128, where bit 0 of db meets hh).
+  const int vy = (lane & 15) >> 2, vg = (lane >> 4) & 1, vx = (lane & 3) >> 1;
+  int vaddr[D == 64 ? 1 : 2];
+  if (D == 64) {
+    // swz(vr) = (4a + 2hh + (y >> 1)) & 7; chunk ^ swz = 4*(db ^ a) + ((2g + x) ^ (2hh + (y >> 1)))
+    vaddr[0] = (4 * hh + vy) * LD + (((2 * vg + vx) ^ (2 * hh + (vy >> 1))) * 8) + 4 * (lane & 1);
+  } else {
+    // swz(vr) = 8a + 4hh + y; chunk ^ swz = 8*((db >> 1) ^ a) + 4*((db & 1) ^ hh) + ((2g + x) ^ y)
+#pragma unroll
+    for (int d0 = 0; d0 < 2; ++d0)
+      vaddr[d0 % (D == 64 ? 1 : 2)] = (4 * hh + vy) * LD + (4 * (d0 ^ hh) + ((2 * vg + vx) ^ vy)) * 8 + 4 * (lane & 1);
+  }
+  auto v_frag = [&](const __bf16* vs, int u, int db) {
+    s16x4 part[2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      const int off = D == 64 ? (16 * u + 8 * a) * LD + 4 * (db ^ a) * 8
+                              : (16 * u + 8 * a) * LD + 8 * ((db >> 1) ^ a) * 8;
+      part[a] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (s16x4 __attribute__((address_space(3)))*)(vs + vaddr[D == 64 ? 0 : (db & 1)] + off));
+    }
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+
+  auto tile_of = [](uint32_t e) { return e == kNoTile ? -1 : (int)(e & 0x7fffffffu); };
+  const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
+
+  // One tile: mask, online softmax and O^T += V^T P^T for tile e0 whose K sits in k_s[PB] (PIPE: whose scores sit in
+  // s_in) and whose V sits in v_s[PB]; the asynchronous copies for the following tiles are started first.
+  uint32_t e0, e1, e2;
+  uint64_t mw_nxt;
+  auto step = [&](auto pb, f32x16 (&s_in)[2], f32x16 (&s_out)[2], int it) {
+    constexpr int PB = decltype(pb)::value;
+    const uint64_t mw = mw_nxt;
+    if (PIPE) e2 = tiles_s[it + 2];
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's asynchronous tile copies of the previous iteration have landed
+    __syncthreads();                // ... and everyone's; every wave is also done with the buffers refilled below
+    if (PIPE) {
+      if (e2 != kNoTile) load_tile_async(Kg, tile_of(e2), k_s + PB * TILE);        // K two tiles ahead replaces K(e0)
+      if (e1 != kNoTile) load_tile_async(Vg, tile_of(e1), v_s + (PB ^ 1) * TILE);  // V(e1) replaces V(previous tile)
+    } else if (e1 != kNoTile) {
+      load_tile_async(Kg, tile_of(e1), k_s + (PB ^ 1) * TILE);
+      load_tile_async(Vg, tile_of(e1), v_s + (PB ^ 1) * TILE);
+    }
+    if (e1 != kNoTile && (e1 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e1) * N];
+
+    if (!PIPE) qk(k_s + PB * TILE, s_in);
 
     // ---- element mask (only where the schedule cannot rule out zeros): keep s where the bit is set, else -inf
-    if (need_mask) {
+    if ((e0 >> 31) == 0) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
-        const uint32_t w = (uint32_t)(mword >> (32 * kb)) >> (4 * hh);
+        const uint32_t w = (uint32_t)(mw >> (32 * kb)) >> (4 * hh);
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int bit = 8 * (e / 4) + (e % 4);
           const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);  // all ones iff the bit is set
-          s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
+          s_in[kb][e] = __uint_as_float((__float_as_uint(s_in[kb][e]) & keep) | (0xff800000u & ~keep));
         }
       }
     }
 
-    // ---- online softmax for this lane's query row
-    float mx = s[0][0];
+    // ---- row maximum of this lane's query row
+    float mx = s_in[0][0];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s_in[kb][e]);
     mx = partner_max(mx);
     // The reference maximum m_run only moves when some row's maximum grew by more than kLazy (in log2 units):
     // softmax is invariant to the reference, probabilities stay <= 2^kLazy, and the rescale of O is skipped.
@@ -266,40 +345,59 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       for (int db = 0; db < DB; ++db)
         for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
     }
-    const float msc = ((m_run == -INFINITY) ? 0.0f : m_run) * c;
-    float rs = 0.0f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-      for (int e = 0; e < 16; ++e) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][e], c, -msc));
-        s[kb][e] = p;
-        rs += p;
-      }
-    l_run += rs;
 
-    // ---- O^T += V^T P^T
+    // ---- scores of the NEXT tile (matrix pipe) alongside the exponentials of this one (vector pipe)
+    if (PIPE) qk(k_s + (PB ^ 1) * TILE, s_out);  // K(e1); harmless stale data if there is no next tile
+
+    const float msc = ((m_run == -INFINITY) ? 0.0f : m_run) * c;
+    const __bf16* vs = v_s + PB * TILE;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       bf16x8 pf;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[u / 2][8 * (u % 2) + e];
+      for (int e = 0; e < 8; ++e)
+        pf[e] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s_in[u / 2][8 * (u % 2) + e], c, -msc));
+      // row sum of the ROUNDED probabilities (the same numbers the second product consumes), two per instruction
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        // transposing read: lane gets keys k0..k0+3 of column dcol; k0 = 16u + 8a + 4hh, matching the key order of pf
-        const int vr = 16 * u + 4 * hh + ((lane & 15) >> 2);
-        const int vc = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (s16x4 __attribute__((address_space(3)))*)(&v_s[buf][vr * LD + vc]));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (s16x4 __attribute__((address_space(3)))*)(&v_s[buf][(vr + 8) * LD + vc]));
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
+      for (int e = 0; e < 8; e += 2) {
+        const bf16x2 pair = {pf[e], pf[e + 1]};
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(pair, ones2, l_run, false);
       }
+      // ---- O^T += V^T P^T
+#pragma unroll
+      for (int db = 0; db < DB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(vs, u, db), pf, oacc[db], 0, 0, 0);
+    }
+    e0 = e1;
+    e1 = e2;
+    if (!PIPE) e2 = tiles_s[it + 3];
+  };
+
+  const int nwin = num_windows(P, m, i);
+  for (int win = 0; win < nwin; ++win) {
+    const int count = build_window<NW>(P, m, i, win, tiles_s, cnt_s);
+    if (count == 0) continue;
+
+    // ---- pipeline fill
+    e0 = tiles_s[0];
+    e1 = tiles_s[1];
+    e2 = tiles_s[2];
+    f32x16 s_a[2], s_b[2];
+    mw_nxt = 0;
+    load_tile_async(Kg, tile_of(e0), k_s);
+    load_tile_async(Vg, tile_of(e0), v_s);
+    if (PIPE && e1 != kNoTile) load_tile_async(Kg, tile_of(e1), k_s + TILE);
+    if ((e0 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e0) * N];
+    if (PIPE) {
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      qk(k_s, s_a);
     }
 
-    buf ^= 1;
-    jt = jn;
-    need_mask = need_mask_next;
+    for (int it = 0; it < count; it += 2) {
+      step(IntC<0>{}, s_a, s_b, it);
+      if (it + 1 < count) step(IntC<1>{}, s_b, s_a, it + 1);
+    }
+    __syncthreads();  // the next window rewrites the tile list and the K/V buffers
   }
 
   // ---- epilogue: normalise, round to bf16, store; fully masked rows give O = 0, lse = -inf
@@ -323,7 +421,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
 
 template <int D, int NW>
 int launch(const AttnParams& P, hipStream_t s) {
-  attn_fwd_kernel<D, NW><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+  attn_fwd_kernel<D, NW, D == 64><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   return bbm::launch_status("bbm_attn_fwd");
 }
 
