@@ -12,7 +12,7 @@ SOURCES = ["bbm_error.hip", "bbm_preprocess.hip", "bbm_index.hip", "bbm_attn.hip
 # packed-fp32 VALU ops are switched off for device code (the host pass warns that it ignores the feature)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-               "-mllvm", "-amdgpu-mfma-vgpr-form"]
+               "-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"]
 
 
 def hipcc_path() -> str:

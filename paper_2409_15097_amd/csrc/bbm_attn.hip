@@ -153,21 +153,30 @@ template <int D, int NW, bool PIPE>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NT = NW * 64;
   constexpr int BR = NW * 32;
-  constexpr int LD = D;                        // LDS row stride in elements (rows are not padded, chunks are swizzled)
+  // LDS tile layout ("blocks"): one asynchronous copy instruction of a wave fills one 1 KiB block with RPB rows
+  // that lie NBLK rows apart: row r sits in block r % NBLK at slot r / NBLK.  Blocks are padded (K by 16 bytes, V
+  // by 64) so that the 16 consecutive rows a 16-byte K read touches, and the 4 consecutive rows a transposing V
+  // read touches, start in different banks.  Every read address is one per-lane register plus a constant.
   constexpr int RC = D / 8;                    // 16-byte chunks per row
-  constexpr int CHUNKS = kBc * RC;             // 16-byte chunks per K (or V) tile
-  constexpr int LPW = CHUNKS / NT;             // direct-to-LDS load instructions per wave and tile
-  static_assert(CHUNKS % NT == 0, "tile must split evenly over the work-group");
+  constexpr int RPB = 64 / RC;                 // rows per 1 KiB block
+  constexpr int NBLK = kBc / RPB;              // blocks per tile = copy instructions per tile
+  constexpr int LPW = NBLK / NW;               // copy instructions per wave and tile
+  static_assert(NBLK % NW == 0, "tile must split evenly over the waves");
+  constexpr int KBLK = 512 + 8;                // K block stride in elements (1 KiB + 16 B)
+  constexpr int VBLK = 512 + 32;               // V block stride in elements (1 KiB + 64 B)
   constexpr int KS = D / 16;                   // MFMA k-steps of the first product
   constexpr int DB = D / 32;                   // 32-wide output-column blocks of the second product
-  constexpr int TILE = kBc * LD;               // elements per LDS tile buffer
 
-  __shared__ __attribute__((aligned(16))) __bf16 k_s[2 * TILE];
-  __shared__ __attribute__((aligned(16))) __bf16 v_s[2 * TILE];
+  // separate arrays per buffer so the compiler can tell an asynchronous copy into one from reads of the other
+  __shared__ __attribute__((aligned(16))) __bf16 k_s0[NBLK * KBLK];
+  __shared__ __attribute__((aligned(16))) __bf16 k_s1[NBLK * KBLK];
+  __shared__ __attribute__((aligned(16))) __bf16 v_s0[NBLK * VBLK];
+  __shared__ __attribute__((aligned(16))) __bf16 v_s1[NBLK * VBLK];
   __shared__ uint32_t tiles_s[kWin + 4];
   __shared__ int cnt_s[kWin / 64];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction: keep it in a scalar register
   const int lq = lane & 31, hh = lane >> 5;
 
   // Work-groups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of logical ids so the
@@ -206,46 +215,34 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   float m_run = -INFINITY, l_run = 0.0f;
   const float c = P.scale * kLog2e;
 
-  // ---- LDS tile layout: row r (one key) holds its RC 16-byte chunks permuted, chunk ch at position ch ^ swz(r),
-  // so that the 16-byte row reads of the first product and the transposing reads of the second both spread over
-  // all banks.  Every address below is "one per-lane register + a compile-time constant".
-  auto swz = [](int r) { return D == 64 ? ((r >> 1) & 7) : (r & 15); };
-
   // Asynchronous global -> LDS copy (no registers in between).  One instruction moves 1 KiB per wave: lane l lands at
-  // LDS base + 16*l, so each lane fetches the chunk that belongs at its slot.  goff[n] is this lane's element
-  // offset inside a tile for its n-th instruction.
-  int goff[LPW];
-#pragma unroll
-  for (int n = 0; n < LPW; ++n) {
-    const int sl = (n * NW + wave) * 64 + lane;
-    const int r = sl / RC, pos = sl % RC;
-    goff[n] = r * D + ((pos ^ swz(r)) * 8);
-  }
-  auto load_tile_async = [&](const __bf16* __restrict__ src, int jt, __bf16* dst) {
+  // LDS base + 16*l, i.e. slot l / RC, chunk l % RC of the block, so it fetches row (block + NBLK * slot).
+  const int g_row = lane / RC, g_chunk = lane % RC;
+  auto load_tile_async = [&](const __bf16* __restrict__ src, int jt, __bf16* dst, int blk_stride) {
     const int64_t key0 = (int64_t)jt * kBc;
     if (key0 + kBc <= N) {
-      const __bf16* __restrict__ base = src + key0 * D;
+      const __bf16* __restrict__ base = src + key0 * D + (g_row * NBLK * D + g_chunk * 8);
 #pragma unroll
-      for (int n = 0; n < LPW; ++n)
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(base + goff[n]),
-                                         (void __attribute__((address_space(3)))*)(dst + (n * NW + wave) * 512), 16, 0, 0);
+      for (int n = 0; n < LPW; ++n) {
+        const int q = n * NW + wave;  // block filled by this instruction
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(base + q * D),
+                                         (void __attribute__((address_space(3)))*)(dst + q * blk_stride), 16, 0, 0);
+      }
     } else {
       // Last tile of a ragged N.  Rows past N re-read row N-1: such keys sit in a tile that is never "full", the
       // element mask gives them probability exactly 0, and a finite duplicate row then adds nothing.
 #pragma unroll
       for (int n = 0; n < LPW; ++n) {
-        const int r = goff[n] / D;
-        const int64_t key = min(key0 + r, N - 1);
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src + key * D + (goff[n] - r * D)),
-                                         (void __attribute__((address_space(3)))*)(dst + (n * NW + wave) * 512), 16, 0, 0);
+        const int q = n * NW + wave;
+        const int64_t key = min(key0 + q + g_row * NBLK, N - 1);
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src + key * D + g_chunk * 8),
+                                         (void __attribute__((address_space(3)))*)(dst + q * blk_stride), 16, 0, 0);
       }
     }
   };
 
-  // K fragment of MFMA k-step t, key block kb: row 32*kb + lq, chunk 2t + hh.  swz(32*kb + lq) = swz(lq).
-  int kaddr[KS];
-#pragma unroll
-  for (int t = 0; t < KS; ++t) kaddr[t] = lq * LD + (((2 * t + hh) ^ swz(lq)) * 8);
+  // K fragment of MFMA k-step t, key block kb: row 32*kb + lq, chunk 2t + hh.
+  const int kaddr = (lq % NBLK) * KBLK + (lq / NBLK) * D + hh * 8;
   // S^T = K Q^T for the 64 keys of one LDS tile x this wave's 32 queries
   auto qk = [&](const __bf16* ks, f32x16 (&s)[2]) {
 #pragma unroll
@@ -255,36 +252,25 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     for (int t = 0; t < KS; ++t) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + kaddr[t] + kb * 32 * LD);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + kaddr + kb * (32 / NBLK) * D + t * 16);
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s[kb], 0, 0, 0);
       }
     }
   };
 
   // V fragment (transposing read) of 16-key step u, half a, column block db: the lane addresses row
-  // vr = 16u + 8a + 4hh + y (y = (lane%16)/4), 16-byte chunk vch = 4db + 2g + x (g = (lane/16)%2, x = (lane%4)/2),
+  // vr = 16u + 8a + 4hh + y (y = (lane%16)/4), 16-byte chunk 4db + 2g + x (g = (lane/16)%2, x = (lane%4)/2),
   // elements 4*(lane%2).. of it, and receives keys 16u + 8a + 4hh + 0..3 of column 32db + lane%32 -- the key
-  // order of the bf16 probabilities taken straight from the S^T accumulators.  u, a and the high bits of db only
-  // add constants; what depends on the lane is one register (two for d = 128, where bit 0 of db meets hh).
+  // order of the bf16 probabilities taken straight from the S^T accumulators.
   const int vy = (lane & 15) >> 2, vg = (lane >> 4) & 1, vx = (lane & 3) >> 1;
-  int vaddr[D == 64 ? 1 : 2];
-  if (D == 64) {
-    // swz(vr) = (4a + 2hh + (y >> 1)) & 7; chunk ^ swz = 4*(db ^ a) + ((2g + x) ^ (2hh + (y >> 1)))
-    vaddr[0] = (4 * hh + vy) * LD + (((2 * vg + vx) ^ (2 * hh + (vy >> 1))) * 8) + 4 * (lane & 1);
-  } else {
-    // swz(vr) = 8a + 4hh + y; chunk ^ swz = 8*((db >> 1) ^ a) + 4*((db & 1) ^ hh) + ((2g + x) ^ y)
-#pragma unroll
-    for (int d0 = 0; d0 < 2; ++d0)
-      vaddr[d0 % (D == 64 ? 1 : 2)] = (4 * hh + vy) * LD + (4 * (d0 ^ hh) + ((2 * vg + vx) ^ vy)) * 8 + 4 * (lane & 1);
-  }
+  const int vaddr = (4 * hh + vy) * VBLK + (2 * vg + vx) * 8 + 4 * (lane & 1);
   auto v_frag = [&](const __bf16* vs, int u, int db) {
     s16x4 part[2];
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
-      const int off = D == 64 ? (16 * u + 8 * a) * LD + 4 * (db ^ a) * 8
-                              : (16 * u + 8 * a) * LD + 8 * ((db >> 1) ^ a) * 8;
-      part[a] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (s16x4 __attribute__((address_space(3)))*)(vs + vaddr[D == 64 ? 0 : (db & 1)] + off));
+      // row 16u + 8a + (4hh + y): block (row % NBLK), slot (row / NBLK)
+      const int off = D == 64 ? (2 * u + a) * D + db * 32 : 8 * a * VBLK + u * D + db * 32;
+      part[a] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vs + vaddr + off));
     }
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7));
   };
@@ -302,16 +288,20 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     if (PIPE) e2 = tiles_s[it + 2];
     __builtin_amdgcn_s_waitcnt(0);  // this wave's asynchronous tile copies of the previous iteration have landed
     __syncthreads();                // ... and everyone's; every wave is also done with the buffers refilled below
+    __bf16* const k_cur = PB ? k_s1 : k_s0;
+    __bf16* const k_oth = PB ? k_s0 : k_s1;
+    __bf16* const v_cur = PB ? v_s1 : v_s0;
+    __bf16* const v_oth = PB ? v_s0 : v_s1;
     if (PIPE) {
-      if (e2 != kNoTile) load_tile_async(Kg, tile_of(e2), k_s + PB * TILE);        // K two tiles ahead replaces K(e0)
-      if (e1 != kNoTile) load_tile_async(Vg, tile_of(e1), v_s + (PB ^ 1) * TILE);  // V(e1) replaces V(previous tile)
+      if (e2 != kNoTile) load_tile_async(Kg, tile_of(e2), k_cur, KBLK);  // K two tiles ahead replaces K(e0)
+      if (e1 != kNoTile) load_tile_async(Vg, tile_of(e1), v_oth, VBLK);  // V(e1) replaces V(previous tile)
     } else if (e1 != kNoTile) {
-      load_tile_async(Kg, tile_of(e1), k_s + (PB ^ 1) * TILE);
-      load_tile_async(Vg, tile_of(e1), v_s + (PB ^ 1) * TILE);
+      load_tile_async(Kg, tile_of(e1), k_oth, KBLK);
+      load_tile_async(Vg, tile_of(e1), v_oth, VBLK);
     }
     if (e1 != kNoTile && (e1 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e1) * N];
 
-    if (!PIPE) qk(k_s + PB * TILE, s_in);
+    if (!PIPE) qk(k_cur, s_in);
 
     // ---- element mask (only where the schedule cannot rule out zeros): keep s where the bit is set, else -inf
     if ((e0 >> 31) == 0) {
@@ -347,10 +337,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     }
 
     // ---- scores of the NEXT tile (matrix pipe) alongside the exponentials of this one (vector pipe)
-    if (PIPE) qk(k_s + (PB ^ 1) * TILE, s_out);  // K(e1); harmless stale data if there is no next tile
+    if (PIPE) qk(k_oth, s_out);  // K(e1); harmless stale data if there is no next tile
 
     const float msc = ((m_run == -INFINITY) ? 0.0f : m_run) * c;
-    const __bf16* vs = v_s + PB * TILE;
+    const __bf16* vs = v_cur;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       bf16x8 pf;
@@ -383,14 +373,14 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     e2 = tiles_s[2];
     f32x16 s_a[2], s_b[2];
     mw_nxt = 0;
-    load_tile_async(Kg, tile_of(e0), k_s);
-    load_tile_async(Vg, tile_of(e0), v_s);
-    if (PIPE && e1 != kNoTile) load_tile_async(Kg, tile_of(e1), k_s + TILE);
+    load_tile_async(Kg, tile_of(e0), k_s0, KBLK);
+    load_tile_async(Vg, tile_of(e0), v_s0, VBLK);
+    if (PIPE && e1 != kNoTile) load_tile_async(Kg, tile_of(e1), k_s1, KBLK);
     if ((e0 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e0) * N];
     if (PIPE) {
       __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
-      qk(k_s, s_a);
+      qk(k_s0, s_a);
     }
 
     for (int it = 0; it < count; it += 2) {
@@ -421,7 +411,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
 
 template <int D, int NW>
 int launch(const AttnParams& P, hipStream_t s) {
-  attn_fwd_kernel<D, NW, D == 64><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+  attn_fwd_kernel<D, NW, false><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   return bbm::launch_status("bbm_attn_fwd");
 }
 
