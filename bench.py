@@ -25,6 +25,19 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0              # MI355X HBM3E
 
 
+def profiled_traffic_bytes(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, each scaled by the
+    copy-kernel factor), or None if no summary exists for this kernel and workload."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}.md")
+    try:
+        for line in open(path):
+            if line.startswith("Total traffic per launch:"):
+                return float(line.split(":")[1].split("MB")[0]) * 1e6
+    except OSError:
+        pass
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -195,7 +208,8 @@ def main():
         "preprocess_ms": main_res["preprocess_ms"], "preprocess_gbs": main_res["preprocess_gbs"],
         "roofline": {"bound": "mfma", "kernel": "attn_fwd_kernel", "achieved": main_res["attn_tflops_visited"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": main_res["attn_tflops_visited"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": main_res["attn_tflops_visited"] / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": profiled_traffic_bytes("attn_fwd_kernel", a.workload),
                      "algo_bytes": main_res["attn_algo_bytes"],
                      "hbm_frac_of_algo_bytes": main_res["attn_algo_bytes"] / (main_res["attn_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "per_mask": rows,
