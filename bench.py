@@ -83,6 +83,7 @@ def measure_mask(bbm, name, Br, warmup, steps, torch):
     idx = bbm.build_index(mask, Br, 64)
     out = torch.empty_like(q)
     lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(16, bbm.bbm_attn_fwd_workspace_bytes(B, H, N, d, Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     tiles = visited_tiles(idx, B, H)
     cls = idx.blk_class
@@ -95,14 +96,14 @@ def measure_mask(bbm, name, Br, warmup, steps, torch):
         bbm.bbm_build_block_mask(mask, Br, 64, idx=idx)
         bbm.bbm_build_runs(idx)
         bbm.bbm_build_sparse_index(idx)
-        bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse)
+        bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws)
 
     res = dict(workload=name, B=B, H=H, N=N, d=d, Mb=Mb, Br=Br, Bc=64, visited_tiles=tiles, blocks=census,
                visited_tflop=flops / 1e12, dense_tflop=dense_flops / 1e12, useful_tflop=useful_flops / 1e12)
     res["step_ms"] = time_gpu(step, warmup, steps)
     for mode_name in ("LIST", "RUNS", "BITMAP"):
         mode = getattr(bbm, "BBM_MODE_" + mode_name)
-        ms = time_gpu(lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=mode, out=out, lse=lse), warmup, steps)
+        ms = time_gpu(lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=mode, out=out, lse=lse, workspace=ws), warmup, steps)
         res[f"attn_{mode_name.lower()}_ms"] = ms
     res["attn_ms"] = res["attn_list_ms"]
     res["attn_tflops_visited"] = flops / (res["attn_ms"] * 1e-3) / 1e12
@@ -120,7 +121,7 @@ def measure_mask(bbm, name, Br, warmup, steps, torch):
     res["index_ms"] = time_gpu(lambda: (bbm.bbm_build_runs(idx), bbm.bbm_build_sparse_index(idx)), warmup, steps)
     # algorithmic HBM bytes of the attention kernel: Q, K, V read once, O written once, lse, packed words of partial tiles
     res["attn_algo_bytes"] = 4.0 * B * H * N * d * 2 + 4.0 * B * H * N + census["partial"] * (B // Mb) * Br * 8.0
-    del mask, q, k, v, idx, out, lse
+    del mask, q, k, v, idx, out, lse, ws
     torch.cuda.empty_cache()
     return res, cfg
 
@@ -172,12 +173,13 @@ def main():
         q, k, v = (bbm.bf16_from_bits(cfg[x]) for x in "qkv")
         out = torch.empty_like(q)
         lse = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(16, bbm.bbm_attn_fwd_workspace_bytes(*q.shape, a.Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
         src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda").fill_(1)     # 256 MiB copy for counter calibration
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         for _ in range(a.warmup + a.steps):
             if a.only_kernel == "attn":
-                bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse)
+                bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws)
             elif a.only_kernel == "preprocess":
                 bbm.bbm_build_block_mask(mask, a.Br, 64, idx=idx)
             elif a.only_kernel == "copy":

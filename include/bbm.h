@@ -46,9 +46,10 @@ extern "C" {
 #define BBM_MODE_RUNS 1           /* paper Sec. 4 "Dense Binary Block Masking": scan [nz_lo, nz_hi), visit iff BinBlkMat,
                                      skip the element mask inside [offset, offset + total_ones)                        */
 #define BBM_MODE_LIST 2           /* walk the compact per-row list of non-zero blocks; element mask skipped on blocks
-                                     flagged full                                                                      */
+                                     flagged full; rows the split schedule cut are computed part by part by extra
+                                     work-groups and merged                                                            */
 #define BBM_MODE_DENSE_BASELINE 3 /* paper Sec. 3 "naive masking": visit every block, apply the element mask everywhere */
-#define BBM_MODE_AUTO 4           /* LIST if the index carries a list, else RUNS, else BITMAP                          */
+#define BBM_MODE_AUTO 4           /* LIST if the index carries list and schedule, else RUNS, else BITMAP               */
 
 /* Device pointers produced by the build functions, gathered for bbm_attn_fwd.  The struct lives in host
  * memory; unused members may be NULL (which ones are needed depends on `mode`, see bbm_attn_fwd). */
@@ -64,6 +65,7 @@ typedef struct bbm_index {
   const int32_t* nz_cnt;      /* [Mb, nbr] number of non-zero blocks                                 */
   const int32_t* row_ptr;     /* [Mb, nbr + 1] list offsets within a plane, row_ptr[m][0] = 0        */
   const uint32_t* col_idx;    /* [Mb * nbr * nbc]; plane m starts at m*nbr*nbc; bit 31 = block full  */
+  const int32_t* sched;       /* bbm_sched_bytes(Mb, nbr) bytes: tile schedule of LIST mode           */
 } bbm_index;
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
@@ -117,10 +119,22 @@ int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nb
  *   col_idx          device out, uint32, capacity Mb*nbr*nbc entries; the list of plane m starts at entry
  *                    m*nbr*nbc; block columns ascending within a row; bit 31 set iff the block is full.
  *                    Entries past row_ptr[m][nbr] are left untouched.
- * Requires nbr*nbc < 2^31.  Errors: BBM_EINVAL, BBM_EHIP.
+ *   sched            device out, bbm_sched_bytes(Mb, nbr) bytes, 32-byte aligned; may be NULL.  The split schedule
+ *                    that LIST mode of bbm_attn_fwd uses to keep one very long block row (a row of global tokens,
+ *                    say) from becoming the whole kernel's critical path: rows with more than
+ *                    T = max(32, 2 * mean entries per non-empty row) list entries are cut into ceil(n/T) near-equal
+ *                    parts.  int32 layout: [0] parts, [1] T, [2] cut rows, [3..7] 0, then 8 ints per part ordered by
+ *                    (row, part): plane*nbr + block row, first entry (position in the plane's list), entries, part,
+ *                    parts of the row, number of the row's first part, index of the row among the cut rows, 0.
+ *                    It depends only on the mask, so it is shared by heads, layers and calls like the rest of the
+ *                    index.
+ * Requires nbr*nbc < 2^31 and Mb*nbr < 2^24.  Errors: BBM_EINVAL, BBM_EHIP.
  */
 int bbm_build_sparse_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* row_ptr,
-                           uint32_t* col_idx, void* stream);
+                           uint32_t* col_idx, int32_t* sched, void* stream);
+
+/* Bytes of the tile schedule bbm_build_sparse_index writes for Mb planes of nbr block rows (0 for sizes < 1). */
+size_t bbm_sched_bytes(int64_t Mb, int64_t nbr);
 
 /*
  * Bytes of device workspace bbm_attn_fwd needs for this problem (0 if none).  Negative sizes return 0.
@@ -145,11 +159,16 @@ size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
  *   idx              host pointer; idx->Bc must be 64 and idx->Br one of 64, 128, 256; idx->Mb == Mb;
  *                    idx->nbr/nbc must equal ceil(N/Br), ceil(N/Bc).  Members needed per mode:
  *                    BITMAP: bin_blk_mat;  RUNS: bin_blk_mat, offset, total_ones, nz_lo, nz_hi;
- *                    LIST: row_ptr, col_idx;  DENSE_BASELINE: none.
+ *                    LIST: row_ptr, col_idx, sched;  DENSE_BASELINE: none.
  *   mode             BBM_MODE_*.
- *   workspace        device scratch of at least bbm_attn_fwd_workspace_bytes(...) bytes (may be NULL if 0).
+ *   workspace        device scratch of at least bbm_attn_fwd_workspace_bytes(...) bytes, 16-byte aligned (may be NULL
+ *                    if 0).  LIST mode keeps its queue counters and the partial results of cut block rows there;
+ *                    contents need not be initialised and are meaningless afterwards.  Two calls that overlap in
+ *                    time (different streams) must not share a workspace.
  * Arithmetic: QK^T and PV on bf16 MFMA with fp32 accumulation; softmax statistics in fp32; P rounded to
- * bf16 before PV.  Deterministic: the same inputs give bit-identical outputs.
+ * bf16 before PV.  Deterministic: the same inputs give bit-identical outputs (in LIST mode the parts of a cut row
+ * are taken from a queue in whatever order work-groups become free, but each part's arithmetic and the order in
+ * which the parts are merged are fixed).
  * Errors: BBM_EINVAL, BBM_EUNSUPPORTED (d / Br / Bc without a kernel instance), BBM_EWORKSPACE, BBM_EHIP.
  */
 int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t N,

@@ -8,4 +8,4 @@ It shares no code with the GPU library or its Python binding.
 from .attention import bf16_bits_to_f64, masked_attention, masked_attention_rows  # noqa: F401
 from .brute import brute_attention, brute_block_counts  # noqa: F401
 from .blocks import (block_counts, block_class, bin_blk_mat, run_index, sparse_index, packed_bits,  # noqa: F401
-                     block_index)
+                     block_index, schedule)

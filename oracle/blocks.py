@@ -102,10 +102,48 @@ def packed_bits(mask):
     return out
 
 
+SCHED_PART_BASE = 8
+SCHED_PART_INTS = 8
+SCHED_MIN_SPLIT = 32
+
+
+def schedule(row_ptr):
+    """Split schedule of the list mode (this build's own layout, stated in the library header).
+
+    row_ptr int32 [Mb, nbr+1] -> int32 array of 8 + 8*Mb*nbr entries: [0] parts, [1] split threshold
+    T = max(32, 2*ceil(mean list length of the non-empty rows)), [2] cut rows, [3..7] 0, then 8 ints per part in
+    (row, part) order: row (= plane*nbr + block row), first entry (position in the plane's list), entries, part,
+    parts of the row, number of the row's first part, index of the row among the cut rows, 0.
+    A row with n > T entries is cut into ceil(n/T) parts of ceil(n/parts) entries (the last part takes the rest);
+    rows with n <= T are not listed.  Entries past the last part are unspecified."""
+    Mb, nbr1 = row_ptr.shape
+    nbr = nbr1 - 1
+    counts = [int(row_ptr[m, i + 1] - row_ptr[m, i]) for m in range(Mb) for i in range(nbr)]
+    nonempty = sum(1 for c in counts if c > 0)
+    mean = -(-sum(counts) // nonempty) if nonempty else 0
+    T = max(SCHED_MIN_SPLIT, 2 * mean)
+    out = np.zeros(SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbr, dtype=np.int32)
+    q, rho = 0, 0
+    for r, c in enumerate(counts):
+        if c <= T:
+            continue
+        parts = -(-c // T)
+        chunk = -(-c // parts)
+        for k in range(parts):
+            first = int(row_ptr[r // nbr, r % nbr]) + k * chunk
+            o = SCHED_PART_BASE + SCHED_PART_INTS * (q + k)
+            out[o:o + 8] = (r, first, min(chunk, c - k * chunk), k, parts, q, rho, 0)
+        q += parts
+        rho += 1
+    out[0], out[1], out[2] = q, T, rho
+    return out
+
+
 def block_index(mask, Br, Bc):
     """Everything the preprocessing stage produces, as a dict."""
     cls = block_class(mask, Br, Bc)
     idx = dict(cls=cls, bin_blk_mat=(cls != 0).astype(np.uint8))
     idx.update(run_index(cls))
     idx["row_ptr"], idx["col_idx"] = sparse_index(cls)
+    idx["sched"] = schedule(idx["row_ptr"])
     return idx

@@ -22,7 +22,7 @@ class _CIndex(C.Structure):
     _fields_ = [("Br", C.c_int32), ("Bc", C.c_int32), ("Mb", C.c_int64), ("nbr", C.c_int64), ("nbc", C.c_int64),
                 ("blk_class", C.c_void_p), ("bin_blk_mat", C.c_void_p), ("offset", C.c_void_p),
                 ("total_ones", C.c_void_p), ("nz_lo", C.c_void_p), ("nz_hi", C.c_void_p), ("nz_cnt", C.c_void_p),
-                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p)]
+                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("sched", C.c_void_p)]
 
 
 def library_path() -> str:
@@ -44,7 +44,9 @@ def _load():
     L.bbm_build_runs.restype = ci
     L.bbm_build_runs.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
     L.bbm_build_sparse_index.restype = ci
-    L.bbm_build_sparse_index.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    L.bbm_build_sparse_index.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
+    L.bbm_sched_bytes.restype = C.c_size_t
+    L.bbm_sched_bytes.argtypes = [i64, i64]
     L.bbm_attn_fwd_workspace_bytes.restype = C.c_size_t
     L.bbm_attn_fwd_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ci]
     L.bbm_attn_fwd.restype = ci
@@ -102,12 +104,13 @@ class BlockIndex:
     nz_cnt: Optional[torch.Tensor] = None
     row_ptr: Optional[torch.Tensor] = None
     col_idx: Optional[torch.Tensor] = None
+    sched: Optional[torch.Tensor] = None
 
     def c_struct(self) -> _CIndex:
         g = lambda t: None if t is None else t.data_ptr()
         return _CIndex(self.Br, self.Bc, self.Mb, self.nbr, self.nbc, g(self.blk_class), g(self.bin_blk_mat),
                        g(self.offset), g(self.total_ones), g(self.nz_lo), g(self.nz_hi), g(self.nz_cnt),
-                       g(self.row_ptr), g(self.col_idx))
+                       g(self.row_ptr), g(self.col_idx), g(self.sched))
 
 
 def bbm_build_block_mask(mask: torch.Tensor, Br: int, Bc: int, idx: Optional[BlockIndex] = None,
@@ -141,14 +144,20 @@ def bbm_build_runs(idx: BlockIndex, stream=None) -> BlockIndex:
     return idx
 
 
+def bbm_sched_bytes(Mb: int, nbr: int) -> int:
+    return int(lib.bbm_sched_bytes(Mb, nbr))
+
+
 def bbm_build_sparse_index(idx: BlockIndex, stream=None) -> BlockIndex:
     dev = idx.blk_class.device
     if idx.row_ptr is None:
         idx.row_ptr = torch.empty((idx.Mb, idx.nbr + 1), dtype=torch.int32, device=dev)
     if idx.col_idx is None:
         idx.col_idx = torch.zeros(idx.Mb * idx.nbr * idx.nbc, dtype=torch.int32, device=dev)
+    if idx.sched is None:
+        idx.sched = torch.empty(bbm_sched_bytes(idx.Mb, idx.nbr) // 4, dtype=torch.int32, device=dev)
     _check(lib.bbm_build_sparse_index(_ptr(idx.blk_class), idx.Mb, idx.nbr, idx.nbc, _ptr(idx.row_ptr),
-                                      _ptr(idx.col_idx), _stream(stream)))
+                                      _ptr(idx.col_idx), _ptr(idx.sched), _stream(stream)))
     return idx
 
 

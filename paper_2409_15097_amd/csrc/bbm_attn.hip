@@ -46,6 +46,12 @@ struct AttnParams {
   int32_t total_wgs;
   int32_t mode;
   float scale;
+  // LIST mode: schedule (read-only), work-queue state and partial results of cut rows (in the caller's workspace)
+  const int32_t* sched;
+  int32_t* queue;     // [0] part items handed out, [8 + rho*hbp + hb] finished parts of cut row rho
+  float* partials;    // [(cut part)*hbp + hb][regs + 2][threads]
+  int32_t hbp;        // (batch, head) pairs per mask plane: B*H if Mb == 1, else H
+  int32_t n_extra;    // leading work-groups that serve the queue of cut-row parts (LIST mode)
 };
 
 __device__ __forceinline__ float partner_max(float x) {
@@ -146,10 +152,11 @@ struct IntC {
   static constexpr int value = V;
 };
 
-// PIPE = true: software-pipelined -- the scores of tile t+1 (matrix pipe) are issued next to the exponentials of
-// tile t (vector pipe) inside one wave; costs a second set of score registers.  PIPE = false: each iteration
-// computes and consumes its own scores and relies on the other waves of the SIMD for overlap.
-template <int D, int NW, bool PIPE>
+// One work-group per (block row, batch, head), tiles from build_window.  With SCHED = true (LIST mode) the first
+// P.n_extra work-groups, before turning to their own block row, take the parts of the block rows which the split
+// schedule cut from a queue; the work-group that completes a row's last part merges the parts in part order and
+// writes the row, and the row's own work-group skips it.
+template <int D, int NW, bool SCHED>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NT = NW * 64;
   constexpr int BR = NW * 32;
@@ -166,6 +173,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   constexpr int VBLK = 512 + 32;               // V block stride in elements (1 KiB + 64 B)
   constexpr int KS = D / 16;                   // MFMA k-steps of the first product
   constexpr int DB = D / 32;                   // 32-wide output-column blocks of the second product
+  constexpr int REGS = DB * 16;                // fp32 accumulator registers per lane
 
   // separate arrays per buffer so the compiler can tell an asynchronous copy into one from reads of the other
   __shared__ __attribute__((aligned(16))) __bf16 k_s0[NBLK * KBLK];
@@ -174,46 +182,46 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   __shared__ __attribute__((aligned(16))) __bf16 v_s1[NBLK * VBLK];
   __shared__ uint32_t tiles_s[kWin + 4];
   __shared__ int cnt_s[kWin / 64];
+  __shared__ int item_s[2];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction: keep it in a scalar register
   const int lq = lane & 31, hh = lane >> 5;
-
-  // Work-groups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of logical ids so the
-  // row blocks of one head (which share K and V) meet in one XCD's L2.
-  const int T = P.total_wgs;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int per = T >> 3, rem = T & 7;
-  const int logical = xcd * per + (xcd < rem ? xcd : rem) + slot;
-  const int bh = logical / P.nbr;
-  const int i = P.nbr - 1 - (logical - bh * P.nbr);  // late (for causal-like masks: long) block rows first
-  const int b = bh / P.H;
-  const int m = (P.Mb == 1) ? 0 : b;
-
   const int64_t N = P.N;
-  const int64_t head_off = (int64_t)bh * N * D;
-  const __bf16* __restrict__ Kg = P.k + head_off;
-  const __bf16* __restrict__ Vg = P.v + head_off;
-  const int64_t qrow = (int64_t)i * BR + wave * 32 + lq;
-  const bool q_ok = qrow < N;
-  // packed mask words of this lane's query row (rows past N borrow row 0: their results are never stored)
-  const uint64_t* __restrict__ mrow = P.packed + (int64_t)m * P.W * N + (q_ok ? qrow : 0);
-
-  bf16x8 qf[KS];
-#pragma unroll
-  for (int t = 0; t < KS; ++t) {
-    if (q_ok)
-      qf[t] = *reinterpret_cast<const bf16x8*>(P.q + head_off + qrow * D + 16 * t + 8 * hh);
-    else
-      for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)0.0f;
-  }
-
-  f32x16 oacc[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-    for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
-  float m_run = -INFINITY, l_run = 0.0f;
   const float c = P.scale * kLog2e;
+
+  // ---- per-item state (SCHED = false: exactly one item, derived from blockIdx)
+  int m, i, bh;
+  const __bf16* __restrict__ Kg;
+  const __bf16* __restrict__ Vg;
+  int64_t head_off, qrow;
+  bool q_ok;
+  const uint64_t* __restrict__ mrow;
+  bf16x8 qf[KS];
+  f32x16 oacc[DB];
+  float m_run, l_run;
+
+  auto begin_item = [&]() {
+    head_off = (int64_t)bh * N * D;
+    Kg = P.k + head_off;
+    Vg = P.v + head_off;
+    qrow = (int64_t)i * BR + wave * 32 + lq;
+    q_ok = qrow < N;
+    // packed mask words of this lane's query row (rows past N borrow row 0: their results are never stored)
+    mrow = P.packed + (int64_t)m * P.W * N + (q_ok ? qrow : 0);
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+      if (q_ok)
+        qf[t] = *reinterpret_cast<const bf16x8*>(P.q + head_off + qrow * D + 16 * t + 8 * hh);
+      else
+        for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)0.0f;
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
+    m_run = -INFINITY;
+    l_run = 0.0f;
+  };
 
   // Asynchronous global -> LDS copy (no registers in between).  One instruction moves 1 KiB per wave: lane l lands at
   // LDS base + 16*l, i.e. slot l / RC, chunk l % RC of the block, so it fetches row (block + NBLK * slot).
@@ -278,30 +286,26 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   auto tile_of = [](uint32_t e) { return e == kNoTile ? -1 : (int)(e & 0x7fffffffu); };
   const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
-  // One tile: mask, online softmax and O^T += V^T P^T for tile e0 whose K sits in k_s[PB] (PIPE: whose scores sit in
-  // s_in) and whose V sits in v_s[PB]; the asynchronous copies for the following tiles are started first.
-  uint32_t e0, e1, e2;
+  // One tile: S^T = K Q^T, mask, online softmax and O^T += V^T P^T for tile e0 whose K and V sit in buffer PB; the
+  // asynchronous copies of the next tile into the other buffer are started first.
+  uint32_t e0, e1;
   uint64_t mw_nxt;
-  auto step = [&](auto pb, f32x16 (&s_in)[2], f32x16 (&s_out)[2], int it) {
+  auto step = [&](auto pb, int it) {
     constexpr int PB = decltype(pb)::value;
     const uint64_t mw = mw_nxt;
-    if (PIPE) e2 = tiles_s[it + 2];
     __builtin_amdgcn_s_waitcnt(0);  // this wave's asynchronous tile copies of the previous iteration have landed
     __syncthreads();                // ... and everyone's; every wave is also done with the buffers refilled below
     __bf16* const k_cur = PB ? k_s1 : k_s0;
     __bf16* const k_oth = PB ? k_s0 : k_s1;
     __bf16* const v_cur = PB ? v_s1 : v_s0;
     __bf16* const v_oth = PB ? v_s0 : v_s1;
-    if (PIPE) {
-      if (e2 != kNoTile) load_tile_async(Kg, tile_of(e2), k_cur, KBLK);  // K two tiles ahead replaces K(e0)
-      if (e1 != kNoTile) load_tile_async(Vg, tile_of(e1), v_oth, VBLK);  // V(e1) replaces V(previous tile)
-    } else if (e1 != kNoTile) {
+    if (e1 != kNoTile) {
       load_tile_async(Kg, tile_of(e1), k_oth, KBLK);
       load_tile_async(Vg, tile_of(e1), v_oth, VBLK);
+      if ((e1 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e1) * N];
     }
-    if (e1 != kNoTile && (e1 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e1) * N];
-
-    if (!PIPE) qk(k_cur, s_in);
+    f32x16 s[2];
+    qk(k_cur, s);
 
     // ---- element mask (only where the schedule cannot rule out zeros): keep s where the bit is set, else -inf
     if ((e0 >> 31) == 0) {
@@ -312,16 +316,16 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
         for (int e = 0; e < 16; ++e) {
           const int bit = 8 * (e / 4) + (e % 4);
           const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);  // all ones iff the bit is set
-          s_in[kb][e] = __uint_as_float((__float_as_uint(s_in[kb][e]) & keep) | (0xff800000u & ~keep));
+          s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
         }
       }
     }
 
     // ---- row maximum of this lane's query row
-    float mx = s_in[0][0];
+    float mx = s[0][0];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s_in[kb][e]);
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
     mx = partner_max(mx);
     // The reference maximum m_run only moves when some row's maximum grew by more than kLazy (in log2 units):
     // softmax is invariant to the reference, probabilities stay <= 2^kLazy, and the rescale of O is skipped.
@@ -336,17 +340,13 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
         for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
     }
 
-    // ---- scores of the NEXT tile (matrix pipe) alongside the exponentials of this one (vector pipe)
-    if (PIPE) qk(k_oth, s_out);  // K(e1); harmless stale data if there is no next tile
-
     const float msc = ((m_run == -INFINITY) ? 0.0f : m_run) * c;
-    const __bf16* vs = v_cur;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       bf16x8 pf;
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        pf[e] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s_in[u / 2][8 * (u % 2) + e], c, -msc));
+        pf[e] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[u / 2][8 * (u % 2) + e], c, -msc));
       // row sum of the ROUNDED probabilities (the same numbers the second product consumes), two per instruction
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
@@ -355,71 +355,193 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       }
       // ---- O^T += V^T P^T
 #pragma unroll
-      for (int db = 0; db < DB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(vs, u, db), pf, oacc[db], 0, 0, 0);
+      for (int db = 0; db < DB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(v_cur, u, db), pf, oacc[db], 0, 0, 0);
     }
     e0 = e1;
-    e1 = e2;
-    if (!PIPE) e2 = tiles_s[it + 3];
+    e1 = tiles_s[it + 2];
   };
 
-  const int nwin = num_windows(P, m, i);
-  for (int win = 0; win < nwin; ++win) {
-    const int count = build_window<NW>(P, m, i, win, tiles_s, cnt_s);
-    if (count == 0) continue;
-
-    // ---- pipeline fill
+  // Runs the tiles listed in tiles_s[0 .. count) (followed by sentinels) through the pipeline.
+  auto run_window = [&](int count) {
     e0 = tiles_s[0];
     e1 = tiles_s[1];
-    e2 = tiles_s[2];
-    f32x16 s_a[2], s_b[2];
     mw_nxt = 0;
     load_tile_async(Kg, tile_of(e0), k_s0, KBLK);
     load_tile_async(Vg, tile_of(e0), v_s0, VBLK);
-    if (PIPE && e1 != kNoTile) load_tile_async(Kg, tile_of(e1), k_s1, KBLK);
     if ((e0 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e0) * N];
-    if (PIPE) {
-      __builtin_amdgcn_s_waitcnt(0);
-      __syncthreads();
-      qk(k_s0, s_a);
-    }
-
     for (int it = 0; it < count; it += 2) {
-      step(IntC<0>{}, s_a, s_b, it);
-      if (it + 1 < count) step(IntC<1>{}, s_b, s_a, it + 1);
+      step(IntC<0>{}, it);
+      if (it + 1 < count) step(IntC<1>{}, it + 1);
     }
-    __syncthreads();  // the next window rewrites the tile list and the K/V buffers
-  }
+    __syncthreads();  // whoever comes next rewrites the tile list and the K/V buffers
+  };
 
-  // ---- epilogue: normalise, round to bf16, store; fully masked rows give O = 0, lse = -inf
-  const float l_tot = partner_sum(l_run);
-  const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
-  if (q_ok) {
-    __bf16* og = P.o + head_off + qrow * D;
+  // normalise, round to bf16, store; fully masked rows give O = 0, lse = -inf
+  auto write_output = [&]() {
+    const float l_tot = partner_sum(l_run);
+    const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+    if (q_ok) {
+      __bf16* og = P.o + head_off + qrow * D;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
+      for (int db = 0; db < DB; ++db) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 ov;
-        for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(oacc[db][4 * g + e] * inv);
-        *reinterpret_cast<bf16x4*>(og + 32 * db + 8 * g + 4 * hh) = ov;
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 ov;
+          for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(oacc[db][4 * g + e] * inv);
+          *reinterpret_cast<bf16x4*>(og + 32 * db + 8 * g + 4 * hh) = ov;
+        }
+      }
+      if (P.lse && hh == 0)
+        P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * P.scale + __logf(l_tot) : -INFINITY;
+    }
+  };
+
+  const int split_T = SCHED ? P.sched[bbm::kSchedSplitT] : 0;  // requested early: needed only after other loads
+  // ---- LIST mode, the first n_extra work-groups: before their own block row they serve the queue of cut-row parts
+  // (nothing to do, and no cost, when the schedule cut no row)
+  if (SCHED && (int)blockIdx.x < P.n_extra) {
+    const int32_t* __restrict__ S = P.sched;
+  const int nparts_all = S[bbm::kSchedNParts];
+  const int n_items = nparts_all * P.hbp;
+  // The first item of a work-group is its own index; later ones come from the queue counter, which therefore stands
+  // for "n_extra items already handed out".
+  int item = blockIdx.x;
+  while (item < n_items) {
+    int next_item = 0;
+    if (tid == 0) next_item = P.n_extra + atomicAdd(P.queue, 1);  // asked now, needed after this item
+    const int hb = item / nparts_all;
+    const int32_t* seg = S + bbm::kSchedPartBase + (int64_t)bbm::kSchedPartInts * (item - hb * nparts_all);
+    const int row = seg[0], p0 = seg[1], nt = seg[2], part = seg[3], nparts = seg[4], q_first = seg[5], rho = seg[6];
+    m = row / P.nbr;
+    i = row - m * P.nbr;
+    bh = (P.Mb == 1) ? hb : m * P.H + hb;
+    begin_item();
+
+    const uint32_t* __restrict__ list = P.col_idx + (int64_t)m * P.nbr * P.nbc + p0;
+    for (int w0 = 0; w0 < nt; w0 += kWin) {
+      const int count = min(kWin, nt - w0);
+      for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
+      if (tid < 3) tiles_s[count + tid] = kNoTile;
+      __syncthreads();
+      run_window(count);
+    }
+
+    {
+      // ---- park the unnormalised partial result; the last part of the row to arrive merges them all
+      float* rec = P.partials + ((int64_t)(q_first + part) * P.hbp + hb) * ((REGS + 2) * NT) + tid;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        for (int e = 0; e < 16; ++e) rec[(db * 16 + e) * NT] = oacc[db][e];
+      rec[REGS * NT] = m_run;
+      rec[(REGS + 1) * NT] = l_run;
+      __threadfence();
+      __syncthreads();
+      if (tid == 0) item_s[1] = atomicAdd(P.queue + 8 + rho * P.hbp + hb, 1);
+      __syncthreads();
+      const bool last = item_s[1] == nparts - 1;
+      if (last) {
+        __threadfence();
+        const float* r0 = P.partials + ((int64_t)q_first * P.hbp + hb) * ((REGS + 2) * NT) + tid;
+        const int64_t pstride = (int64_t)P.hbp * ((REGS + 2) * NT);
+        float m_all = -INFINITY;
+        for (int k = 0; k < nparts; ++k) m_all = fmaxf(m_all, r0[k * pstride + REGS * NT]);
+        const float m_fin = (m_all == -INFINITY) ? 0.0f : m_all;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
+        l_run = 0.0f;
+        for (int k = 0; k < nparts; ++k) {  // fixed order: the result does not depend on which part came last
+          const float* rk = r0 + k * pstride;
+          const float wgt = __builtin_amdgcn_exp2f((rk[REGS * NT] - m_fin) * c);
+          l_run += wgt * rk[(REGS + 1) * NT];
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+            for (int e = 0; e < 16; ++e) oacc[db][e] += wgt * rk[(db * 16 + e) * NT];
+        }
+        m_run = m_all;
+        write_output();
       }
     }
-    if (P.lse && hh == 0)
-      P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * P.scale + __logf(l_tot) : -INFINITY;
+
+    if (tid == 0) item_s[0] = next_item;
+    __syncthreads();
+    item = item_s[0];
+    __syncthreads();  // everyone has read the item before thread 0 may publish another one
+  }
+  }
+
+  {
+    // Work-groups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of logical ids so the
+    // row blocks of one head (which share K and V) meet in one XCD's L2.
+    const int wg = (int)blockIdx.x;
+    const int T = P.total_wgs;
+    const int xcd = wg & 7, slot = wg >> 3;
+    const int per = T >> 3, rem = T & 7;
+    const int logical = xcd * per + (xcd < rem ? xcd : rem) + slot;
+    bh = logical / P.nbr;
+    i = P.nbr - 1 - (logical - bh * P.nbr);  // late (for causal-like masks: long) block rows first
+    m = (P.Mb == 1) ? 0 : bh / P.H;
+    int n_list = 0;
+    if (SCHED) {  // a row the schedule cut belongs to the queue (the loads overlap with those of begin_item)
+      const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
+      n_list = rp[1] - rp[0];
+    }
+    begin_item();
+    if (!(SCHED && n_list > split_T)) {
+      const int nwin = num_windows(P, m, i);
+      for (int win = 0; win < nwin; ++win) {
+        const int count = build_window<NW>(P, m, i, win, tiles_s, cnt_s);
+        if (count > 0) run_window(count);
+      }
+      write_output();
+    }
   }
 }
 
+
+__global__ void zero_ints_kernel(int32_t* p, int n) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n) p[t] = 0;
+}
+
+// Leading work-groups that serve the queue of cut-row parts before their own block row (LIST mode).
+constexpr int kExtraWGs = 256;
+
+constexpr size_t kQueueAlign = 256;
+inline size_t queue_bytes(int64_t Mb, int64_t nbr, int64_t hbp) {
+  const size_t n = (size_t)(8 + Mb * nbr * hbp) * sizeof(int32_t);
+  return (n + kQueueAlign - 1) / kQueueAlign * kQueueAlign;
+}
+inline size_t partial_bytes(int64_t Mb, int64_t nbr, int64_t hbp, int d, int Br) {
+  // at most Mb*nbr cut parts exist (T >= 2 * mean list length); one record per (cut part, head-batch)
+  return (size_t)(Mb * nbr * hbp) * (size_t)((d / 32 * 16 + 2) * (Br * 2)) * sizeof(float);
+}
+
 template <int D, int NW>
-int launch(const AttnParams& P, hipStream_t s) {
-  attn_fwd_kernel<D, NW, false><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+int launch(AttnParams& P, int64_t Mb, void* workspace, hipStream_t s) {
+  if (P.mode == BBM_MODE_LIST) {
+    P.queue = static_cast<int32_t*>(workspace);
+    P.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + queue_bytes(Mb, P.nbr, P.hbp));
+    const int nq = (int)(8 + Mb * P.nbr * P.hbp);
+    zero_ints_kernel<<<(nq + 255) / 256, 256, 0, s>>>(P.queue, nq);
+    int rc = bbm::launch_status("bbm_attn_fwd(queue reset)");
+    if (rc) return rc;
+    P.n_extra = P.total_wgs < kExtraWGs ? P.total_wgs : kExtraWGs;
+    attn_fwd_kernel<D, NW, true><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+  } else {
+    attn_fwd_kernel<D, NW, false><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+  }
   return bbm::launch_status("bbm_attn_fwd");
 }
 
 }  // namespace
 
 extern "C" __attribute__((visibility("default"))) size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int Br, int Bc, int mode) {
-  (void)B; (void)H; (void)N; (void)d; (void)Br; (void)Bc; (void)mode;
-  return 0;
+  if (B < 1 || H < 1 || N < 1 || Br < 1 || Bc < 1 || (d != 64 && d != 128)) return 0;
+  if (mode != BBM_MODE_LIST && mode != BBM_MODE_AUTO) return 0;
+  // sized for the larger of the two plane counts a caller may use (Mb = 1 or Mb = B): both give Mb*hbp = B*H
+  const int64_t nbr = (N + Br - 1) / Br;
+  return queue_bytes(1, nbr, B * H) + partial_bytes(1, nbr, B * H, d, Br);
 }
 
 extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H,
@@ -427,7 +549,6 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
                             const bbm_index* idx, int mode, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace bbm;
   clear_error();
-  (void)workspace;
   if (!q || !k || !v || !o) return fail(BBM_EINVAL, "bbm_attn_fwd: q, k, v, o must not be NULL");
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16))
     return fail(BBM_EINVAL, "bbm_attn_fwd: q, k, v, o must be 16-byte aligned");
@@ -445,7 +566,7 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
     return fail(BBM_EINVAL, "bbm_attn_fwd: index (Mb=%lld, nbr=%lld, nbc=%lld) does not match the problem (Mb=%lld, nbr=%lld, nbc=%lld)",
                 (long long)idx->Mb, (long long)idx->nbr, (long long)idx->nbc, (long long)Mb, (long long)nbr, (long long)nbc);
   if (mode == BBM_MODE_AUTO)
-    mode = (idx->row_ptr && idx->col_idx) ? BBM_MODE_LIST
+    mode = (idx->row_ptr && idx->col_idx && idx->sched) ? BBM_MODE_LIST
            : (idx->bin_blk_mat && idx->offset && idx->total_ones && idx->nz_lo && idx->nz_hi) ? BBM_MODE_RUNS
                                                                                               : BBM_MODE_BITMAP;
   switch (mode) {
@@ -457,7 +578,8 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
         return fail(BBM_EINVAL, "bbm_attn_fwd: RUNS mode needs bin_blk_mat, offset, total_ones, nz_lo, nz_hi");
       break;
     case BBM_MODE_LIST:
-      if (!idx->row_ptr || !idx->col_idx) return fail(BBM_EINVAL, "bbm_attn_fwd: LIST mode needs row_ptr and col_idx");
+      if (!idx->row_ptr || !idx->col_idx || !idx->sched)
+        return fail(BBM_EINVAL, "bbm_attn_fwd: LIST mode needs row_ptr, col_idx and sched");
       break;
     case BBM_MODE_DENSE_BASELINE:
       break;
@@ -466,8 +588,10 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
   }
   if (nbr * nbc >= (1ll << 31) || B * H * nbr >= (1ll << 31) || N >= (1ll << 31))
     return fail(BBM_EUNSUPPORTED, "bbm_attn_fwd: problem too large for 32-bit tile counters");
-  if (workspace_bytes < bbm_attn_fwd_workspace_bytes(B, H, N, d, idx->Br, idx->Bc, mode))
-    return fail(BBM_EWORKSPACE, "bbm_attn_fwd: workspace too small");
+  const size_t need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx->Br, idx->Bc, mode);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(BBM_EWORKSPACE, "bbm_attn_fwd: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+  if (need > 0 && !aligned(workspace, 16)) return fail(BBM_EINVAL, "bbm_attn_fwd: workspace must be 16-byte aligned");
 
   AttnParams P;
   P.q = static_cast<const __bf16*>(q);
@@ -492,13 +616,18 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
   P.total_wgs = (int32_t)(B * H * nbr);
   P.mode = mode;
   P.scale = softmax_scale;
+  P.sched = idx->sched;
+  P.queue = nullptr;
+  P.partials = nullptr;
+  P.hbp = (int32_t)(Mb == 1 ? B * H : H);
+  P.n_extra = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (d == 64) {
-    if (idx->Br == 64) return launch<64, 2>(P, s);
-    if (idx->Br == 128) return launch<64, 4>(P, s);
-    return launch<64, 8>(P, s);
+    if (idx->Br == 64) return launch<64, 2>(P, Mb, workspace, s);
+    if (idx->Br == 128) return launch<64, 4>(P, Mb, workspace, s);
+    return launch<64, 8>(P, Mb, workspace, s);
   }
-  if (idx->Br == 64) return launch<128, 2>(P, s);
-  if (idx->Br == 128) return launch<128, 4>(P, s);
-  return launch<128, 8>(P, s);
+  if (idx->Br == 64) return launch<128, 2>(P, Mb, workspace, s);
+  if (idx->Br == 128) return launch<128, 4>(P, Mb, workspace, s);
+  return launch<128, 8>(P, Mb, workspace, s);
 }

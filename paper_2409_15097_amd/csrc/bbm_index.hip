@@ -120,6 +120,99 @@ __global__ __launch_bounds__(kWavesPerWG * 64) void list_fill_kernel(const uint8
   }
 }
 
+// Split schedule of LIST mode (layout in bbm_internal.h).  One work-group; every thread owns a contiguous range of
+// block rows.  Pass 1 counts, per thread, the parts and the cut rows; an exclusive scan over the threads turns the
+// counts into positions; pass 2 writes the parts in (row, part) order, so the result does not depend on the thread
+// count.
+constexpr int kSchedThreads = 256;
+
+__global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __restrict__ row_ptr, int Mb, int nbr,
+                                                              int32_t* __restrict__ sched) {
+  using namespace bbm;
+  __shared__ int pre[2][kSchedThreads + 1];
+  __shared__ int red[2][kSchedThreads];
+  const int tid = threadIdx.x;
+  const int nrows = Mb * nbr;
+  const int per = (nrows + kSchedThreads - 1) / kSchedThreads;
+  const int r_lo = min(nrows, tid * per), r_hi = min(nrows, r_lo + per);
+  auto first_entry = [&](int r) {
+    const int m = r / nbr, i = r - m * nbr;
+    return row_ptr + (int64_t)m * (nbr + 1) + i;
+  };
+
+  // split threshold from the mean list length of the non-empty rows
+  int total = 0, nonempty = 0;
+  for (int r = r_lo; r < r_hi; ++r) {
+    const int32_t* rp = first_entry(r);
+    const int c = rp[1] - rp[0];
+    total += c;
+    nonempty += c > 0;
+  }
+  red[0][tid] = total;
+  red[1][tid] = nonempty;
+  __syncthreads();
+  for (int s = kSchedThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) {
+      red[0][tid] += red[0][tid + s];
+      red[1][tid] += red[1][tid + s];
+    }
+    __syncthreads();
+  }
+  total = red[0][0];
+  nonempty = red[1][0];
+  const int mean = nonempty > 0 ? (total + nonempty - 1) / nonempty : 0;
+  const int T = max(kSchedMinSplit, 2 * mean);
+
+  int nparts = 0, ncut = 0;
+  for (int r = r_lo; r < r_hi; ++r) {
+    const int32_t* rp = first_entry(r);
+    const int c = rp[1] - rp[0];
+    if (c > T) {
+      nparts += (c + T - 1) / T;
+      ncut += 1;
+    }
+  }
+  pre[0][tid + 1] = nparts;
+  pre[1][tid + 1] = ncut;
+  if (tid == 0) pre[0][0] = pre[1][0] = 0;
+  __syncthreads();
+  if (tid < 2) {  // one thread per column: serial inclusive scan over 256 entries
+    int run = 0;
+    for (int t = 1; t <= kSchedThreads; ++t) {
+      run += pre[tid][t];
+      pre[tid][t] = run;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    sched[kSchedNParts] = pre[0][kSchedThreads];
+    sched[kSchedSplitT] = T;
+    sched[kSchedNCutRows] = pre[1][kSchedThreads];
+    for (int x = 3; x < kSchedPartBase; ++x) sched[x] = 0;
+  }
+  int q = pre[0][tid], rho = pre[1][tid];
+  for (int r = r_lo; r < r_hi; ++r) {
+    const int32_t* rp = first_entry(r);
+    const int c = rp[1] - rp[0];
+    if (c <= T) continue;
+    const int np = (c + T - 1) / T;
+    const int chunk = (c + np - 1) / np;
+    for (int k = 0; k < np; ++k) {
+      int32_t* rec = sched + kSchedPartBase + (int64_t)kSchedPartInts * (q + k);
+      rec[0] = r;
+      rec[1] = rp[0] + k * chunk;
+      rec[2] = min(chunk, c - k * chunk);
+      rec[3] = k;
+      rec[4] = np;
+      rec[5] = q;
+      rec[6] = rho;
+      rec[7] = 0;
+    }
+    q += np;
+    rho += 1;
+  }
+}
+
 }  // namespace
 
 extern "C" __attribute__((visibility("default"))) int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset,
@@ -138,15 +231,21 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_runs(const uint8
   return launch_status("bbm_build_runs");
 }
 
+extern "C" __attribute__((visibility("default"))) size_t bbm_sched_bytes(int64_t Mb, int64_t nbr) {
+  if (Mb < 1 || nbr < 1) return 0;
+  return (size_t)bbm::sched_ints(Mb, nbr) * sizeof(int32_t);
+}
+
 extern "C" __attribute__((visibility("default"))) int bbm_build_sparse_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc,
-                                      int32_t* row_ptr, uint32_t* col_idx, void* stream) {
+                                      int32_t* row_ptr, uint32_t* col_idx, int32_t* sched, void* stream) {
   using namespace bbm;
   clear_error();
   if (!blk_class || !row_ptr || !col_idx) return fail(BBM_EINVAL, "bbm_build_sparse_index: NULL pointer argument");
   if (Mb < 1 || nbr < 1 || nbc < 1)
     return fail(BBM_EINVAL, "bbm_build_sparse_index: Mb=%lld, nbr=%lld, nbc=%lld must be >= 1", (long long)Mb, (long long)nbr, (long long)nbc);
-  if (nbr * nbc >= (1ll << 31) || Mb > (1ll << 30) || Mb * nbr > (1ll << 31) * kWavesPerWG - 1)
-    return fail(BBM_EUNSUPPORTED, "bbm_build_sparse_index: nbr*nbc=%lld must be < 2^31", (long long)(nbr * nbc));
+  if (nbr * nbc >= (1ll << 31) || Mb * nbr >= (1ll << 24))
+    return fail(BBM_EUNSUPPORTED, "bbm_build_sparse_index: needs nbr*nbc=%lld < 2^31 and Mb*nbr=%lld < 2^24", (long long)(nbr * nbc), (long long)(Mb * nbr));
+  if (sched && !aligned(sched, 32)) return fail(BBM_EINVAL, "bbm_build_sparse_index: sched must be 32-byte aligned");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const unsigned grid = (unsigned)ceil_div(Mb * nbr, kWavesPerWG);
   list_count_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr);
@@ -156,5 +255,8 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_sparse_index(con
   rc = launch_status("bbm_build_sparse_index(scan)");
   if (rc) return rc;
   list_fill_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr, col_idx);
-  return launch_status("bbm_build_sparse_index(fill)");
+  rc = launch_status("bbm_build_sparse_index(fill)");
+  if (rc || !sched) return rc;
+  sched_kernel<<<1, kSchedThreads, 0, s>>>(row_ptr, (int)Mb, (int)nbr, sched);
+  return launch_status("bbm_build_sparse_index(schedule)");
 }

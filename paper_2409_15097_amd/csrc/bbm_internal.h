@@ -23,4 +23,17 @@ inline int launch_status(const char* what) {
   return BBM_OK;
 }
 
+// Layout of the split schedule that bbm_build_sparse_index writes and bbm_attn_fwd (LIST mode) reads; int32 units.
+//   [kSchedNParts]           number of parts (0 if no block row was cut)
+//   [kSchedSplitT]           split threshold T: block rows with more than T list entries are cut into parts
+//   [kSchedNCutRows]         number of block rows that were cut
+//   [kSchedPartBase + 8*q]   part q (ordered by row, then part): row (= plane*nbr + block row), first entry in the
+//                            plane's list, entries, part index, parts of the row, q of the row's first part, index
+//                            of the row among the cut rows, unused
+constexpr int kSchedNParts = 0, kSchedSplitT = 1, kSchedNCutRows = 2;
+constexpr int kSchedPartBase = 8;
+constexpr int kSchedPartInts = 8;
+constexpr int kSchedMinSplit = 32;
+inline int64_t sched_ints(int64_t Mb, int64_t nbr) { return kSchedPartBase + kSchedPartInts * Mb * nbr; }
+
 }  // namespace bbm

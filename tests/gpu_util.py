@@ -21,6 +21,7 @@ def index_to_numpy(idx):
         t = getattr(idx, name)
         out[name] = None if t is None else t.cpu().numpy()
     out["col_idx"] = None if idx.col_idx is None else idx.col_idx.cpu().numpy().view(np.uint32)
+    out["sched"] = None if idx.sched is None else idx.sched.cpu().numpy()
     out["packed_mask"] = None if idx.packed_mask is None else idx.packed_mask.cpu().numpy().view(np.uint64)
     return out
 
@@ -41,6 +42,9 @@ def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
             n = int(want["row_ptr"][m, -1])
             lo = m * nbr * nbc
             assert np.array_equal(got["col_idx"][lo:lo + n], want["col_idx"][lo:lo + n])
+    if got.get("sched") is not None:
+        n = oracle.blocks.SCHED_PART_BASE + oracle.blocks.SCHED_PART_INTS * int(want["sched"][0])
+        assert np.array_equal(got["sched"][:n], want["sched"][:n])
     if got["packed_mask"] is not None:
         assert np.array_equal(got["packed_mask"], oracle.packed_bits(mask))
 

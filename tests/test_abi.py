@@ -20,7 +20,7 @@ def test_every_declared_symbol_is_exported(bbm):
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(bbm_[a-z_]+)\s*\(", hdr))
     assert names == {"bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs",
-                     "bbm_build_sparse_index", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"}
+                     "bbm_build_sparse_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"}
     raw = C.CDLL(bbm.library_path())
     for n in names:
         assert getattr(raw, n) is not None
@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(bbm):
 
 def test_binding_has_the_same_names(bbm):
     for n in ("bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs", "bbm_build_sparse_index",
-              "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"):
+              "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"):
         assert callable(getattr(bbm, n))
 
 
@@ -55,14 +55,16 @@ def test_index_builders_reject_bad_arguments(bbm):
     assert L.bbm_build_runs(None, 1, 4, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == bbm.BBM_EINVAL
     assert L.bbm_build_runs(FAKE, 1, 4, 4, FAKE, None, FAKE, FAKE, FAKE, None) == bbm.BBM_EINVAL
     assert L.bbm_build_runs(FAKE, 1, 0, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == bbm.BBM_EINVAL
-    assert L.bbm_build_sparse_index(FAKE, 1, 4, 4, None, FAKE, None) == bbm.BBM_EINVAL
-    assert L.bbm_build_sparse_index(FAKE, 1, 4, 0, FAKE, FAKE, None) == bbm.BBM_EINVAL
-    assert L.bbm_build_sparse_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None) == bbm.BBM_EUNSUPPORTED
+    assert L.bbm_build_sparse_index(FAKE, 1, 4, 4, None, FAKE, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_sparse_index(FAKE, 1, 4, 0, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_sparse_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None, None) == bbm.BBM_EUNSUPPORTED
+    assert L.bbm_build_sparse_index(FAKE, 1, 4, 4, FAKE, FAKE, C.c_void_p(0x1004), None) == bbm.BBM_EINVAL
+    assert bbm.bbm_sched_bytes(1, 4) == 4 * (8 + 8 * 4) and bbm.bbm_sched_bytes(0, 4) == 0
 
 
 def _idx(bbm, Br=128, Bc=64, Mb=1, N=256, **ptrs):
     from paper_2409_15097_amd.binding import _CIndex
-    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), *([None] * 9))
+    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), *([None] * 10))
     for k, v in ptrs.items():
         setattr(s, k, v)
     return s
@@ -97,5 +99,11 @@ def test_attn_fwd_rejects_bad_arguments(bbm):
     assert _attn(bbm, idx, mode=bbm.BBM_MODE_AUTO) == bbm.BBM_EINVAL          # AUTO falls back to BITMAP, which needs bin_blk_mat
 
 
-def test_workspace_query(bbm):
-    assert bbm.bbm_attn_fwd_workspace_bytes(4, 16, 4096, 64, 128, 64, bbm.BBM_MODE_LIST) >= 0
+def test_workspace_query_and_check(bbm):
+    need = bbm.bbm_attn_fwd_workspace_bytes(4, 16, 4096, 64, 128, 64, bbm.BBM_MODE_LIST)
+    assert need > 0 and need == bbm.bbm_attn_fwd_workspace_bytes(4, 16, 4096, 64, 128, 64, bbm.BBM_MODE_AUTO)
+    assert bbm.bbm_attn_fwd_workspace_bytes(4, 16, 4096, 64, 128, 64, bbm.BBM_MODE_BITMAP) == 0
+    assert bbm.bbm_attn_fwd_workspace_bytes(0, 16, 4096, 64, 128, 64, bbm.BBM_MODE_LIST) == 0
+    idx = _idx(bbm, row_ptr=0x2000, col_idx=0x3000, sched=0x4000)
+    assert _attn(bbm, idx, mode=bbm.BBM_MODE_LIST) == bbm.BBM_EWORKSPACE          # no workspace given
+    assert "workspace" in bbm.bbm_last_error()

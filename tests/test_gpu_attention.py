@@ -47,9 +47,11 @@ def test_small_variants_all_modes(name, N, B, H, Br):
         o, lse = _gpu_attn(cfg, Br, mode)
         assert_attention_close(o, lse, O_ref, lse_ref)
         outs[mode] = (o, lse)
-    # same tile visit order and same arithmetic in every schedule that skips only all-masked tiles
-    for mode in ("RUNS", "LIST", "AUTO"):
-        assert torch.equal(outs[mode][0].view(torch.int16), outs["BITMAP"][0].view(torch.int16)), mode
+    # same tile visit order and same arithmetic in the schedules that walk a whole block row in one work-group
+    assert torch.equal(outs["RUNS"][0].view(torch.int16), outs["BITMAP"][0].view(torch.int16))
+    # AUTO is LIST; LIST may cut long rows into parts, which only changes the rounding order
+    assert torch.equal(outs["AUTO"][0].view(torch.int16), outs["LIST"][0].view(torch.int16))
+    assert torch.equal(outs["AUTO"][1], outs["LIST"][1])
 
 
 @pytest.mark.parametrize("N", [200, 333, 77, 1, 65, 1000])
@@ -62,7 +64,7 @@ def test_ragged_sizes_with_empty_rows(N, d):
     m[rng.integers(0, N, size=max(1, N // 10))] = 0        # fully masked rows
     cfg = dict(q=q, k=k, v=v, mask=np.stack([m, np.roll(m, 3, axis=1)]))
     O_ref, lse_ref = oracle.masked_attention(q, k, v, cfg["mask"])
-    for Br in (64, 128):
+    for Br in (64, 128, 256):
         for mode in MODES:
             print(f"ragged N={N} d={d} Br={Br} mode={mode}", flush=True)
             o, lse = _gpu_attn(cfg, Br, mode)
@@ -142,7 +144,7 @@ def test_full_size_sampled_rows(name):
         fin = np.isfinite(lse_ref)
         assert np.array_equal(np.isfinite(lg), fin) and np.abs(lg[fin] - lse_ref[fin]).max() <= LSE_MAX_ABS
         assert not torch.isnan(o.float()).any()
-        if Br == 128:
+        if Br == 128 and mode in ("RUNS", "BITMAP"):
             bits = o.view(torch.int16)
             if ref_bits is None:
                 ref_bits = bits.clone()

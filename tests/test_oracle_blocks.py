@@ -157,3 +157,37 @@ def test_skip_rule_matches_paper_wording():
             inside = o <= j < o + t
             if idx["bin_blk_mat"][0, i, j] and not inside and idx["cls"][0, i, j] == 2:
                 assert t >= 1            # a full block outside the run exists only if a longer/equal run was kept
+
+
+def test_schedule_cuts_only_long_rows():
+    # rows with 3, 0, 40, 5 entries: mean of non-empty = 16 -> T = 32 -> only the 40-entry row is cut, into 2 x 20
+    rp = np.array([[0, 3, 3, 43, 48]], dtype=np.int32)
+    s = oracle.schedule(rp)
+    assert (s[0], s[1], s[2]) == (2, 32, 1) and not s[3:8].any()
+    assert s[8:24].reshape(2, 8).tolist() == [[2, 3, 20, 0, 2, 0, 0, 0], [2, 23, 20, 1, 2, 0, 0, 0]]
+    # the floor of the threshold: rows of 1, 33 -> mean 17 -> T = 34: nothing cut; rows 1, 1, 1, 40 -> T = 32: 40 cut
+    assert oracle.schedule(np.array([[0, 1, 34]], dtype=np.int32))[:3].tolist() == [0, 34, 0]
+    assert oracle.schedule(np.array([[0, 1, 2, 3, 43]], dtype=np.int32))[:3].tolist() == [2, 32, 1]
+    assert oracle.schedule(np.array([[0, 5, 10, 15]], dtype=np.int32))[0] == 0          # uniform rows: nothing cut
+
+
+def test_schedule_parts_tile_each_cut_row_exactly():
+    rng = np.random.default_rng(0)
+    counts = rng.integers(0, 300, size=(3, 37))
+    counts[rng.random(counts.shape) < 0.6] //= 20
+    rp = np.zeros((3, 38), dtype=np.int32)
+    rp[:, 1:] = np.cumsum(counts, axis=1)
+    s = oracle.schedule(rp)
+    nparts, T, ncut = int(s[0]), int(s[1]), int(s[2])
+    assert T == max(32, 2 * -(-int(counts.sum()) // int((counts > 0).sum())))
+    parts = s[8:8 + 8 * nparts].reshape(nparts, 8)
+    covered = np.zeros(counts.shape, dtype=np.int64)
+    for q, (r, first, nt, k, np_, qf, rho, _) in enumerate(parts):
+        m, i = divmod(int(r), 37)
+        assert counts[m, i] > T and np_ == -(-counts[m, i] // T) and 1 <= nt <= T and q == qf + k
+        assert first == rp[m, i] + covered[m, i]            # parts are consecutive slices of the row's list
+        covered[m, i] += nt
+    cut = counts > T
+    assert np.array_equal(covered[cut], counts[cut]) and not covered[~cut].any()
+    assert ncut == int(cut.sum()) and nparts <= counts.size          # the bound the workspace size relies on
+    assert sorted(set(parts[:, 6].tolist())) == list(range(ncut))
