@@ -126,6 +126,9 @@ int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nb
  *                    parts.  int32 layout: [0] parts, [1] T, [2] cut rows, [3..7] 0, then 8 ints per part ordered by
  *                    (row, part): plane*nbr + block row, first entry (position in the plane's list), entries, part,
  *                    parts of the row, number of the row's first part, index of the row among the cut rows, 0.
+ *                    The last Mb*nbr ints list, per plane, the block rows by list length, longest first (ties: higher
+ *                    row first; planes with more than 4096 block rows: simply last row first): the order in which
+ *                    LIST mode starts work-groups.
  *                    It depends only on the mask, so it is shared by heads, layers and calls like the rest of the
  *                    index.
  * Requires nbr*nbc < 2^31 and Mb*nbr < 2^24.  Errors: BBM_EINVAL, BBM_EHIP.

@@ -105,24 +105,33 @@ def packed_bits(mask):
 SCHED_PART_BASE = 8
 SCHED_PART_INTS = 8
 SCHED_MIN_SPLIT = 32
+SCHED_MAX_SORT_ROWS = 4096
 
 
 def schedule(row_ptr):
     """Split schedule of the list mode (this build's own layout, stated in the library header).
 
-    row_ptr int32 [Mb, nbr+1] -> int32 array of 8 + 8*Mb*nbr entries: [0] parts, [1] split threshold
+    row_ptr int32 [Mb, nbr+1] -> int32 array of 8 + 9*Mb*nbr entries: [0] parts, [1] split threshold
     T = max(32, 2*ceil(mean list length of the non-empty rows)), [2] cut rows, [3..7] 0, then 8 ints per part in
     (row, part) order: row (= plane*nbr + block row), first entry (position in the plane's list), entries, part,
     parts of the row, number of the row's first part, index of the row among the cut rows, 0.
     A row with n > T entries is cut into ceil(n/T) parts of ceil(n/parts) entries (the last part takes the rest);
-    rows with n <= T are not listed.  Entries past the last part are unspecified."""
+    rows with n <= T are not listed.  Table entries past the last part are unspecified.  The last Mb*nbr entries
+    give, per plane, the block rows ordered by list length, longest first, ties broken towards the higher row
+    (planes of more than 4096 block rows are listed from the last row to the first instead)."""
     Mb, nbr1 = row_ptr.shape
     nbr = nbr1 - 1
     counts = [int(row_ptr[m, i + 1] - row_ptr[m, i]) for m in range(Mb) for i in range(nbr)]
     nonempty = sum(1 for c in counts if c > 0)
     mean = -(-sum(counts) // nonempty) if nonempty else 0
     T = max(SCHED_MIN_SPLIT, 2 * mean)
-    out = np.zeros(SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbr, dtype=np.int32)
+    out = np.zeros(SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbr + Mb * nbr, dtype=np.int32)
+    order_base = SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbr
+    for m in range(Mb):
+        rows = list(range(nbr - 1, -1, -1))
+        if nbr <= SCHED_MAX_SORT_ROWS:
+            rows.sort(key=lambda i: -counts[m * nbr + i])        # stable: equal lengths stay in descending row order
+        out[order_base + m * nbr:order_base + (m + 1) * nbr] = rows
     q, rho = 0, 0
     for r, c in enumerate(counts):
         if c <= T:

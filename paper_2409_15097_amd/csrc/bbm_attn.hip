@@ -479,8 +479,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     const int per = T >> 3, rem = T & 7;
     const int logical = xcd * per + (xcd < rem ? xcd : rem) + slot;
     bh = logical / P.nbr;
-    i = P.nbr - 1 - (logical - bh * P.nbr);  // late (for causal-like masks: long) block rows first
     m = (P.Mb == 1) ? 0 : bh / P.H;
+    // longest rows first: by the schedule's order (LIST), else from the last row up (long first for causal-like masks)
+    const int rank = logical - bh * P.nbr;
+    i = SCHED ? P.sched[bbm::sched_order_base(P.Mb, P.nbr) + m * P.nbr + rank] : P.nbr - 1 - rank;
     int n_list = 0;
     if (SCHED) {  // a row the schedule cut belongs to the queue (the loads overlap with those of begin_item)
       const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;

@@ -211,6 +211,23 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
     q += np;
     rho += 1;
   }
+
+  // longest-list-first order of the block rows of every plane (rank by counting; ties: higher row first)
+  int32_t* order = sched + sched_order_base(Mb, nbr);
+  for (int r = tid; r < nrows; r += kSchedThreads) {
+    const int m = r / nbr, i = r - m * nbr;
+    int rank = nbr - 1 - i;
+    if (nbr <= kSchedMaxSortRows) {
+      const int32_t* rp = row_ptr + (int64_t)m * (nbr + 1);
+      const int c = rp[i + 1] - rp[i];
+      rank = 0;
+      for (int j = 0; j < nbr; ++j) {
+        const int cj = rp[j + 1] - rp[j];
+        rank += (cj > c) || (cj == c && j > i);
+      }
+    }
+    order[m * nbr + rank] = i;
+  }
 }
 
 }  // namespace

@@ -169,6 +169,9 @@ def test_schedule_cuts_only_long_rows():
     assert oracle.schedule(np.array([[0, 1, 34]], dtype=np.int32))[:3].tolist() == [0, 34, 0]
     assert oracle.schedule(np.array([[0, 1, 2, 3, 43]], dtype=np.int32))[:3].tolist() == [2, 32, 1]
     assert oracle.schedule(np.array([[0, 5, 10, 15]], dtype=np.int32))[0] == 0          # uniform rows: nothing cut
+    # row order: lengths 3, 0, 40, 5 -> rows 2, 3, 0, 1; equal lengths -> higher row first (causal masks: last row first)
+    assert s[-4:].tolist() == [2, 3, 0, 1]
+    assert oracle.schedule(np.array([[0, 5, 10, 15], [0, 1, 3, 6]], dtype=np.int32))[-6:].tolist() == [2, 1, 0, 2, 1, 0]
 
 
 def test_schedule_parts_tile_each_cut_row_exactly():
