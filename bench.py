@@ -83,7 +83,7 @@ def measure_mask(bbm, name, Br, warmup, steps, torch):
     idx = bbm.build_index(mask, Br, 64)
     out = torch.empty_like(q)
     lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
-    ws = torch.empty(max(16, bbm.bbm_attn_fwd_workspace_bytes(B, H, N, d, Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(max(16, bbm.bbm_attn_fwd_workspace_bytes(B, H, N, d, Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     tiles = visited_tiles(idx, B, H)
     cls = idx.blk_class
@@ -173,7 +173,7 @@ def main():
         q, k, v = (bbm.bf16_from_bits(cfg[x]) for x in "qkv")
         out = torch.empty_like(q)
         lse = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
-        ws = torch.empty(max(16, bbm.bbm_attn_fwd_workspace_bytes(*q.shape, a.Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
+        ws = torch.zeros(max(16, bbm.bbm_attn_fwd_workspace_bytes(*q.shape, a.Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
         src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda").fill_(1)     # 256 MiB copy for counter calibration
         dst = torch.empty_like(src)
         torch.cuda.synchronize()

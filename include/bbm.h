@@ -165,9 +165,11 @@ size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
  *                    LIST: row_ptr, col_idx, sched;  DENSE_BASELINE: none.
  *   mode             BBM_MODE_*.
  *   workspace        device scratch of at least bbm_attn_fwd_workspace_bytes(...) bytes, 16-byte aligned (may be NULL
- *                    if 0).  LIST mode keeps its queue counters and the partial results of cut block rows there;
- *                    contents need not be initialised and are meaningless afterwards.  Two calls that overlap in
- *                    time (different streams) must not share a workspace.
+ *                    if 0).  LIST mode keeps its queue counters and the partial results of cut block rows there.
+ *                    The workspace must be ZERO-FILLED ONCE after it is allocated; every call puts back the zeros it
+ *                    disturbed, so the same workspace can serve any number of later calls (of any shape that fits)
+ *                    without being cleared again.  Two calls that overlap in time (different streams) must not
+ *                    share a workspace.
  * Arithmetic: QK^T and PV on bf16 MFMA with fp32 accumulation; softmax statistics in fp32; P rounded to
  * bf16 before PV.  Deterministic: the same inputs give bit-identical outputs (in LIST mode the parts of a cut row
  * are taken from a queue in whatever order work-groups become free, but each part's arithmetic and the order in

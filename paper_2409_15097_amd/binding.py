@@ -194,7 +194,7 @@ def bbm_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIn
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
     need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx.Br, idx.Bc, mode)
     if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)   # the library wants it zero-filled once
     cs = idx.c_struct()
     _check(lib.bbm_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, N, d, softmax_scale, idx.Mb,
                             _ptr(idx.packed_mask), C.byref(cs), mode, _ptr(workspace),

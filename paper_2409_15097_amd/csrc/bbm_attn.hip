@@ -15,6 +15,8 @@
 // tested with compile-time bit positions.
 #include "bbm_internal.h"
 
+#include <algorithm>
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -48,10 +50,12 @@ struct AttnParams {
   float scale;
   // LIST mode: schedule (read-only), work-queue state and partial results of cut rows (in the caller's workspace)
   const int32_t* sched;
-  int32_t* queue;     // [0] part items handed out, [8 + rho*hbp + hb] finished parts of cut row rho
+  int32_t* queue;     // [0] part items handed out, [1] leading work-groups done, [8 + rho*hbp + hb] finished parts of
+                      // cut row rho; all zero between calls (each call puts back the zeros it disturbed)
   float* partials;    // [(cut part)*hbp + hb][regs + 2][threads]
   int32_t hbp;        // (batch, head) pairs per mask plane: B*H if Mb == 1, else H
   int32_t n_extra;    // leading work-groups that serve the queue of cut-row parts (LIST mode)
+  int32_t G;          // (batch, head) planes whose block rows are interleaved in launch order
 };
 
 __device__ __forceinline__ float partner_max(float x) {
@@ -460,6 +464,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
         }
         m_run = m_all;
         write_output();
+        if (tid == 0) P.queue[8 + rho * P.hbp + hb] = 0;  // last user of this counter: leave it zero for the next call
       }
     }
 
@@ -467,6 +472,11 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     __syncthreads();
     item = item_s[0];
     __syncthreads();  // everyone has read the item before thread 0 may publish another one
+  }
+  // the last leading work-group to leave the queue puts the two queue counters back to zero for the next call
+  if (n_items > 0 && tid == 0 && atomicAdd(P.queue + 1, 1) == P.n_extra - 1) {
+    P.queue[0] = 0;
+    P.queue[1] = 0;
   }
   }
 
@@ -478,10 +488,15 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     const int xcd = wg & 7, slot = wg >> 3;
     const int per = T >> 3, rem = T & 7;
     const int logical = xcd * per + (xcd < rem ? xcd : rem) + slot;
-    bh = logical / P.nbr;
+    // Launch order inside a group of G consecutive (batch, head) planes: rank-major, i.e. the longest row of every
+    // plane of the group, then the second longest of every plane, ...  The hardware starts work-groups in index
+    // order as slots free up, so long rows start early everywhere and the short ones fill the tail.
+    const int grp = logical / (P.G * P.nbr), within = logical - grp * (P.G * P.nbr);
+    const int g_planes = min(P.G, T / P.nbr - grp * P.G);
+    const int rank = within / g_planes;
+    bh = grp * P.G + (within - rank * g_planes);
     m = (P.Mb == 1) ? 0 : bh / P.H;
-    // longest rows first: by the schedule's order (LIST), else from the last row up (long first for causal-like masks)
-    const int rank = logical - bh * P.nbr;
+    // rank -> row, longest first: by the schedule's order (LIST), else from the last row up (long first for causal-like masks)
     i = SCHED ? P.sched[bbm::sched_order_base(P.Mb, P.nbr) + m * P.nbr + rank] : P.nbr - 1 - rank;
     int n_list = 0;
     if (SCHED) {  // a row the schedule cut belongs to the queue (the loads overlap with those of begin_item)
@@ -501,11 +516,6 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
 }
 
 
-__global__ void zero_ints_kernel(int32_t* p, int n) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < n) p[t] = 0;
-}
-
 // Leading work-groups that serve the queue of cut-row parts before their own block row (LIST mode).
 constexpr int kExtraWGs = 256;
 
@@ -524,10 +534,6 @@ int launch(AttnParams& P, int64_t Mb, void* workspace, hipStream_t s) {
   if (P.mode == BBM_MODE_LIST) {
     P.queue = static_cast<int32_t*>(workspace);
     P.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + queue_bytes(Mb, P.nbr, P.hbp));
-    const int nq = (int)(8 + Mb * P.nbr * P.hbp);
-    zero_ints_kernel<<<(nq + 255) / 256, 256, 0, s>>>(P.queue, nq);
-    int rc = bbm::launch_status("bbm_attn_fwd(queue reset)");
-    if (rc) return rc;
     P.n_extra = P.total_wgs < kExtraWGs ? P.total_wgs : kExtraWGs;
     attn_fwd_kernel<D, NW, true><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   } else {
@@ -623,6 +629,8 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
   P.partials = nullptr;
   P.hbp = (int32_t)(Mb == 1 ? B * H : H);
   P.n_extra = 0;
+  // interleave the planes that one XCD's share of the launch spans (at most 8: their K and V should stay in its L2)
+  P.G = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, (B * H * nbr / 8) / nbr));
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (d == 64) {
     if (idx->Br == 64) return launch<64, 2>(P, Mb, workspace, s);
