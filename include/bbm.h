@@ -125,10 +125,13 @@ int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nb
  *                    T = max(32, 2 * mean entries per non-empty row) list entries are cut into ceil(n/T) near-equal
  *                    parts.  int32 layout: [0] parts, [1] T, [2] cut rows, [3..7] 0, then 8 ints per part ordered by
  *                    (row, part): plane*nbr + block row, first entry (position in the plane's list), entries, part,
- *                    parts of the row, number of the row's first part, index of the row among the cut rows, 0.
- *                    The last Mb*nbr ints list, per plane, the block rows by list length, longest first (ties: higher
- *                    row first; planes with more than 4096 block rows: simply last row first): the order in which
- *                    LIST mode starts work-groups.
+ *                    parts of the row, number of the row's first part, index of the row among the cut rows, the list
+ *                    entry at the part's first position.
+ *                    The last 4*Mb*nbr ints are one 4-int record per (plane, rank): the block rows of a plane by list
+ *                    length, longest first (ties: higher row first; planes with more than 4096 block rows: simply
+ *                    last row first) -- the order in which LIST mode starts work-groups; a record holds the block
+ *                    row, the position of its first entry in the plane's list, its number of entries and its first
+ *                    list entry (-1 if it has none), i.e. all a work-group needs to start fetching.
  *                    It depends only on the mask, so it is shared by heads, layers and calls like the rest of the
  *                    index.
  * Requires nbr*nbc < 2^31 and Mb*nbr < 2^24.  Errors: BBM_EINVAL, BBM_EHIP.

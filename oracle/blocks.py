@@ -106,32 +106,41 @@ SCHED_PART_BASE = 8
 SCHED_PART_INTS = 8
 SCHED_MIN_SPLIT = 32
 SCHED_MAX_SORT_ROWS = 4096
+SCHED_ROW_INTS = 4
 
 
-def schedule(row_ptr):
+def schedule(row_ptr, col_idx):
     """Split schedule of the list mode (this build's own layout, stated in the library header).
 
-    row_ptr int32 [Mb, nbr+1] -> int32 array of 8 + 9*Mb*nbr entries: [0] parts, [1] split threshold
-    T = max(32, 2*ceil(mean list length of the non-empty rows)), [2] cut rows, [3..7] 0, then 8 ints per part in
-    (row, part) order: row (= plane*nbr + block row), first entry (position in the plane's list), entries, part,
-    parts of the row, number of the row's first part, index of the row among the cut rows, 0.
+    row_ptr int32 [Mb, nbr+1], col_idx uint32 [Mb*nbr*nbc] (as sparse_index returns them) -> int32 array of 8 + 12*Mb*nbr entries: [0] parts,
+    [1] split threshold T = max(32, 2*ceil(mean list length of the non-empty rows)), [2] cut rows, [3..7] 0, then
+    8 ints per part in (row, part) order: row (= plane*nbr + block row), first entry (position in the plane's list),
+    entries, part, parts of the row, number of the row's first part, index of the row among the cut rows, the list
+    entry at the part's first position (as int32).
     A row with n > T entries is cut into ceil(n/T) parts of ceil(n/parts) entries (the last part takes the rest);
-    rows with n <= T are not listed.  Table entries past the last part are unspecified.  The last Mb*nbr entries
-    give, per plane, the block rows ordered by list length, longest first, ties broken towards the higher row
-    (planes of more than 4096 block rows are listed from the last row to the first instead)."""
+    rows with n <= T are not listed.  Table entries past the last part are unspecified.  The last 4*Mb*nbr entries
+    are one record of 4 ints per (plane, rank): the block rows of a plane ordered by list length, longest first,
+    ties broken towards the higher row (planes of more than 4096 block rows are listed from the last row to the
+    first instead); the record holds the block row, the position of its first list entry in the plane's list, its
+    number of entries, and its first list entry (-1 if it has none)."""
     Mb, nbr1 = row_ptr.shape
     nbr = nbr1 - 1
     counts = [int(row_ptr[m, i + 1] - row_ptr[m, i]) for m in range(Mb) for i in range(nbr)]
     nonempty = sum(1 for c in counts if c > 0)
     mean = -(-sum(counts) // nonempty) if nonempty else 0
     T = max(SCHED_MIN_SPLIT, 2 * mean)
-    out = np.zeros(SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbr + Mb * nbr, dtype=np.int32)
     order_base = SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbr
+    out = np.zeros(order_base + SCHED_ROW_INTS * Mb * nbr, dtype=np.int32)
+    lists = np.asarray(col_idx, dtype=np.uint32).reshape(Mb, -1)
+    entry = lambda m, pos: int(lists[m, pos].astype(np.int32))
     for m in range(Mb):
         rows = list(range(nbr - 1, -1, -1))
         if nbr <= SCHED_MAX_SORT_ROWS:
             rows.sort(key=lambda i: -counts[m * nbr + i])        # stable: equal lengths stay in descending row order
-        out[order_base + m * nbr:order_base + (m + 1) * nbr] = rows
+        for rank, i in enumerate(rows):
+            o = order_base + SCHED_ROW_INTS * (m * nbr + rank)
+            c = counts[m * nbr + i]
+            out[o:o + 4] = (i, int(row_ptr[m, i]), c, entry(m, int(row_ptr[m, i])) if c > 0 else -1)
     q, rho = 0, 0
     for r, c in enumerate(counts):
         if c <= T:
@@ -141,7 +150,7 @@ def schedule(row_ptr):
         for k in range(parts):
             first = int(row_ptr[r // nbr, r % nbr]) + k * chunk
             o = SCHED_PART_BASE + SCHED_PART_INTS * (q + k)
-            out[o:o + 8] = (r, first, min(chunk, c - k * chunk), k, parts, q, rho, 0)
+            out[o:o + 8] = (r, first, min(chunk, c - k * chunk), k, parts, q, rho, entry(r // nbr, first))
         q += parts
         rho += 1
     out[0], out[1], out[2] = q, T, rho
@@ -154,5 +163,5 @@ def block_index(mask, Br, Bc):
     idx = dict(cls=cls, bin_blk_mat=(cls != 0).astype(np.uint8))
     idx.update(run_index(cls))
     idx["row_ptr"], idx["col_idx"] = sparse_index(cls)
-    idx["sched"] = schedule(idx["row_ptr"])
+    idx["sched"] = schedule(idx["row_ptr"], idx["col_idx"])
     return idx

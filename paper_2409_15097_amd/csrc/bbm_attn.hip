@@ -73,7 +73,7 @@ constexpr uint32_t kNoTile = 0xffffffffu;  // sentinel after the last entry of a
 
 // Builds, in LDS, the ascending list of tiles one block row visits inside one schedule window; entry =
 // block column | (1 << 31 if the element mask can be skipped there).  Returns the number of entries (uniform).
-// `win` counts windows of kWin block columns (BITMAP, RUNS, DENSE_BASELINE) or of kWin list entries (LIST).
+// `win` counts windows of kWin block columns.  (BITMAP, RUNS and DENSE_BASELINE; LIST mode copies its list instead.)
 template <int NW>
 __device__ __forceinline__ int build_window(const AttnParams& P, int m, int i, int win, uint32_t* tiles_s, int* cnt_s) {
   constexpr int NT = NW * 64;
@@ -81,13 +81,7 @@ __device__ __forceinline__ int build_window(const AttnParams& P, int m, int i, i
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t r = (int64_t)m * P.nbr + i;
   int count;
-  if (P.mode == BBM_MODE_LIST) {
-    const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
-    const int p0 = rp[0] + win * kWin;
-    count = min(kWin, rp[1] - p0);
-    const uint32_t* list = P.col_idx + (int64_t)m * P.nbr * P.nbc + p0;
-    for (int t = tid; t < count; t += NT) tiles_s[t] = list[t];
-  } else if (P.mode == BBM_MODE_DENSE_BASELINE) {
+  if (P.mode == BBM_MODE_DENSE_BASELINE) {
     const int j0 = win * kWin;
     count = min(kWin, P.nbc - j0);
     for (int t = tid; t < count; t += NT) tiles_s[t] = (uint32_t)(j0 + t);
@@ -139,10 +133,6 @@ __device__ __forceinline__ int build_window(const AttnParams& P, int m, int i, i
 
 // Number of schedule windows of one block row (uniform).
 __device__ __forceinline__ int num_windows(const AttnParams& P, int m, int i) {
-  if (P.mode == BBM_MODE_LIST) {
-    const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
-    return (rp[1] - rp[0] + kWin - 1) / kWin;
-  }
   if (P.mode == BBM_MODE_RUNS) {
     const int64_t r = (int64_t)m * P.nbr + i;
     const int lo = P.nz_lo[r] & ~63, hi = P.nz_hi[r];
@@ -178,6 +168,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   constexpr int KS = D / 16;                   // MFMA k-steps of the first product
   constexpr int DB = D / 32;                   // 32-wide output-column blocks of the second product
   constexpr int REGS = DB * 16;                // fp32 accumulator registers per lane
+  static_assert(2 * 32 * D <= NBLK * KBLK && NW <= 8, "two 32 x D output slabs must fit in each tile buffer");
 
   // separate arrays per buffer so the compiler can tell an asynchronous copy into one from reads of the other
   __shared__ __attribute__((aligned(16))) __bf16 k_s0[NBLK * KBLK];
@@ -365,14 +356,20 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     e1 = tiles_s[it + 2];
   };
 
-  // Runs the tiles listed in tiles_s[0 .. count) (followed by sentinels) through the pipeline.
-  auto run_window = [&](int count) {
-    e0 = tiles_s[0];
-    e1 = tiles_s[1];
+  // Starts the asynchronous copies of a window's first tile e (into buffer 0) and asks for its mask word.
+  auto start_tile0 = [&](uint32_t e) {
+    e0 = e;
     mw_nxt = 0;
     load_tile_async(Kg, tile_of(e0), k_s0, KBLK);
     load_tile_async(Vg, tile_of(e0), v_s0, VBLK);
     if ((e0 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e0) * N];
+  };
+
+  // Runs the tiles listed in tiles_s[0 .. count) (followed by sentinels) through the pipeline; `started` says that
+  // start_tile0 was already called for tiles_s[0].
+  auto run_window = [&](int count, bool started) {
+    if (!started) start_tile0(tiles_s[0]);
+    e1 = tiles_s[1];
     for (int it = 0; it < count; it += 2) {
       step(IntC<0>{}, it);
       if (it + 1 < count) step(IntC<1>{}, it + 1);
@@ -380,24 +377,49 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     __syncthreads();  // whoever comes next rewrites the tile list and the K/V buffers
   };
 
-  // normalise, round to bf16, store; fully masked rows give O = 0, lse = -inf
+  // Runs nt >= 1 consecutive list entries, the first of which is already known: its copies start before the list
+  // itself has been fetched.
+  auto run_list = [&](const uint32_t* __restrict__ list, int nt, uint32_t first) {
+    start_tile0(first);
+    for (int w0 = 0; w0 < nt; w0 += kWin) {
+      const int count = min(kWin, nt - w0);
+      for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
+      if (tid < 3) tiles_s[count + tid] = kNoTile;
+      __syncthreads();
+      run_window(count, w0 == 0);
+    }
+  };
+
+  // normalise, round to bf16, store; fully masked rows give O = 0, lse = -inf.  The wave's 32 x D output slab goes
+  // through LDS (the tile buffers are idle here: two slabs fit in each) so that the global stores are whole rows:
+  // 16-byte chunk ch of row r sits at chunk position ch ^ (r % RC) of the row.
   auto write_output = [&]() {
     const float l_tot = partner_sum(l_run);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
-    if (q_ok) {
-      __bf16* og = P.o + head_off + qrow * D;
+    __bf16* const stage = ((wave >> 1) == 0 ? k_s0 : (wave >> 1) == 1 ? k_s1 : (wave >> 1) == 2 ? v_s0 : v_s1) + (wave & 1) * 32 * D;
+    // lane coordinates, re-derived behind an optimisation barrier: otherwise the per-lane staging addresses are
+    // hoisted to the kernel's start and occupy registers throughout the tile loop
+    int lqo = lq, hho = hh, gro = g_row, gco = g_chunk;
+    asm volatile("" : "+v"(lqo), "+v"(hho), "+v"(gro), "+v"(gco));
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
+    for (int db = 0; db < DB; ++db) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 ov;
-          for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(oacc[db][4 * g + e] * inv);
-          *reinterpret_cast<bf16x4*>(og + 32 * db + 8 * g + 4 * hh) = ov;
-        }
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 ov;
+        for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(oacc[db][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(stage + lqo * D + (((4 * db + g) ^ (lqo % RC)) * 8) + 4 * hho) = ov;
       }
-      if (P.lse && hh == 0)
-        P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * P.scale + __logf(l_tot) : -INFINITY;
     }
+    const int64_t row0 = (int64_t)i * BR + wave * 32;
+    __bf16* og = P.o + head_off + row0 * D;
+#pragma unroll
+    for (int n = 0; n < 32 / RPB; ++n) {
+      const int r = n * RPB + gro;
+      const bf16x8 ov = *reinterpret_cast<const bf16x8*>(stage + r * D + ((gco ^ (r % RC)) * 8));
+      if (row0 + r < N) *reinterpret_cast<bf16x8*>(og + r * D + gco * 8) = ov;
+    }
+    if (q_ok && P.lse && hh == 0)
+      P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * P.scale + __logf(l_tot) : -INFINITY;
   };
 
   const int split_T = SCHED ? P.sched[bbm::kSchedSplitT] : 0;  // requested early: needed only after other loads
@@ -420,15 +442,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     i = row - m * P.nbr;
     bh = (P.Mb == 1) ? hb : m * P.H + hb;
     begin_item();
-
-    const uint32_t* __restrict__ list = P.col_idx + (int64_t)m * P.nbr * P.nbc + p0;
-    for (int w0 = 0; w0 < nt; w0 += kWin) {
-      const int count = min(kWin, nt - w0);
-      for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
-      if (tid < 3) tiles_s[count + tid] = kNoTile;
-      __syncthreads();
-      run_window(count);
-    }
+    run_list(P.col_idx + (int64_t)m * P.nbr * P.nbc + p0, nt, (uint32_t)seg[7]);
 
     {
       // ---- park the unnormalised partial result; the last part of the row to arrive merges them all
@@ -496,19 +510,24 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     const int rank = within / g_planes;
     bh = grp * P.G + (within - rank * g_planes);
     m = (P.Mb == 1) ? 0 : bh / P.H;
-    // rank -> row, longest first: by the schedule's order (LIST), else from the last row up (long first for causal-like masks)
-    i = SCHED ? P.sched[bbm::sched_order_base(P.Mb, P.nbr) + m * P.nbr + rank] : P.nbr - 1 - rank;
-    int n_list = 0;
-    if (SCHED) {  // a row the schedule cut belongs to the queue (the loads overlap with those of begin_item)
-      const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
-      n_list = rp[1] - rp[0];
-    }
-    begin_item();
-    if (!(SCHED && n_list > split_T)) {
+    if (SCHED) {
+      // one record says which block row has this rank (longest list first), where its list lies and how it starts
+      const int4 rec = *reinterpret_cast<const int4*>(P.sched + bbm::sched_order_base(P.Mb, P.nbr) +
+                                                      bbm::kSchedRowInts * (int64_t)(m * P.nbr + rank));
+      i = rec.x;
+      const int n_list = rec.z;
+      begin_item();
+      if (n_list <= split_T) {  // a row the schedule cut belongs to the queue
+        if (n_list > 0) run_list(P.col_idx + (int64_t)m * P.nbr * P.nbc + rec.y, n_list, (uint32_t)rec.w);
+        write_output();
+      }
+    } else {
+      i = P.nbr - 1 - rank;  // from the last row up: long rows first for causal-like masks
+      begin_item();
       const int nwin = num_windows(P, m, i);
       for (int win = 0; win < nwin; ++win) {
         const int count = build_window<NW>(P, m, i, win, tiles_s, cnt_s);
-        if (count > 0) run_window(count);
+        if (count > 0) run_window(count, false);
       }
       write_output();
     }

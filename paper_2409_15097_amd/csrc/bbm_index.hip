@@ -120,18 +120,47 @@ __global__ __launch_bounds__(kWavesPerWG * 64) void list_fill_kernel(const uint8
   }
 }
 
-// Split schedule of LIST mode (layout in bbm_internal.h).  One work-group; every thread owns a contiguous range of
-// block rows.  Pass 1 counts, per thread, the parts and the cut rows; an exclusive scan over the threads turns the
-// counts into positions; pass 2 writes the parts in (row, part) order, so the result does not depend on the thread
-// count.
+// Split schedule of LIST mode (layout in bbm_internal.h).  Work-group 0 writes the header and the parts table: every
+// thread owns a contiguous range of block rows; pass 1 counts, per thread, the parts and the cut rows; an exclusive
+// scan over the threads turns the counts into positions; pass 2 writes the parts in (row, part) order, so the
+// result does not depend on the thread count.  Work-group 1 + m writes the row records of plane m, longest list
+// first, ranking by counting over the list lengths staged in LDS.
 constexpr int kSchedThreads = 256;
 
-__global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __restrict__ row_ptr, int Mb, int nbr,
-                                                              int32_t* __restrict__ sched) {
+__global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __restrict__ row_ptr,
+                                                              const uint32_t* __restrict__ col_idx, int Mb, int nbr,
+                                                              int64_t plane_entries, int32_t* __restrict__ sched) {
   using namespace bbm;
   __shared__ int pre[2][kSchedThreads + 1];
   __shared__ int red[2][kSchedThreads];
+  __shared__ int len_s[kSchedMaxSortRows];
   const int tid = threadIdx.x;
+
+  if (blockIdx.x > 0) {
+    const int m = blockIdx.x - 1;
+    const int32_t* rp = row_ptr + (int64_t)m * (nbr + 1);
+    const uint32_t* list = col_idx + (int64_t)m * plane_entries;
+    int4* rec = reinterpret_cast<int4*>(sched + sched_order_base(Mb, nbr)) + (int64_t)m * nbr;
+    const bool sorted = nbr <= kSchedMaxSortRows;
+    if (sorted) {
+      for (int j = tid; j < nbr; j += kSchedThreads) len_s[j] = rp[j + 1] - rp[j];
+      __syncthreads();
+    }
+    for (int i = tid; i < nbr; i += kSchedThreads) {
+      const int p0 = rp[i], c = rp[i + 1] - p0;
+      int rank = nbr - 1 - i;
+      if (sorted) {
+        rank = 0;
+        for (int j = 0; j < nbr; ++j) {
+          const int cj = len_s[j];
+          rank += (cj > c) || (cj == c && j > i);
+        }
+      }
+      rec[rank] = make_int4(i, p0, c, c > 0 ? (int)list[p0] : -1);
+    }
+    return;
+  }
+
   const int nrows = Mb * nbr;
   const int per = (nrows + kSchedThreads - 1) / kSchedThreads;
   const int r_lo = min(nrows, tid * per), r_hi = min(nrows, r_lo + per);
@@ -195,6 +224,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
     const int32_t* rp = first_entry(r);
     const int c = rp[1] - rp[0];
     if (c <= T) continue;
+    const uint32_t* list = col_idx + (int64_t)(r / nbr) * plane_entries;
     const int np = (c + T - 1) / T;
     const int chunk = (c + np - 1) / np;
     for (int k = 0; k < np; ++k) {
@@ -206,27 +236,10 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
       rec[4] = np;
       rec[5] = q;
       rec[6] = rho;
-      rec[7] = 0;
+      rec[7] = (int32_t)list[rp[0] + k * chunk];
     }
     q += np;
     rho += 1;
-  }
-
-  // longest-list-first order of the block rows of every plane (rank by counting; ties: higher row first)
-  int32_t* order = sched + sched_order_base(Mb, nbr);
-  for (int r = tid; r < nrows; r += kSchedThreads) {
-    const int m = r / nbr, i = r - m * nbr;
-    int rank = nbr - 1 - i;
-    if (nbr <= kSchedMaxSortRows) {
-      const int32_t* rp = row_ptr + (int64_t)m * (nbr + 1);
-      const int c = rp[i + 1] - rp[i];
-      rank = 0;
-      for (int j = 0; j < nbr; ++j) {
-        const int cj = rp[j + 1] - rp[j];
-        rank += (cj > c) || (cj == c && j > i);
-      }
-    }
-    order[m * nbr + rank] = i;
   }
 }
 
@@ -274,6 +287,6 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_sparse_index(con
   list_fill_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr, col_idx);
   rc = launch_status("bbm_build_sparse_index(fill)");
   if (rc || !sched) return rc;
-  sched_kernel<<<1, kSchedThreads, 0, s>>>(row_ptr, (int)Mb, (int)nbr, sched);
+  sched_kernel<<<(unsigned)(1 + Mb), kSchedThreads, 0, s>>>(row_ptr, col_idx, (int)Mb, (int)nbr, nbr * nbc, sched);
   return launch_status("bbm_build_sparse_index(schedule)");
 }

@@ -46,7 +46,7 @@ def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
         n = oracle.blocks.SCHED_PART_BASE + oracle.blocks.SCHED_PART_INTS * int(want["sched"][0])
         assert np.array_equal(got["sched"][:n], want["sched"][:n])
         Mb, nbr, _ = want["cls"].shape
-        assert np.array_equal(got["sched"][-Mb * nbr:], want["sched"][-Mb * nbr:])       # longest-first row order
+        assert np.array_equal(got["sched"][-4 * Mb * nbr:], want["sched"][-4 * Mb * nbr:])       # longest-first row records
     if got["packed_mask"] is not None:
         assert np.array_equal(got["packed_mask"], oracle.packed_bits(mask))
 

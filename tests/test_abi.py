@@ -59,7 +59,7 @@ def test_index_builders_reject_bad_arguments(bbm):
     assert L.bbm_build_sparse_index(FAKE, 1, 4, 0, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
     assert L.bbm_build_sparse_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None, None) == bbm.BBM_EUNSUPPORTED
     assert L.bbm_build_sparse_index(FAKE, 1, 4, 4, FAKE, FAKE, C.c_void_p(0x1004), None) == bbm.BBM_EINVAL
-    assert bbm.bbm_sched_bytes(1, 4) == 4 * (8 + 9 * 4) and bbm.bbm_sched_bytes(0, 4) == 0
+    assert bbm.bbm_sched_bytes(1, 4) == 4 * (8 + 12 * 4) and bbm.bbm_sched_bytes(0, 4) == 0
 
 
 def _idx(bbm, Br=128, Bc=64, Mb=1, N=256, **ptrs):

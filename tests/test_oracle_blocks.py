@@ -159,19 +159,37 @@ def test_skip_rule_matches_paper_wording():
                 assert t >= 1            # a full block outside the run exists only if a longer/equal run was kept
 
 
+def _fake_lists(rp, width):
+    """A col_idx array whose entry at position p of plane m is the recognisable value 1000*m + p (bit 31 set on odd p)."""
+    Mb = rp.shape[0]
+    ci = np.zeros((Mb, width), dtype=np.uint32)
+    for m in range(Mb):
+        for p in range(int(rp[m, -1])):
+            ci[m, p] = (1000 * m + p) | (0x80000000 if p % 2 else 0)
+    return ci.reshape(-1)
+
+
+def _sched(rows, width=512):
+    rp = np.array(rows, dtype=np.int32)
+    return oracle.schedule(rp, _fake_lists(rp, width))
+
+
 def test_schedule_cuts_only_long_rows():
-    # rows with 3, 0, 40, 5 entries: mean of non-empty = 16 -> T = 32 -> only the 40-entry row is cut, into 2 x 20
-    rp = np.array([[0, 3, 3, 43, 48]], dtype=np.int32)
-    s = oracle.schedule(rp)
+    # rows with 3, 0, 40, 5 entries: mean of non-empty = 16 -> T = 32 -> only the 40-entry row is cut, into 2 x 20;
+    # the last int of a part is the list entry at its first position (position 23 is odd: bit 31 set -> negative)
+    s = _sched([[0, 3, 3, 43, 48]])
     assert (s[0], s[1], s[2]) == (2, 32, 1) and not s[3:8].any()
-    assert s[8:24].reshape(2, 8).tolist() == [[2, 3, 20, 0, 2, 0, 0, 0], [2, 23, 20, 1, 2, 0, 0, 0]]
+    assert s[8:24].reshape(2, 8).tolist() == [[2, 3, 20, 0, 2, 0, 0, 3 - 2**31], [2, 23, 20, 1, 2, 0, 0, 23 - 2**31]]
     # the floor of the threshold: rows of 1, 33 -> mean 17 -> T = 34: nothing cut; rows 1, 1, 1, 40 -> T = 32: 40 cut
-    assert oracle.schedule(np.array([[0, 1, 34]], dtype=np.int32))[:3].tolist() == [0, 34, 0]
-    assert oracle.schedule(np.array([[0, 1, 2, 3, 43]], dtype=np.int32))[:3].tolist() == [2, 32, 1]
-    assert oracle.schedule(np.array([[0, 5, 10, 15]], dtype=np.int32))[0] == 0          # uniform rows: nothing cut
-    # row order: lengths 3, 0, 40, 5 -> rows 2, 3, 0, 1; equal lengths -> higher row first (causal masks: last row first)
-    assert s[-4:].tolist() == [2, 3, 0, 1]
-    assert oracle.schedule(np.array([[0, 5, 10, 15], [0, 1, 3, 6]], dtype=np.int32))[-6:].tolist() == [2, 1, 0, 2, 1, 0]
+    assert _sched([[0, 1, 34]])[:3].tolist() == [0, 34, 0]
+    assert _sched([[0, 1, 2, 3, 43]])[:3].tolist() == [2, 32, 1]
+    assert _sched([[0, 5, 10, 15]])[0] == 0          # uniform rows: nothing cut
+    # row records (row, first position, entries, first entry): lengths 3, 0, 40, 5 -> rows 2, 3, 0, 1; an empty row has
+    # first entry -1; equal lengths -> higher row first (causal masks: last row first)
+    assert s[-16:].reshape(4, 4).tolist() == [[2, 3, 40, 3 - 2**31], [3, 43, 5, 43 - 2**31], [0, 0, 3, 0], [1, 3, 0, -1]]
+    s2 = _sched([[0, 5, 10, 15], [0, 1, 3, 6]])
+    assert s2[-24:].reshape(6, 4).tolist() == [[2, 10, 5, 10], [1, 5, 5, 5 - 2**31], [0, 0, 5, 0],
+                                              [2, 3, 3, 1003 - 2**31], [1, 1, 2, 1001 - 2**31], [0, 0, 1, 1000]]
 
 
 def test_schedule_parts_tile_each_cut_row_exactly():
@@ -180,13 +198,15 @@ def test_schedule_parts_tile_each_cut_row_exactly():
     counts[rng.random(counts.shape) < 0.6] //= 20
     rp = np.zeros((3, 38), dtype=np.int32)
     rp[:, 1:] = np.cumsum(counts, axis=1)
-    s = oracle.schedule(rp)
+    lists = _fake_lists(rp, 37 * 300)
+    s = oracle.schedule(rp, lists)
     nparts, T, ncut = int(s[0]), int(s[1]), int(s[2])
     assert T == max(32, 2 * -(-int(counts.sum()) // int((counts > 0).sum())))
     parts = s[8:8 + 8 * nparts].reshape(nparts, 8)
     covered = np.zeros(counts.shape, dtype=np.int64)
-    for q, (r, first, nt, k, np_, qf, rho, _) in enumerate(parts):
+    for q, (r, first, nt, k, np_, qf, rho, e_first) in enumerate(parts):
         m, i = divmod(int(r), 37)
+        assert (int(e_first) & 0xffffffff) == int(lists.reshape(3, -1)[m, first])
         assert counts[m, i] > T and np_ == -(-counts[m, i] // T) and 1 <= nt <= T and q == qf + k
         assert first == rp[m, i] + covered[m, i]            # parts are consecutive slices of the row's list
         covered[m, i] += nt
