@@ -94,8 +94,7 @@ def measure_mask(bbm, name, Br, warmup, steps, torch):
 
     def step():
         bbm.bbm_build_block_mask(mask, Br, 64, idx=idx)
-        bbm.bbm_build_runs(idx)
-        bbm.bbm_build_sparse_index(idx)
+        bbm.bbm_build_index(idx)
         bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws)
 
     res = dict(workload=name, B=B, H=H, N=N, d=d, Mb=Mb, Br=Br, Bc=64, visited_tiles=tiles, blocks=census,
@@ -118,7 +117,7 @@ def measure_mask(bbm, name, Br, warmup, steps, torch):
     res["preprocess_ms"] = pre_ms
     res["preprocess_gbs"] = pre_bytes / (pre_ms * 1e-3) / 1e9
     res["preprocess_hbm_frac"] = res["preprocess_gbs"] / HBM_PEAK_GBS
-    res["index_ms"] = time_gpu(lambda: (bbm.bbm_build_runs(idx), bbm.bbm_build_sparse_index(idx)), warmup, steps)
+    res["index_ms"] = time_gpu(lambda: bbm.bbm_build_index(idx), warmup, steps)
     # algorithmic HBM bytes of the attention kernel: Q, K, V read once, O written once, lse, packed words of partial tiles
     res["attn_algo_bytes"] = 4.0 * B * H * N * d * 2 + 4.0 * B * H * N + census["partial"] * (B // Mb) * Br * 8.0
     del mask, q, k, v, idx, out, lse, ws

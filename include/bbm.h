@@ -139,6 +139,16 @@ int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nb
 int bbm_build_sparse_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* row_ptr,
                            uint32_t* col_idx, int32_t* sched, void* stream);
 
+/*
+ * Stages 1b and 1c in one call: exactly the outputs of bbm_build_runs followed by bbm_build_sparse_index (same
+ * arguments, same requirements, same errors), none of the output pointers except sched may be NULL.  Class matrices
+ * of at most 256 (block row, 64-column chunk) pairs -- 4 planes of a 4096 x 4096 mask in 128 x 64 tiles, say -- are
+ * served by a single kernel launch, which at that size is most of the cost.
+ */
+int bbm_build_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset, int32_t* total_ones,
+                    int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt, int32_t* row_ptr, uint32_t* col_idx, int32_t* sched,
+                    void* stream);
+
 /* Bytes of the tile schedule bbm_build_sparse_index writes for Mb planes of nbr block rows (0 for sizes < 1). */
 size_t bbm_sched_bytes(int64_t Mb, int64_t nbr);
 

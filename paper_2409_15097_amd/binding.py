@@ -45,6 +45,8 @@ def _load():
     L.bbm_build_runs.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
     L.bbm_build_sparse_index.restype = ci
     L.bbm_build_sparse_index.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
+    L.bbm_build_index.restype = ci
+    L.bbm_build_index.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.bbm_sched_bytes.restype = C.c_size_t
     L.bbm_sched_bytes.argtypes = [i64, i64]
     L.bbm_attn_fwd_workspace_bytes.restype = C.c_size_t
@@ -134,11 +136,24 @@ def bbm_build_block_mask(mask: torch.Tensor, Br: int, Bc: int, idx: Optional[Blo
     return idx
 
 
-def bbm_build_runs(idx: BlockIndex, stream=None) -> BlockIndex:
-    dev = idx.blk_class.device
+def _alloc_runs(idx: BlockIndex):
     for name in ("offset", "total_ones", "nz_lo", "nz_hi", "nz_cnt"):
         if getattr(idx, name) is None:
-            setattr(idx, name, torch.empty((idx.Mb, idx.nbr), dtype=torch.int32, device=dev))
+            setattr(idx, name, torch.empty((idx.Mb, idx.nbr), dtype=torch.int32, device=idx.blk_class.device))
+
+
+def _alloc_list(idx: BlockIndex):
+    dev = idx.blk_class.device
+    if idx.row_ptr is None:
+        idx.row_ptr = torch.empty((idx.Mb, idx.nbr + 1), dtype=torch.int32, device=dev)
+    if idx.col_idx is None:
+        idx.col_idx = torch.zeros(idx.Mb * idx.nbr * idx.nbc, dtype=torch.int32, device=dev)
+    if idx.sched is None:
+        idx.sched = torch.empty(bbm_sched_bytes(idx.Mb, idx.nbr) // 4, dtype=torch.int32, device=dev)
+
+
+def bbm_build_runs(idx: BlockIndex, stream=None) -> BlockIndex:
+    _alloc_runs(idx)
     _check(lib.bbm_build_runs(_ptr(idx.blk_class), idx.Mb, idx.nbr, idx.nbc, _ptr(idx.offset), _ptr(idx.total_ones),
                               _ptr(idx.nz_lo), _ptr(idx.nz_hi), _ptr(idx.nz_cnt), _stream(stream)))
     return idx
@@ -149,21 +164,29 @@ def bbm_sched_bytes(Mb: int, nbr: int) -> int:
 
 
 def bbm_build_sparse_index(idx: BlockIndex, stream=None) -> BlockIndex:
-    dev = idx.blk_class.device
-    if idx.row_ptr is None:
-        idx.row_ptr = torch.empty((idx.Mb, idx.nbr + 1), dtype=torch.int32, device=dev)
-    if idx.col_idx is None:
-        idx.col_idx = torch.zeros(idx.Mb * idx.nbr * idx.nbc, dtype=torch.int32, device=dev)
-    if idx.sched is None:
-        idx.sched = torch.empty(bbm_sched_bytes(idx.Mb, idx.nbr) // 4, dtype=torch.int32, device=dev)
+    _alloc_list(idx)
     _check(lib.bbm_build_sparse_index(_ptr(idx.blk_class), idx.Mb, idx.nbr, idx.nbc, _ptr(idx.row_ptr),
                                       _ptr(idx.col_idx), _ptr(idx.sched), _stream(stream)))
     return idx
 
 
-def build_index(mask: torch.Tensor, Br: int, Bc: int = 64, idx: Optional[BlockIndex] = None, stream=None) -> BlockIndex:
-    """The whole preprocessing stage: the three build calls in order."""
+def bbm_build_index(idx: BlockIndex, stream=None) -> BlockIndex:
+    """Run index, block list and schedule from idx.blk_class in one library call."""
+    _alloc_runs(idx)
+    _alloc_list(idx)
+    _check(lib.bbm_build_index(_ptr(idx.blk_class), idx.Mb, idx.nbr, idx.nbc, _ptr(idx.offset), _ptr(idx.total_ones),
+                               _ptr(idx.nz_lo), _ptr(idx.nz_hi), _ptr(idx.nz_cnt), _ptr(idx.row_ptr), _ptr(idx.col_idx),
+                               _ptr(idx.sched), _stream(stream)))
+    return idx
+
+
+def build_index(mask: torch.Tensor, Br: int, Bc: int = 64, idx: Optional[BlockIndex] = None, stream=None,
+                fused: bool = True) -> BlockIndex:
+    """The whole preprocessing stage: block classes, then run index + block list + schedule (through the one-call
+    entry point, or with fused=False through the two separate ones)."""
     idx = bbm_build_block_mask(mask, Br, Bc, idx=idx, stream=stream)
+    if fused:
+        return bbm_build_index(idx, stream=stream)
     bbm_build_runs(idx, stream=stream)
     bbm_build_sparse_index(idx, stream=stream)
     return idx

@@ -9,7 +9,44 @@ constexpr int kWavesPerWG = 4;
 
 __device__ __forceinline__ int ctz64(uint64_t x) { return x ? __builtin_ctzll(x) : 64; }
 
-// One wave per block row.  Longest run of FULL blocks (leftmost on ties) and the span of non-zero blocks.
+// Longest run of FULL blocks of one block row (leftmost on ties) and the span of its non-zero blocks, fed 64 block
+// columns at a time in ascending order (bit t of `full` / `nz` = block column base + t).
+struct RunScan {
+  int best_len = 0, best_start = 0;  // longest finished run so far
+  int cur_len = 0, cur_start = 0;    // run that touches the end of the previous chunk (0 = none)
+  int lo = 0, hi = 0, cnt = 0;
+  __device__ __forceinline__ void feed(uint64_t full, uint64_t nz, int base) {
+    if (nz) {
+      if (cnt == 0) lo = base + ctz64(nz);
+      hi = base + 64 - __builtin_clzll(nz);
+      cnt += __popcll(nz);
+    }
+    if (cur_len > 0) {  // continue the run that reached the chunk boundary
+      const int ones = ctz64(~full);
+      cur_len += ones;
+      if (ones == 64) return;
+      if (cur_len > best_len) { best_len = cur_len; best_start = cur_start; }
+      cur_len = 0;
+      full &= ~((1ull << ones) - 1ull);
+    }
+    while (full) {
+      const int s = ctz64(full);
+      const int ones = ctz64(~(full >> s));  // full >> s has zeros shifted in, so ones <= 64 - s
+      if (s + ones == 64) {                  // run reaches the chunk end: decide when it ends
+        cur_start = base + s;
+        cur_len = ones;
+        return;
+      }
+      if (ones > best_len) { best_len = ones; best_start = base + s; }
+      full &= ~(((1ull << ones) - 1ull) << s);
+    }
+  }
+  __device__ __forceinline__ void finish() {
+    if (cur_len > best_len) { best_len = cur_len; best_start = cur_start; }
+  }
+};
+
+// One wave per block row.
 __global__ __launch_bounds__(kWavesPerWG * 64) void runs_kernel(const uint8_t* __restrict__ cls, int64_t rows_total,
                                                                 int64_t nbc, int32_t* __restrict__ offset,
                                                                 int32_t* __restrict__ total_ones,
@@ -19,46 +56,18 @@ __global__ __launch_bounds__(kWavesPerWG * 64) void runs_kernel(const uint8_t* _
   const int64_t row = (int64_t)blockIdx.x * kWavesPerWG + (threadIdx.x >> 6);
   if (row >= rows_total) return;
   const uint8_t* c = cls + row * nbc;
-
-  int best_len = 0, best_start = 0;  // longest finished run so far
-  int cur_len = 0, cur_start = 0;    // run that touches the end of the previous chunk (0 = none)
-  int lo = 0, hi = 0, cnt = 0;
+  RunScan rs;
   for (int64_t base = 0; base < nbc; base += 64) {
     const uint8_t v = (base + lane < nbc) ? c[base + lane] : (uint8_t)0;
-    uint64_t full = __ballot(v == BBM_BLOCK_FULL);
-    const uint64_t nz = __ballot(v != BBM_BLOCK_EMPTY);
-    if (nz) {
-      if (cnt == 0) lo = (int)base + ctz64(nz);
-      hi = (int)base + 64 - __builtin_clzll(nz);
-      cnt += __popcll(nz);
-    }
-    if (cur_len > 0) {  // continue the run that reached the chunk boundary
-      const int ones = ctz64(~full);
-      cur_len += ones;
-      if (ones == 64) continue;
-      if (cur_len > best_len) { best_len = cur_len; best_start = cur_start; }
-      cur_len = 0;
-      full &= ~((1ull << ones) - 1ull);
-    }
-    while (full) {
-      const int s = ctz64(full);
-      const int ones = ctz64(~(full >> s));  // full >> s has zeros shifted in, so ones <= 64 - s
-      if (s + ones == 64) {                  // run reaches the chunk end: decide when it ends
-        cur_start = (int)base + s;
-        cur_len = ones;
-        break;
-      }
-      if (ones > best_len) { best_len = ones; best_start = (int)base + s; }
-      full &= ~(((1ull << ones) - 1ull) << s);
-    }
+    rs.feed(__ballot(v == BBM_BLOCK_FULL), __ballot(v != BBM_BLOCK_EMPTY), (int)base);
   }
-  if (cur_len > best_len) { best_len = cur_len; best_start = cur_start; }
+  rs.finish();
   if (lane == 0) {
-    offset[row] = best_start;
-    total_ones[row] = best_len;
-    nz_lo[row] = lo;
-    nz_hi[row] = hi;
-    nz_cnt[row] = cnt;
+    offset[row] = rs.best_start;
+    total_ones[row] = rs.best_len;
+    nz_lo[row] = rs.lo;
+    nz_hi[row] = rs.hi;
+    nz_cnt[row] = rs.cnt;
   }
 }
 
@@ -243,40 +252,219 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
   }
 }
 
+// Whole sparse index (row_ptr, col_idx and, if asked for, the schedule), and if asked for the run index as well,
+// in ONE launch of one work-group, for class matrices of at most kSmallPairs (row, 64-column chunk) pairs -- e.g. 4 planes of a 4096 x 4096 mask in 128 x 64
+// tiles.  At this size the four launches of the general path cost far more than the work itself.  Pair p = (row r,
+// chunk ch) with p = r*CH + ch is owned by slot p % 16 of wave p / 16; lists are row-major and ascending, so the
+// position of a pair's first entry in its plane's list is the exclusive prefix sum of the pairs' popcounts.
+constexpr int kSmallWaves = 16, kSmallSlots = 16, kSmallPairs = kSmallWaves * kSmallSlots;
+
+__global__ __launch_bounds__(kSmallWaves * 64) void small_index_kernel(const uint8_t* __restrict__ cls, int Mb, int nbr,
+                                                                       int nbc, int32_t* __restrict__ row_ptr,
+                                                                       uint32_t* col_idx, int32_t* __restrict__ sched,
+                                                                       int32_t* __restrict__ offset,
+                                                                       int32_t* __restrict__ total_ones,
+                                                                       int32_t* __restrict__ nz_lo,
+                                                                       int32_t* __restrict__ nz_hi,
+                                                                       int32_t* __restrict__ nz_cnt) {
+  using namespace bbm;
+  __shared__ int pc[kSmallPairs];     // non-zero blocks of a pair
+  __shared__ int pos[kSmallPairs];    // position of the pair's first entry in the plane's list
+  __shared__ int len_s[kSmallPairs];  // list length of a row
+  __shared__ int np_s[kSmallPairs];   // parts of a row (0 = not cut)
+  __shared__ int tot_s[4];            // list entries, non-empty rows, parts, cut rows
+  __shared__ int gpre_s[kSmallPairs], wsum_s[kSmallPairs / 64];
+  __shared__ uint64_t full_s[kSmallPairs], nz_s[kSmallPairs];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int CH = (nbc + 63) / 64, PP = nbr * CH, npairs = Mb * PP, nrows = Mb * nbr;
+  const int64_t plane_entries = (int64_t)nbr * nbc;
+  if (tid < 4) tot_s[tid] = 0;
+
+  uint8_t v[kSmallSlots];
+  uint64_t nz[kSmallSlots];
+#pragma unroll
+  for (int k = 0; k < kSmallSlots; ++k) {
+    const int p = wave * kSmallSlots + k;
+    const int r = p / CH, col = (p - r * CH) * 64 + lane;
+    v[k] = (p < npairs && col < nbc) ? cls[(int64_t)r * nbc + col] : (uint8_t)0;
+  }
+#pragma unroll
+  for (int k = 0; k < kSmallSlots; ++k) {
+    const int p = wave * kSmallSlots + k;
+    nz[k] = __ballot(v[k] != BBM_BLOCK_EMPTY);
+    const uint64_t full = __ballot(v[k] == BBM_BLOCK_FULL);
+    if (lane == 0 && p < npairs) {
+      pc[p] = __popcll(nz[k]);
+      nz_s[p] = nz[k];
+      full_s[p] = full;
+    }
+  }
+  __syncthreads();
+  // exclusive prefix sums of pc over all pairs (the first four waves scan 64 pairs each), then made plane-relative
+  if (wave < kSmallPairs / 64) {
+    const int x = tid < npairs ? pc[tid] : 0;
+    int incl = x;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int y = __shfl_up(incl, d);
+      if (lane >= d) incl += y;
+    }
+    if (lane == 63) wsum_s[wave] = incl;
+    gpre_s[tid] = incl - x;
+  }
+  __syncthreads();
+  if (tid < npairs) {
+    const int q0 = tid / PP * PP;  // first pair of this pair's plane
+    int own = 0, first = 0;
+    for (int w = 0; w < kSmallPairs / 64; ++w) {
+      own += w < wave ? wsum_s[w] : 0;
+      first += w < (q0 >> 6) ? wsum_s[w] : 0;
+    }
+    pos[tid] = gpre_s[tid] + own - (gpre_s[q0] + first);
+  }
+  __syncthreads();
+  int c = 0, start = 0;  // list length and list position of row `tid`
+  if (tid < nrows) {
+    const int m = tid / nbr, i = tid - m * nbr, p0 = tid * CH;
+    start = pos[p0];
+    const int end = (i == nbr - 1) ? pos[p0 + CH - 1] + pc[p0 + CH - 1] : pos[p0 + CH];
+    c = end - start;
+    row_ptr[(int64_t)m * (nbr + 1) + i] = start;
+    if (i == nbr - 1) row_ptr[(int64_t)m * (nbr + 1) + nbr] = end;
+    len_s[tid] = c;
+    if (c > 0) {
+      atomicAdd(&tot_s[0], c);
+      atomicAdd(&tot_s[1], 1);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < kSmallSlots; ++k) {
+    const int p = wave * kSmallSlots + k;
+    if (p < npairs && ((nz[k] >> lane) & 1ull)) {
+      const int r = p / CH, col = (p - r * CH) * 64 + lane;
+      col_idx[(int64_t)(r / nbr) * plane_entries + pos[p] + __popcll(nz[k] & ((1ull << lane) - 1ull))] =
+          (uint32_t)col | (v[k] == BBM_BLOCK_FULL ? 0x80000000u : 0u);
+    }
+  }
+  if (offset && tid < nrows) {  // run index: this thread walks the chunks of its row
+    RunScan rs;
+    for (int ch = 0; ch < CH; ++ch) rs.feed(full_s[tid * CH + ch], nz_s[tid * CH + ch], 64 * ch);
+    rs.finish();
+    offset[tid] = rs.best_start;
+    total_ones[tid] = rs.best_len;
+    nz_lo[tid] = rs.lo;
+    nz_hi[tid] = rs.hi;
+    nz_cnt[tid] = rs.cnt;
+  }
+  if (!sched) return;
+  __syncthreads();  // totals complete
+  // list entry number n of row r, from the chunk masks (the same value the fill above stores)
+  auto entry_at = [&](int r, int n) {
+    for (int ch = 0; ch < CH; ++ch) {
+      uint64_t x = nz_s[r * CH + ch];
+      const int cnt = __popcll(x);
+      if (n < cnt) {
+        for (int t = 0; t < n; ++t) x &= x - 1;
+        const int bit = ctz64(x);
+        return (int)((uint32_t)(64 * ch + bit) | (((full_s[r * CH + ch] >> bit) & 1ull) ? 0x80000000u : 0u));
+      }
+      n -= cnt;
+    }
+    return -1;
+  };
+
+  // ---- schedule (same definition as sched_kernel; everything sits in LDS here)
+  const int total = tot_s[0], nonempty = tot_s[1];
+  const int mean = nonempty > 0 ? (total + nonempty - 1) / nonempty : 0;
+  const int T = max(kSchedMinSplit, 2 * mean);
+  const int np = (tid < nrows && c > T) ? (c + T - 1) / T : 0;
+  if (tid < nrows) np_s[tid] = np;
+  if (np > 0) {
+    atomicAdd(&tot_s[2], np);
+    atomicAdd(&tot_s[3], 1);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    sched[kSchedNParts] = tot_s[2];
+    sched[kSchedSplitT] = T;
+    sched[kSchedNCutRows] = tot_s[3];
+    for (int x = 3; x < kSchedPartBase; ++x) sched[x] = 0;
+  }
+  if (tid < nrows) {
+    const int m = tid / nbr, i = tid - m * nbr;
+    if (np > 0) {
+      int q = 0, rho = 0;
+      for (int r = 0; r < tid; ++r) {
+        q += np_s[r];
+        rho += np_s[r] > 0;
+      }
+      const int chunk = (c + np - 1) / np;
+      for (int k = 0; k < np; ++k) {
+        int32_t* rec = sched + kSchedPartBase + (int64_t)kSchedPartInts * (q + k);
+        rec[0] = tid;
+        rec[1] = start + k * chunk;
+        rec[2] = min(chunk, c - k * chunk);
+        rec[3] = k;
+        rec[4] = np;
+        rec[5] = q;
+        rec[6] = rho;
+        rec[7] = entry_at(tid, k * chunk);
+      }
+    }
+    int rank = 0;
+#pragma unroll 8
+    for (int j = 0; j < nbr; ++j) {
+      const int cj = len_s[m * nbr + j];
+      rank += (cj > c) || (cj == c && j > i);
+    }
+    reinterpret_cast<int4*>(sched + sched_order_base(Mb, nbr))[(int64_t)m * nbr + rank] =
+        make_int4(i, start, c, entry_at(tid, 0));
+  }
+}
+
 }  // namespace
 
-extern "C" __attribute__((visibility("default"))) int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset,
-                              int32_t* total_ones, int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt, void* stream) {
+namespace {
+
+int check_runs_args(const char* fn, const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, const int32_t* offset,
+                    const int32_t* total_ones, const int32_t* nz_lo, const int32_t* nz_hi, const int32_t* nz_cnt) {
   using namespace bbm;
-  clear_error();
-  if (!blk_class || !offset || !total_ones || !nz_lo || !nz_hi || !nz_cnt)
-    return fail(BBM_EINVAL, "bbm_build_runs: NULL pointer argument");
+  if (!blk_class || !offset || !total_ones || !nz_lo || !nz_hi || !nz_cnt) return fail(BBM_EINVAL, "%s: NULL pointer argument", fn);
   if (Mb < 1 || nbr < 1 || nbc < 1)
-    return fail(BBM_EINVAL, "bbm_build_runs: Mb=%lld, nbr=%lld, nbc=%lld must be >= 1", (long long)Mb, (long long)nbr, (long long)nbc);
-  if (nbc > (1ll << 30) || Mb * nbr > (1ll << 31) * kWavesPerWG - 1)
-    return fail(BBM_EUNSUPPORTED, "bbm_build_runs: index too large");
-  const int64_t rows = Mb * nbr;
-  runs_kernel<<<(unsigned)ceil_div(rows, kWavesPerWG), kWavesPerWG * 64, 0, static_cast<hipStream_t>(stream)>>>(
-      blk_class, rows, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt);
-  return launch_status("bbm_build_runs");
+    return fail(BBM_EINVAL, "%s: Mb=%lld, nbr=%lld, nbc=%lld must be >= 1", fn, (long long)Mb, (long long)nbr, (long long)nbc);
+  if (nbc > (1ll << 30) || Mb * nbr > (1ll << 31) * kWavesPerWG - 1) return fail(BBM_EUNSUPPORTED, "%s: index too large", fn);
+  return BBM_OK;
 }
 
-extern "C" __attribute__((visibility("default"))) size_t bbm_sched_bytes(int64_t Mb, int64_t nbr) {
-  if (Mb < 1 || nbr < 1) return 0;
-  return (size_t)bbm::sched_ints(Mb, nbr) * sizeof(int32_t);
-}
-
-extern "C" __attribute__((visibility("default"))) int bbm_build_sparse_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc,
-                                      int32_t* row_ptr, uint32_t* col_idx, int32_t* sched, void* stream) {
+int check_list_args(const char* fn, const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, const int32_t* row_ptr,
+                    const uint32_t* col_idx, const int32_t* sched) {
   using namespace bbm;
-  clear_error();
-  if (!blk_class || !row_ptr || !col_idx) return fail(BBM_EINVAL, "bbm_build_sparse_index: NULL pointer argument");
+  if (!blk_class || !row_ptr || !col_idx) return fail(BBM_EINVAL, "%s: NULL pointer argument", fn);
   if (Mb < 1 || nbr < 1 || nbc < 1)
-    return fail(BBM_EINVAL, "bbm_build_sparse_index: Mb=%lld, nbr=%lld, nbc=%lld must be >= 1", (long long)Mb, (long long)nbr, (long long)nbc);
+    return fail(BBM_EINVAL, "%s: Mb=%lld, nbr=%lld, nbc=%lld must be >= 1", fn, (long long)Mb, (long long)nbr, (long long)nbc);
   if (nbr * nbc >= (1ll << 31) || Mb * nbr >= (1ll << 24))
-    return fail(BBM_EUNSUPPORTED, "bbm_build_sparse_index: needs nbr*nbc=%lld < 2^31 and Mb*nbr=%lld < 2^24", (long long)(nbr * nbc), (long long)(Mb * nbr));
-  if (sched && !aligned(sched, 32)) return fail(BBM_EINVAL, "bbm_build_sparse_index: sched must be 32-byte aligned");
-  hipStream_t s = static_cast<hipStream_t>(stream);
+    return fail(BBM_EUNSUPPORTED, "%s: needs nbr*nbc=%lld < 2^31 and Mb*nbr=%lld < 2^24", fn, (long long)(nbr * nbc), (long long)(Mb * nbr));
+  if (sched && !aligned(sched, 32)) return fail(BBM_EINVAL, "%s: sched must be 32-byte aligned", fn);
+  return BBM_OK;
+}
+
+int launch_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset, int32_t* total_ones,
+                int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt, hipStream_t s) {
+  const int64_t rows = Mb * nbr;
+  runs_kernel<<<(unsigned)bbm::ceil_div(rows, kWavesPerWG), kWavesPerWG * 64, 0, s>>>(blk_class, rows, nbc, offset, total_ones,
+                                                                                    nz_lo, nz_hi, nz_cnt);
+  return bbm::launch_status("bbm_build_runs");
+}
+
+bool is_small(int64_t Mb, int64_t nbr, int64_t nbc) { return Mb * nbr * bbm::ceil_div(nbc, (int64_t)64) <= kSmallPairs; }
+
+int launch_list(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* row_ptr, uint32_t* col_idx,
+                int32_t* sched, hipStream_t s) {
+  using namespace bbm;
+  if (is_small(Mb, nbr, nbc)) {
+    small_index_kernel<<<1, kSmallWaves * 64, 0, s>>>(blk_class, (int)Mb, (int)nbr, (int)nbc, row_ptr, col_idx, sched,
+                                                      nullptr, nullptr, nullptr, nullptr, nullptr);
+    return launch_status("bbm_build_sparse_index(small)");
+  }
   const unsigned grid = (unsigned)ceil_div(Mb * nbr, kWavesPerWG);
   list_count_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr);
   int rc = launch_status("bbm_build_sparse_index(count)");
@@ -289,4 +477,47 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_sparse_index(con
   if (rc || !sched) return rc;
   sched_kernel<<<(unsigned)(1 + Mb), kSchedThreads, 0, s>>>(row_ptr, col_idx, (int)Mb, (int)nbr, nbr * nbc, sched);
   return launch_status("bbm_build_sparse_index(schedule)");
+}
+
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset,
+                              int32_t* total_ones, int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt, void* stream) {
+  bbm::clear_error();
+  const int rc = check_runs_args("bbm_build_runs", blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt);
+  if (rc) return rc;
+  return launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, static_cast<hipStream_t>(stream));
+}
+
+extern "C" __attribute__((visibility("default"))) size_t bbm_sched_bytes(int64_t Mb, int64_t nbr) {
+  if (Mb < 1 || nbr < 1) return 0;
+  return (size_t)bbm::sched_ints(Mb, nbr) * sizeof(int32_t);
+}
+
+extern "C" __attribute__((visibility("default"))) int bbm_build_sparse_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc,
+                                      int32_t* row_ptr, uint32_t* col_idx, int32_t* sched, void* stream) {
+  bbm::clear_error();
+  const int rc = check_list_args("bbm_build_sparse_index", blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched);
+  if (rc) return rc;
+  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, static_cast<hipStream_t>(stream));
+}
+
+extern "C" __attribute__((visibility("default"))) int bbm_build_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset,
+                               int32_t* total_ones, int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt, int32_t* row_ptr,
+                               uint32_t* col_idx, int32_t* sched, void* stream) {
+  using namespace bbm;
+  clear_error();
+  int rc = check_runs_args("bbm_build_index", blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt);
+  if (rc) return rc;
+  rc = check_list_args("bbm_build_index", blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (is_small(Mb, nbr, nbc)) {
+    small_index_kernel<<<1, kSmallWaves * 64, 0, s>>>(blk_class, (int)Mb, (int)nbr, (int)nbc, row_ptr, col_idx, sched, offset,
+                                                      total_ones, nz_lo, nz_hi, nz_cnt);
+    return launch_status("bbm_build_index(small)");
+  }
+  rc = launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, s);
+  if (rc) return rc;
+  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, s);
 }

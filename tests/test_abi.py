@@ -20,7 +20,8 @@ def test_every_declared_symbol_is_exported(bbm):
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(bbm_[a-z_]+)\s*\(", hdr))
     assert names == {"bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs",
-                     "bbm_build_sparse_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"}
+                     "bbm_build_sparse_index", "bbm_build_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes",
+                     "bbm_attn_fwd"}
     raw = C.CDLL(bbm.library_path())
     for n in names:
         assert getattr(raw, n) is not None
@@ -29,6 +30,7 @@ def test_every_declared_symbol_is_exported(bbm):
 
 def test_binding_has_the_same_names(bbm):
     for n in ("bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs", "bbm_build_sparse_index",
+              "bbm_build_index",
               "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"):
         assert callable(getattr(bbm, n))
 
@@ -59,6 +61,11 @@ def test_index_builders_reject_bad_arguments(bbm):
     assert L.bbm_build_sparse_index(FAKE, 1, 4, 0, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
     assert L.bbm_build_sparse_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None, None) == bbm.BBM_EUNSUPPORTED
     assert L.bbm_build_sparse_index(FAKE, 1, 4, 4, FAKE, FAKE, C.c_void_p(0x1004), None) == bbm.BBM_EINVAL
+    # the one-call form reports the same errors as the two stages
+    assert L.bbm_build_index(FAKE, 1, 4, 4, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_index(FAKE, 1, 4, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_index(FAKE, 1, 4, 4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, C.c_void_p(0x1004), None) == bbm.BBM_EINVAL
+    assert L.bbm_build_index(FAKE, 1, 0, 4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
     assert bbm.bbm_sched_bytes(1, 4) == 4 * (8 + 12 * 4) and bbm.bbm_sched_bytes(0, 4) == 0
 
 

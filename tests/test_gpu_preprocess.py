@@ -14,7 +14,7 @@ def _bbm():
     return bbm
 
 
-def _run(mask_np, Br, Bc, row_stride=None):
+def _run(mask_np, Br, Bc, row_stride=None, fused=True):
     bbm = _bbm()
     Mb, N, _ = mask_np.shape
     if row_stride is None:
@@ -23,7 +23,7 @@ def _run(mask_np, Br, Bc, row_stride=None):
         buf = torch.zeros((Mb, N, row_stride), dtype=torch.uint8, device="cuda")
         buf[:, :, :N] = torch.from_numpy(mask_np).cuda()
         mask = buf[:, :, :N]
-    idx = bbm.build_index(mask, Br, Bc)
+    idx = bbm.build_index(mask, Br, Bc, fused=fused)      # one-call entry point, or runs and list separately
     torch.cuda.synchronize()
     return idx
 
@@ -36,10 +36,11 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("name,N,Br,Bc", CASES)
-def test_index_bit_exact_small_variants(name, N, Br, Bc):
+def test_index_bit_exact_small_variants(name, N, Br, Bc, fused):
     cfg = small_variant(name, N=N, B=2, H=1, with_qkv=False)
-    idx = _run(cfg["mask"], Br, Bc)
+    idx = _run(cfg["mask"], Br, Bc, fused=fused)
     assert_index_equal(index_to_numpy(idx), cfg["mask"], Br, Bc)
 
 
@@ -52,7 +53,7 @@ def test_index_bit_exact_ragged_sizes(N, Br, Bc):
     idx = _run(mask, Br, Bc)                       # rows not 16-byte aligned unless N % 16 == 0: byte path
     assert_index_equal(index_to_numpy(idx), mask, Br, Bc)
     stride = 16 * (-(-N // 16)) + 16
-    idx = _run(mask, Br, Bc, row_stride=stride)    # padded, aligned rows: vector path with a ragged tail
+    idx = _run(mask, Br, Bc, row_stride=stride, fused=False)    # padded, aligned rows: vector path with a ragged tail
     assert_index_equal(index_to_numpy(idx), mask, Br, Bc)
 
 
@@ -73,14 +74,15 @@ def test_long_rows_of_blocks_cross_ballot_chunks():
     mask[0, 128:192, 16 * 63:16 * 65] = 1           # two-block run straddling the boundary
     mask[0, 128:192, 16 * 100:16 * 102] = 1         # equal-length run later: leftmost must win
     mask[0, 192:256, 16 * 128:] = 1                 # run reaching the row end
-    idx = _run(mask, 64, Bc)
-    assert_index_equal(index_to_numpy(idx), mask, 64, Bc)
+    for fused in (True, False):
+        idx = _run(mask, 64, Bc, fused=fused)      # 36 rows x 3 chunks: still one launch when fused
+        assert_index_equal(index_to_numpy(idx), mask, 64, Bc)
 
 
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
 def test_index_bit_exact_full_size(name):
     cfg = make_config(name, with_qkv=False)
     for Br in (128, 64):
-        idx = _run(cfg["mask"], Br, 64)
+        idx = _run(cfg["mask"], Br, 64, fused=(Br == 128))
         assert_index_equal(index_to_numpy(idx), cfg["mask"], Br, 64)
         del idx
