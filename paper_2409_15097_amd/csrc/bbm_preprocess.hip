@@ -2,7 +2,7 @@
 // Masking"; Appendix A, block-based summation).  The sum of a block is only ever compared with 0 and with
 // Br*Bc, so the kernel carries an OR and an AND of the non-zero bits instead of a count.
 //
-// One work-group (4 wavefronts) owns one block row (Br mask rows) x 1024 mask columns.  A wavefront streams
+// One work-group (8 wavefronts) owns one block row (Br mask rows) x 1024 mask columns.  A wavefront streams
 // whole 1 KiB row segments (16 B per lane, fully coalesced); each lane turns its 16 bytes into 16 bits and
 // keeps a running OR / AND over the rows it sees.  The bits go to LDS as uint16 quarters of the 64-bit
 // words and leave word-column major, so the global writes of the packed mask are contiguous too.
@@ -10,8 +10,9 @@
 
 namespace {
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
+constexpr int kUnroll = 8;        // rows a lane has in flight
 constexpr int kColsPerWG = 1024;  // 64 lanes x 16 bytes
 constexpr int kWordsPerWG = kColsPerWG / 64;
 constexpr int kMaxBr = 256;
@@ -55,19 +56,19 @@ __global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* _
   uint32_t any16 = 0, all16 = 0xffffu;
   if (col < N) {
     int r = wave;
-    for (; r + 3 * kWaves < rows; r += 4 * kWaves) {  // four independent 16-byte loads in flight per lane
-      uint32_t b0 = load_bits16<ALIGNED>(base + (int64_t)r * row_stride, col, N);
-      uint32_t b1 = load_bits16<ALIGNED>(base + (int64_t)(r + kWaves) * row_stride, col, N);
-      uint32_t b2 = load_bits16<ALIGNED>(base + (int64_t)(r + 2 * kWaves) * row_stride, col, N);
-      uint32_t b3 = load_bits16<ALIGNED>(base + (int64_t)(r + 3 * kWaves) * row_stride, col, N);
-      any16 |= b0 | b1 | b2 | b3;
-      all16 &= b0 & b1 & b2 & b3;
+    for (; r + (kUnroll - 1) * kWaves < rows; r += kUnroll * kWaves) {  // kUnroll independent 16-byte loads in flight per lane
+      uint32_t b[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) b[u] = load_bits16<ALIGNED>(base + (int64_t)(r + u * kWaves) * row_stride, col, N);
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        any16 |= b[u];
+        all16 &= b[u];
+      }
       if (packed) {
         uint16_t* s = stage + ((lane >> 2) * BrP) * 4 + (lane & 3);
-        s[r * 4] = (uint16_t)b0;
-        s[(r + kWaves) * 4] = (uint16_t)b1;
-        s[(r + 2 * kWaves) * 4] = (uint16_t)b2;
-        s[(r + 3 * kWaves) * 4] = (uint16_t)b3;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) s[(r + u * kWaves) * 4] = (uint16_t)b[u];
       }
     }
     for (; r < rows; r += kWaves) {
@@ -87,9 +88,13 @@ __global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* _
   __syncthreads();
 
   if (wave == 0) {
-    uint32_t a = acc[0][lane], b = acc[1][lane], c = acc[2][lane], d = acc[3][lane];
-    uint32_t any_v = (a | b | c | d) & 0xffffu;
-    uint32_t all_v = (a & b & c & d) >> 16;
+    uint32_t any_v = 0, all_v = 0xffffu;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const uint32_t a = acc[w][lane];
+      any_v |= a & 0xffffu;
+      all_v &= a >> 16;
+    }
     const int g = Bc / 16;  // lanes per block column
     for (int s = 1; s < g; s <<= 1) {
       any_v |= __shfl_xor(any_v, s);
