@@ -275,18 +275,28 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_index_kernel(const uin
   __shared__ int tot_s[4];            // list entries, non-empty rows, parts, cut rows
   __shared__ int gpre_s[kSmallPairs], wsum_s[kSmallPairs / 64];
   __shared__ uint64_t full_s[kSmallPairs], nz_s[kSmallPairs];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: pair -> (row, chunk) arithmetic stays off the vector ALU
   const int CH = (nbc + 63) / 64, PP = nbr * CH, npairs = Mb * PP, nrows = Mb * nbr;
   const int64_t plane_entries = (int64_t)nbr * nbc;
   if (tid < 4) tot_s[tid] = 0;
 
+  // (row, chunk, plane) of the wave's first pair by division, of the following ones by counting (integer division is
+  // dozens of instructions)
+  const int r_first = wave * kSmallSlots / CH, ch_first = wave * kSmallSlots - r_first * CH, m_first = r_first / nbr;
   uint8_t v[kSmallSlots];
   uint64_t nz[kSmallSlots];
+  {
+    int r = r_first, ch = ch_first;
 #pragma unroll
-  for (int k = 0; k < kSmallSlots; ++k) {
-    const int p = wave * kSmallSlots + k;
-    const int r = p / CH, col = (p - r * CH) * 64 + lane;
-    v[k] = (p < npairs && col < nbc) ? cls[(int64_t)r * nbc + col] : (uint8_t)0;
+    for (int k = 0; k < kSmallSlots; ++k) {
+      const int p = wave * kSmallSlots + k, col = ch * 64 + lane;
+      v[k] = (p < npairs && col < nbc) ? cls[(int64_t)r * nbc + col] : (uint8_t)0;
+      if (++ch == CH) {
+        ch = 0;
+        ++r;
+      }
+    }
   }
 #pragma unroll
   for (int k = 0; k < kSmallSlots; ++k) {
@@ -336,13 +346,18 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_index_kernel(const uin
       atomicAdd(&tot_s[1], 1);
     }
   }
+  {
+    int r = r_first, ch = ch_first, m = m_first;
 #pragma unroll
-  for (int k = 0; k < kSmallSlots; ++k) {
-    const int p = wave * kSmallSlots + k;
-    if (p < npairs && ((nz[k] >> lane) & 1ull)) {
-      const int r = p / CH, col = (p - r * CH) * 64 + lane;
-      col_idx[(int64_t)(r / nbr) * plane_entries + pos[p] + __popcll(nz[k] & ((1ull << lane) - 1ull))] =
-          (uint32_t)col | (v[k] == BBM_BLOCK_FULL ? 0x80000000u : 0u);
+    for (int k = 0; k < kSmallSlots; ++k) {
+      const int p = wave * kSmallSlots + k;
+      if (p < npairs && ((nz[k] >> lane) & 1ull))
+        col_idx[(int64_t)m * plane_entries + pos[p] + __popcll(nz[k] & ((1ull << lane) - 1ull))] =
+            (uint32_t)(ch * 64 + lane) | (v[k] == BBM_BLOCK_FULL ? 0x80000000u : 0u);
+      if (++ch == CH) {
+        ch = 0;
+        if (++r == (m + 1) * nbr) ++m;
+      }
     }
   }
   if (offset && tid < nrows) {  // run index: this thread walks the chunks of its row
