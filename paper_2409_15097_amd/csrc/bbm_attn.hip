@@ -221,24 +221,27 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   // Asynchronous global -> LDS copy (no registers in between).  One instruction moves 1 KiB per wave: lane l lands at
   // LDS base + 16*l, i.e. slot l / RC, chunk l % RC of the block, so it fetches row (block + NBLK * slot).
   const int g_row = lane / RC, g_chunk = lane % RC;
+  // Addresses are (uniform 64-bit tile base) + (32-bit per-lane byte offset): one register per lane, not a pair per copy.
+  const uint32_t g_off = (uint32_t)(g_row * NBLK * D + g_chunk * 8) * 2u;
   auto load_tile_async = [&](const __bf16* __restrict__ src, int jt, __bf16* dst, int blk_stride) {
     const int64_t key0 = (int64_t)jt * kBc;
+    const char* tile = reinterpret_cast<const char*>(src + key0 * D);
     if (key0 + kBc <= N) {
-      const __bf16* __restrict__ base = src + key0 * D + (g_row * NBLK * D + g_chunk * 8);
 #pragma unroll
       for (int n = 0; n < LPW; ++n) {
         const int q = n * NW + wave;  // block filled by this instruction
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(base + q * D),
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(tile + q * D * 2 + g_off),
                                          (void __attribute__((address_space(3)))*)(dst + q * blk_stride), 16, 0, 0);
       }
     } else {
       // Last tile of a ragged N.  Rows past N re-read row N-1: such keys sit in a tile that is never "full", the
       // element mask gives them probability exactly 0, and a finite duplicate row then adds nothing.
+      const int last = (int)(N - 1 - key0);  // last real row of the tile
 #pragma unroll
       for (int n = 0; n < LPW; ++n) {
         const int q = n * NW + wave;
-        const int64_t key = min(key0 + q + g_row * NBLK, N - 1);
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src + key * D + g_chunk * 8),
+        const uint32_t off = (uint32_t)(min(q + g_row * NBLK, last) * D + g_chunk * 8) * 2u;
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(tile + off),
                                          (void __attribute__((address_space(3)))*)(dst + q * blk_stride), 16, 0, 0);
       }
     }
