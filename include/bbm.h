@@ -127,11 +127,16 @@ int bbm_build_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nb
  *                    (row, part): plane*nbr + block row, first entry (position in the plane's list), entries, part,
  *                    parts of the row, number of the row's first part, index of the row among the cut rows, the list
  *                    entry at the part's first position.
- *                    The last 4*Mb*nbr ints are one 4-int record per (plane, rank): the block rows of a plane by list
- *                    length, longest first (ties: higher row first; planes with more than 4096 block rows: simply
- *                    last row first) -- the order in which LIST mode starts work-groups; a record holds the block
- *                    row, the position of its first entry in the plane's list, its number of entries and its first
- *                    list entry (-1 if it has none), i.e. all a work-group needs to start fetching.
+ *                    The last 4*Mb*nbr ints are one 4-int record per (plane, rank), in the order in which LIST mode
+ *                    starts the block rows of a plane: groups of 4 consecutive block rows if T = 32, i.e. while rows
+ *                    are short (neighbours share most of their key/value tiles, so they should run at the same time),
+ *                    else single rows (with long rows the plain longest-first order balances the tail better); the
+ *                    groups by the list length of their longest row, longest first (ties: the group of higher rows
+ *                    first), the rows of a group by list length, longest first (ties: higher row first); planes with
+ *                    more than 4096 block rows: simply last row first.
+ *                    A record holds the block row, the position of its first entry in the plane's list, its number of
+ *                    entries and its first list entry (-1 if it has none), i.e. all a work-group needs to start
+ *                    fetching.
  *                    It depends only on the mask, so it is shared by heads, layers and calls like the rest of the
  *                    index.
  * Requires nbr*nbc < 2^31 and Mb*nbr < 2^24.  Errors: BBM_EINVAL, BBM_EHIP.

@@ -107,6 +107,7 @@ SCHED_PART_INTS = 8
 SCHED_MIN_SPLIT = 32
 SCHED_MAX_SORT_ROWS = 4096
 SCHED_ROW_INTS = 4
+SCHED_GROUP_ROWS = 4
 
 
 def schedule(row_ptr, col_idx):
@@ -119,10 +120,14 @@ def schedule(row_ptr, col_idx):
     entry at the part's first position (as int32).
     A row with n > T entries is cut into ceil(n/T) parts of ceil(n/parts) entries (the last part takes the rest);
     rows with n <= T are not listed.  Table entries past the last part are unspecified.  The last 4*Mb*nbr entries
-    are one record of 4 ints per (plane, rank): the block rows of a plane ordered by list length, longest first,
-    ties broken towards the higher row (planes of more than 4096 block rows are listed from the last row to the
-    first instead); the record holds the block row, the position of its first list entry in the plane's list, its
-    number of entries, and its first list entry (-1 if it has none)."""
+    are one record of 4 ints per (plane, rank), in the order in which the block rows of a plane are started: the rows
+    are taken in groups of 4 consecutive rows if T = 32, i.e. while rows are short (neighbours share most of their
+    key/value tiles, so they should run at the same time), else one by one (with long rows the plain longest-first
+    order balances the tail better); the groups are ordered by the list length of their longest row, longest first
+    (ties: the group of higher rows first), the rows inside a group by list length, longest first (ties: higher row
+    first).  Planes of more than 4096
+    block rows are listed from the last row to the first instead.  A record holds the block row, the position of its
+    first list entry in the plane's list, its number of entries, and its first list entry (-1 if it has none)."""
     Mb, nbr1 = row_ptr.shape
     nbr = nbr1 - 1
     counts = [int(row_ptr[m, i + 1] - row_ptr[m, i]) for m in range(Mb) for i in range(nbr)]
@@ -136,7 +141,11 @@ def schedule(row_ptr, col_idx):
     for m in range(Mb):
         rows = list(range(nbr - 1, -1, -1))
         if nbr <= SCHED_MAX_SORT_ROWS:
-            rows.sort(key=lambda i: -counts[m * nbr + i])        # stable: equal lengths stay in descending row order
+            length = lambda i: counts[m * nbr + i]
+            gsz = SCHED_GROUP_ROWS if T == SCHED_MIN_SPLIT else 1
+            groups = [list(range(a, min(a + gsz, nbr))) for a in range(0, nbr, gsz)]
+            groups.sort(key=lambda g: (-max(length(i) for i in g), -g[0]))      # group of the longest row first; ties: higher rows
+            rows = [i for g in groups for i in sorted(g, key=lambda i: (-length(i), -i))]
         for rank, i in enumerate(rows):
             o = order_base + SCHED_ROW_INTS * (m * nbr + rank)
             c = counts[m * nbr + i]

@@ -129,11 +129,35 @@ __global__ __launch_bounds__(kWavesPerWG * 64) void list_fill_kernel(const uint8
   }
 }
 
+// Rows per launch-order group: neighbouring rows are kept together only while rows are short (split threshold at its
+// floor, i.e. mean list length <= 16); with long rows the plain longest-first order balances the tail better.
+__device__ __forceinline__ int launch_group_rows(int T) { return T == bbm::kSchedMinSplit ? bbm::kSchedGroupRows : 1; }
+
+// Position of block row i in the launch order of its plane.  len[0 .. nbr) = list lengths of the plane's rows,
+// gmax[0 .. ceil(nbr/gsz)) = longest list of every group of gsz consecutive rows.  Order: the group holding the longest
+// row first (ties: higher rows first); inside a group the longest row first (ties: higher row first).
+__device__ __forceinline__ int launch_rank(const int* len, const int* gmax, int nbr, int gsz, int i) {
+  const int ng = (nbr + gsz - 1) / gsz, g = i / gsz;
+  const int mine = gmax[g];
+  int before = 0;  // groups that go first
+  for (int gg = 0; gg < ng; ++gg) {
+    const int t = gmax[gg];
+    before += (t > mine) || (t == mine && gg > g);
+  }
+  int rank = before * gsz;
+  // the last group may be short; it is among the groups that go first iff its turn comes before g's
+  const int last = ng - 1, last_rows = nbr - last * gsz;
+  if (last != g && (gmax[last] > mine || gmax[last] == mine)) rank -= gsz - last_rows;
+  const int c = len[i];
+  for (int j = g * gsz; j < min(nbr, (g + 1) * gsz); ++j) rank += (len[j] > c) || (len[j] == c && j > i);
+  return rank;
+}
+
 // Split schedule of LIST mode (layout in bbm_internal.h).  Work-group 0 writes the header and the parts table: every
 // thread owns a contiguous range of block rows; pass 1 counts, per thread, the parts and the cut rows; an exclusive
 // scan over the threads turns the counts into positions; pass 2 writes the parts in (row, part) order, so the
-// result does not depend on the thread count.  Work-group 1 + m writes the row records of plane m, longest list
-// first, ranking by counting over the list lengths staged in LDS.
+// result does not depend on the thread count.  Work-group 1 + m writes the row records of plane m in launch order,
+// ranking by counting over the list lengths staged in LDS.
 constexpr int kSchedThreads = 256;
 
 __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __restrict__ row_ptr,
@@ -143,33 +167,8 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
   __shared__ int pre[2][kSchedThreads + 1];
   __shared__ int red[2][kSchedThreads];
   __shared__ int len_s[kSchedMaxSortRows];
+  __shared__ int gmax_s[kSchedMaxSortRows];
   const int tid = threadIdx.x;
-
-  if (blockIdx.x > 0) {
-    const int m = blockIdx.x - 1;
-    const int32_t* rp = row_ptr + (int64_t)m * (nbr + 1);
-    const uint32_t* list = col_idx + (int64_t)m * plane_entries;
-    int4* rec = reinterpret_cast<int4*>(sched + sched_order_base(Mb, nbr)) + (int64_t)m * nbr;
-    const bool sorted = nbr <= kSchedMaxSortRows;
-    if (sorted) {
-      for (int j = tid; j < nbr; j += kSchedThreads) len_s[j] = rp[j + 1] - rp[j];
-      __syncthreads();
-    }
-    for (int i = tid; i < nbr; i += kSchedThreads) {
-      const int p0 = rp[i], c = rp[i + 1] - p0;
-      int rank = nbr - 1 - i;
-      if (sorted) {
-        rank = 0;
-        for (int j = 0; j < nbr; ++j) {
-          const int cj = len_s[j];
-          rank += (cj > c) || (cj == c && j > i);
-        }
-      }
-      rec[rank] = make_int4(i, p0, c, c > 0 ? (int)list[p0] : -1);
-    }
-    return;
-  }
-
   const int nrows = Mb * nbr;
   const int per = (nrows + kSchedThreads - 1) / kSchedThreads;
   const int r_lo = min(nrows, tid * per), r_hi = min(nrows, r_lo + per);
@@ -178,7 +177,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
     return row_ptr + (int64_t)m * (nbr + 1) + i;
   };
 
-  // split threshold from the mean list length of the non-empty rows
+  // split threshold from the mean list length of the non-empty rows (every work-group needs it)
   int total = 0, nonempty = 0;
   for (int r = r_lo; r < r_hi; ++r) {
     const int32_t* rp = first_entry(r);
@@ -200,6 +199,31 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
   nonempty = red[1][0];
   const int mean = nonempty > 0 ? (total + nonempty - 1) / nonempty : 0;
   const int T = max(kSchedMinSplit, 2 * mean);
+
+  if (blockIdx.x > 0) {
+    const int m = blockIdx.x - 1;
+    const int32_t* rp = row_ptr + (int64_t)m * (nbr + 1);
+    const uint32_t* list = col_idx + (int64_t)m * plane_entries;
+    int4* rec = reinterpret_cast<int4*>(sched + sched_order_base(Mb, nbr)) + (int64_t)m * nbr;
+    const bool sorted = nbr <= kSchedMaxSortRows;
+    const int gsz = launch_group_rows(T);
+    if (sorted) {
+      for (int j = tid; j < nbr; j += kSchedThreads) len_s[j] = rp[j + 1] - rp[j];
+      __syncthreads();
+      for (int g = tid; g * gsz < nbr; g += kSchedThreads) {
+        int t = 0;
+        for (int j = g * gsz; j < min(nbr, (g + 1) * gsz); ++j) t = max(t, len_s[j]);
+        gmax_s[g] = t;
+      }
+      __syncthreads();
+    }
+    for (int i = tid; i < nbr; i += kSchedThreads) {
+      const int p0 = rp[i], c = rp[i + 1] - p0;
+      const int rank = sorted ? launch_rank(len_s, gmax_s, nbr, gsz, i) : nbr - 1 - i;
+      rec[rank] = make_int4(i, p0, c, c > 0 ? (int)list[p0] : -1);
+    }
+    return;
+  }
 
   int nparts = 0, ncut = 0;
   for (int r = r_lo; r < r_hi; ++r) {
@@ -271,6 +295,7 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_index_kernel(const uin
   __shared__ int pc[kSmallPairs];     // non-zero blocks of a pair
   __shared__ int pos[kSmallPairs];    // position of the pair's first entry in the plane's list
   __shared__ int len_s[kSmallPairs];  // list length of a row
+  __shared__ int gmax_s[kSmallPairs]; // longest list of a launch-order group (groups never span planes)
   __shared__ int np_s[kSmallPairs];   // parts of a row (0 = not cut)
   __shared__ int tot_s[4];            // list entries, non-empty rows, parts, cut rows
   __shared__ int gpre_s[kSmallPairs], wsum_s[kSmallPairs / 64];
@@ -397,6 +422,13 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_index_kernel(const uin
     atomicAdd(&tot_s[2], np);
     atomicAdd(&tot_s[3], 1);
   }
+  const int gsz = launch_group_rows(T), ngp = (nbr + gsz - 1) / gsz;  // launch-order groups: rows each, groups per plane
+  if (tid < Mb * ngp) {
+    const int m = tid / ngp, g = tid - m * ngp;
+    int t = 0;
+    for (int j = g * gsz; j < min(nbr, (g + 1) * gsz); ++j) t = max(t, len_s[m * nbr + j]);
+    gmax_s[tid] = t;
+  }
   __syncthreads();
   if (tid == 0) {
     sched[kSchedNParts] = tot_s[2];
@@ -425,12 +457,7 @@ __global__ __launch_bounds__(kSmallWaves * 64) void small_index_kernel(const uin
         rec[7] = entry_at(tid, k * chunk);
       }
     }
-    int rank = 0;
-#pragma unroll 8
-    for (int j = 0; j < nbr; ++j) {
-      const int cj = len_s[m * nbr + j];
-      rank += (cj > c) || (cj == c && j > i);
-    }
+    const int rank = launch_rank(len_s + m * nbr, gmax_s + m * ngp, nbr, gsz, i);
     reinterpret_cast<int4*>(sched + sched_order_base(Mb, nbr))[(int64_t)m * nbr + rank] =
         make_int4(i, start, c, entry_at(tid, 0));
   }

@@ -30,16 +30,19 @@ inline int launch_status(const char* what) {
 //   [kSchedPartBase + 8*q]   part q (ordered by row, then part): row (= plane*nbr + block row), first entry in the
 //                            plane's list, entries, part index, parts of the row, q of the row's first part, index
 //                            of the row among the cut rows, list entry at the part's first position
-//   [order_base + 4*(m*nbr + k)]  record of the block row of plane m with the k-th longest list (ties: higher row
-//                            first): block row, position of its first entry in the plane's list, entries, first list
-//                            entry (-1 if none); order_base = kSchedPartBase + 8*Mb*nbr; planes with more than
-//                            kSchedMaxSortRows block rows are simply listed from the last row to the first
+//   [order_base + 4*(m*nbr + k)]  record of the k-th block row of plane m in launch order: block row, position of
+//                            its first entry in the plane's list, entries, first list entry (-1 if none);
+//                            order_base = kSchedPartBase + 8*Mb*nbr.  Launch order: groups of kSchedGroupRows
+//                            consecutive rows if T is at its floor, else single rows; the group holding the longest row
+//                            first (ties: higher rows first), inside a group the longest row first (ties: higher row first); planes with more
+//                            than kSchedMaxSortRows block rows are simply listed from the last row to the first
 constexpr int kSchedNParts = 0, kSchedSplitT = 1, kSchedNCutRows = 2;
 constexpr int kSchedPartBase = 8;
 constexpr int kSchedPartInts = 8;
 constexpr int kSchedMinSplit = 32;
 constexpr int kSchedMaxSortRows = 4096;
 constexpr int kSchedRowInts = 4;
+constexpr int kSchedGroupRows = 4;
 __host__ __device__ inline int64_t sched_order_base(int64_t Mb, int64_t nbr) { return kSchedPartBase + kSchedPartInts * Mb * nbr; }
 __host__ __device__ inline int64_t sched_ints(int64_t Mb, int64_t nbr) { return sched_order_base(Mb, nbr) + kSchedRowInts * Mb * nbr; }
 

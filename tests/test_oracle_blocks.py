@@ -184,12 +184,39 @@ def test_schedule_cuts_only_long_rows():
     assert _sched([[0, 1, 34]])[:3].tolist() == [0, 34, 0]
     assert _sched([[0, 1, 2, 3, 43]])[:3].tolist() == [2, 32, 1]
     assert _sched([[0, 5, 10, 15]])[0] == 0          # uniform rows: nothing cut
-    # row records (row, first position, entries, first entry): lengths 3, 0, 40, 5 -> rows 2, 3, 0, 1; an empty row has
-    # first entry -1; equal lengths -> higher row first (causal masks: last row first)
+    # row records (row, first position, entries, first entry) in launch order.  Up to 4 rows are one group: rows by
+    # length, longest first: lengths 3, 0, 40, 5 -> rows 2, 3, 0, 1; an empty row has first entry -1; equal lengths ->
+    # higher row first (causal masks: last row first)
     assert s[-16:].reshape(4, 4).tolist() == [[2, 3, 40, 3 - 2**31], [3, 43, 5, 43 - 2**31], [0, 0, 3, 0], [1, 3, 0, -1]]
     s2 = _sched([[0, 5, 10, 15], [0, 1, 3, 6]])
     assert s2[-24:].reshape(6, 4).tolist() == [[2, 10, 5, 10], [1, 5, 5, 5 - 2**31], [0, 0, 5, 0],
                                               [2, 3, 3, 1003 - 2**31], [1, 1, 2, 1001 - 2**31], [0, 0, 1, 1000]]
+
+
+def test_schedule_launch_order_groups_of_four_rows():
+    # 11 rows: groups {0..3}, {4..7}, {8..10} whose longest rows have 2, 30, 5 entries -> groups 1, 2, 0; inside group 1
+    # the 30-entry row 6 first, then the equal rows from the highest down
+    lens = [2] * 4 + [1] * 4 + [5] * 3
+    lens[6] = 30
+    rp = np.zeros((1, 12), dtype=np.int32)
+    rp[0, 1:] = np.cumsum(lens)
+    s = oracle.schedule(rp, _fake_lists(rp, 128))
+    order = s[-4 * 11:].reshape(11, 4)
+    assert order[:, 0].tolist() == [6, 7, 5, 4, 10, 9, 8, 3, 2, 1, 0]
+    assert all(order[k, 1] == rp[0, order[k, 0]] and order[k, 2] == lens[order[k, 0]] for k in range(11))
+    lens2 = [1] * 8                                        # two groups with equal longest rows: the higher rows first
+    rp2 = np.zeros((1, 9), dtype=np.int32)
+    rp2[0, 1:] = np.cumsum(lens2)
+    assert oracle.schedule(rp2, _fake_lists(rp2, 32))[-32:].reshape(8, 4)[:, 0].tolist() == list(range(7, -1, -1))
+    # the longest row decides, not the total: group {0..3} = 9 + 1 + 1 + 1 goes before group {4..7} = 4 x 8
+    rp3 = np.zeros((1, 9), dtype=np.int32)
+    rp3[0, 1:] = np.cumsum([9, 1, 1, 1, 8, 8, 8, 8])
+    assert oracle.schedule(rp3, _fake_lists(rp3, 64))[-32:].reshape(8, 4)[:, 0].tolist() == [0, 3, 2, 1, 7, 6, 5, 4]
+    # long rows (mean 30 -> T = 60 > 32): no grouping, plain longest-first order
+    rp4 = np.zeros((1, 7), dtype=np.int32)
+    rp4[0, 1:] = np.cumsum([40, 10, 30, 20, 50, 30])
+    s4 = oracle.schedule(rp4, _fake_lists(rp4, 256))
+    assert s4[1] == 60 and s4[-24:].reshape(6, 4)[:, 0].tolist() == [4, 0, 5, 2, 3, 1]
 
 
 def test_schedule_parts_tile_each_cut_row_exactly():
