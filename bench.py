@@ -45,8 +45,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--Br", type=int, default=128)
-    ap.add_argument("--masks", default="C2,C3,C4,C5,C0d,C0c,C0d128,C0c128",
-                    help="comma list of extra per-mask rows (empty string = none)")
+    ap.add_argument("--masks", default="",
+                    help="comma list of extra workloads measured the same way and reported under per_mask, or 'all' "
+                         "(C3,C4,C5,C0d,C0c,C0d128,C0c128); default: the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-kernel", default="", help="profile helper: run only 'attn', 'preprocess' or 'copy' (256 MiB device copy) launches")
     return ap.parse_args()
@@ -126,29 +127,36 @@ def measure_mask(bbm, name, Br, warmup, steps, torch):
 
 
 def cpu_baseline(cfg, Br, budget_s=20.0):
-    """The fp64 oracle, as it stands, on a bounded sample of the headline workload: (batch 0, first heads)."""
+    """The fp64 oracle, as it stands, on a bounded sample of the headline workload: whole (batch entry, head) slices,
+    batch entry by batch entry, until the time budget is used up (the whole workload if it fits)."""
     import oracle
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    N, d, H = cfg["N"], cfg["d"], cfg["H"]
-    q, k, v, mask = cfg["q"][:1], cfg["k"][:1], cfg["v"][:1], cfg["mask"][:1]
-    t0 = time.perf_counter()
-    idx = oracle.block_index(mask, Br, 64)
-    t_idx = time.perf_counter() - t0
-    tiles_per_head = int(idx["nz_cnt"].sum())
-    heads, t_attn = 0, 0.0
-    while heads < H and t_attn < budget_s:
+    N, d, H, B = cfg["N"], cfg["d"], cfg["H"], cfg["B"]
+    Mb = cfg["mask"].shape[0]
+    slices, flops, t_idx, t_attn = 0, 0.0, 0.0, 0.0
+    for b in range(B):
+        mask = cfg["mask"][b:b + 1] if Mb == B else cfg["mask"][:1]
         t0 = time.perf_counter()
-        oracle.masked_attention(q[:, heads:heads + 1], k[:, heads:heads + 1], v[:, heads:heads + 1], mask)
-        t_attn += time.perf_counter() - t0
-        heads += 1
-    flops = 4.0 * Br * 64 * d * tiles_per_head * heads
+        idx = oracle.block_index(mask, Br, 64)
+        t_idx += time.perf_counter() - t0
+        tiles_per_head = int(idx["nz_cnt"].sum())
+        for h in range(H):
+            if t_idx + t_attn >= budget_s:
+                break
+            t0 = time.perf_counter()
+            oracle.masked_attention(cfg["q"][b:b + 1, h:h + 1], cfg["k"][b:b + 1, h:h + 1], cfg["v"][b:b + 1, h:h + 1], mask)
+            t_attn += time.perf_counter() - t0
+            slices += 1
+            flops += 4.0 * Br * 64 * d * tiles_per_head
+        if t_idx + t_attn >= budget_s:
+            break
     return dict(value=flops / (t_idx + t_attn) / 1e12, unit="TFLOP/s (visited tiles)", cores=int(threads), kind="oracle",
-                sample=f"batch entry 0, {heads} of {H} heads of {cfg['name']} (N={N}, d={d}): block index once "
-                       f"({t_idx:.2f} s) + dense fp64 masked attention ({t_attn:.2f} s)",
+                sample=f"{slices} of {B * H} (batch entry, head) slices of {cfg['name']} (N={N}, d={d}): block index per batch "
+                       f"entry ({t_idx:.2f} s) + dense fp64 masked attention ({t_attn:.2f} s)",
                 seconds=t_idx + t_attn, host_cpus=os.cpu_count())
 
 
@@ -190,7 +198,8 @@ def main():
 
     main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch)
     rows = [main_res]
-    for name in [m for m in a.masks.split(",") if m and m != a.workload]:
+    extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128" if a.masks == "all" else a.masks
+    for name in [m for m in extra.split(",") if m and m != a.workload]:
         r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch)
         rows.append(r)
 
