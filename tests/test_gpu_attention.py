@@ -153,3 +153,37 @@ def test_full_size_sampled_rows(name):
         # properties that hold at any size: fully masked rows are exactly zero
         if empty.size:
             assert torch.all(o[0, :, torch.from_numpy(empty).cuda()] == 0)
+
+
+def test_tile_lists_longer_than_one_window():
+    """nbc = 1025 block columns: every schedule needs a second window of its LDS tile list (window = 1024 entries).
+    All-ones mask built on the device; the oracle evaluates sampled rows (plain softmax rows here)."""
+    bbm = _bbm()
+    N, d, Br = 65600, 64, 128                       # 1025 x 64 columns; 512.5 x 128 rows: the last block row is ragged
+    q, k, v = make_qkv(1, 1, N, d, seed=11)
+    mask = torch.ones((1, N, N), dtype=torch.uint8, device="cuda")
+    idx = bbm.build_index(mask, Br, 64)
+    torch.cuda.synchronize()
+    nbr, nbc = idx.nbr, idx.nbc
+    assert (nbr, nbc) == (513, 1025)
+    cls = idx.blk_class.cpu().numpy()
+    assert np.all(cls[0, :-1] == 2) and np.all(cls[0, -1] == 1)           # the ragged block row holds padding: partial
+    assert np.array_equal(idx.row_ptr.cpu().numpy()[0], 1025 * np.arange(nbr + 1))
+    ci = idx.col_idx.cpu().numpy().view(np.uint32)[:nbr * nbc].reshape(nbr, nbc)
+    assert np.array_equal(ci[:-1], np.broadcast_to(np.arange(nbc, dtype=np.uint32) | np.uint32(1 << 31), (nbr - 1, nbc)))
+    assert np.array_equal(ci[-1], np.arange(nbc, dtype=np.uint32))
+    sched = idx.sched.cpu().numpy()
+    assert sched[0] == 0 and sched[1] == 2050                             # nothing cut: rows are walked window by window
+    rows = [(0, 0, r) for r in (0, 1, 127, 128, 4097, 33000, 65471, 65472, 65535, 65536, 65599)]
+    ones_rows = np.broadcast_to(np.ones((1, 1, N), dtype=np.uint8), (1, N, N))
+    O_ref, lse_ref = oracle.masked_attention_rows(q, k, v, ones_rows, rows)
+    qt, kt, vt = (bf16_tensor(x) for x in (q, k, v))
+    ri = torch.tensor([r for _, _, r in rows], device="cuda")
+    for mode in ("LIST", "RUNS", "BITMAP"):
+        print(f"two-window lists, mode={mode}", flush=True)
+        o, lse = bbm.bbm_attn_fwd(qt, kt, vt, idx, mode=_mode(bbm, mode))
+        torch.cuda.synchronize()
+        err = np.abs(bf16_result_to_f64(o[0, 0, ri]) - O_ref)
+        assert err.max() <= O_MAX_ABS and err.mean() <= O_MEAN_ABS
+        assert np.abs(lse[0, 0, ri].cpu().numpy().astype(np.float64) - lse_ref).max() <= LSE_MAX_ABS
+        assert not torch.isnan(o.float()).any()
