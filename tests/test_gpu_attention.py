@@ -187,3 +187,28 @@ def test_tile_lists_longer_than_one_window():
         assert err.max() <= O_MAX_ABS and err.mean() <= O_MEAN_ABS
         assert np.abs(lse[0, 0, ri].cpu().numpy().astype(np.float64) - lse_ref).max() <= LSE_MAX_ABS
         assert not torch.isnan(o.float()).any()
+
+
+@pytest.mark.parametrize("Br", [64, 128, 256])
+def test_cut_rows_with_a_mask_shared_by_the_batch(Br):
+    """A few block rows with 64 tiles among rows with 3: the split schedule cuts them into parts that several
+    work-groups compute and one merges; the mask is shared by B = 3 batch entries (parts x (batch, head) items)."""
+    B, H, N, d = 3, 2, 4096, 64
+    q, k, v = make_qkv(B, H, N, d, seed=21)
+    i = np.arange(N)
+    m = (np.abs(i[:, None] - i[None, :]) <= 70).astype(np.uint8)
+    m[300:340] = 1                                   # "global" query rows that see every key
+    m[2000:2003, ::3] = 1                            # and a sparse long row: every tile partial
+    m[3900:3910] = 0                                 # fully masked rows
+    cfg = dict(q=q, k=k, v=v, mask=m[None])
+    bbm = _bbm()
+    idx = bbm.build_index(torch.from_numpy(cfg["mask"]).cuda(), Br, 64)
+    sched = idx.sched.cpu().numpy()
+    assert sched[0] >= 4 and sched[2] >= 2           # parts exist, from at least two cut rows
+    O_ref, lse_ref = oracle.masked_attention(q, k, v, cfg["mask"])
+    for mode in ("LIST", "AUTO", "BITMAP"):
+        o, lse = _gpu_attn(cfg, Br, mode)
+        assert_attention_close(o, lse, O_ref, lse_ref)
+    o1, l1 = _gpu_attn(cfg, Br, "LIST")              # merging in part order: the same bits on every run
+    o2, l2 = _gpu_attn(cfg, Br, "LIST")
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(l1, l2)
