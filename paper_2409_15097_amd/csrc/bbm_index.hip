@@ -276,6 +276,188 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
   }
 }
 
+// The same products for the smallest class matrices -- at most 64 block rows per plane, at most 256 block columns in
+// whole 16-byte groups, at most 16 planes (4 planes of a 4096 x 4096 mask in 128 x 64 or 64 x 64 tiles) -- with one
+// WAVE per plane and one LANE per block row: a lane reads its row as 16-byte words and turns it into a non-zero and a
+// full bit mask in registers, so counting, run search and list positions need no ballots and no LDS; row_ptr is a
+// shuffle scan over the lanes.  Only the split threshold (a mean over all planes) and the launch-order ranks cross
+// lanes through LDS, behind two barriers.
+constexpr int kTinyMaxPlanes = 16, kTinyMaxRows = 64, kTinyMaxChunks = 4;
+
+// 16 class bytes -> 16 bits: bit t = (byte t != 0) in the low half, (byte t == BBM_BLOCK_FULL) in the high half.
+__device__ __forceinline__ uint32_t class_bits16(uint4 x) {
+  auto nz4 = [](uint32_t w) {  // 4 bytes -> 4 bits (bit t = byte t non-zero)
+    const uint32_t y = (((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w) & 0x80808080u;
+    return (((y >> 7) * 0x00204081u) >> 21) & 0xfu;
+  };
+  const uint32_t f = 0x01010101u * BBM_BLOCK_FULL;
+  const uint32_t nz = nz4(x.x) | (nz4(x.y) << 4) | (nz4(x.z) << 8) | (nz4(x.w) << 12);
+  const uint32_t ne = nz4(x.x ^ f) | (nz4(x.y ^ f) << 4) | (nz4(x.z ^ f) << 8) | (nz4(x.w ^ f) << 12);  // byte != FULL
+  return nz | ((~ne & 0xffffu) << 16);
+}
+
+__device__ __forceinline__ int wave_excl_scan(int x, int lane) {  // exclusive prefix sum over the 64 lanes
+  int incl = x;
+  for (int d = 1; d < 64; d <<= 1) {
+    const int y = __shfl_up(incl, d);
+    if (lane >= d) incl += y;
+  }
+  return incl - x;
+}
+__device__ __forceinline__ int wave_sum(int x) {
+  for (int d = 32; d > 0; d >>= 1) x += __shfl_xor(x, d);
+  return x;
+}
+
+__global__ __launch_bounds__(kTinyMaxPlanes * 64) void tiny_index_kernel(const uint8_t* __restrict__ cls, int Mb, int nbr,
+                                                                        int nbc, int32_t* __restrict__ row_ptr,
+                                                                        uint32_t* __restrict__ col_idx,
+                                                                        int32_t* __restrict__ sched,
+                                                                        int32_t* __restrict__ offset,
+                                                                        int32_t* __restrict__ total_ones,
+                                                                        int32_t* __restrict__ nz_lo,
+                                                                        int32_t* __restrict__ nz_hi,
+                                                                        int32_t* __restrict__ nz_cnt) {
+  using namespace bbm;
+  __shared__ int tot_s[kTinyMaxPlanes][2];   // per plane: list entries, non-empty rows
+  __shared__ int part_s[kTinyMaxPlanes][2];  // per plane: parts, cut rows
+  __shared__ int len_s[kTinyMaxPlanes][kTinyMaxRows];
+  __shared__ int gmax_s[kTinyMaxPlanes][kTinyMaxRows];
+  const int lane = threadIdx.x & 63;
+  const int m = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // plane of this wave
+  const int i = lane;                                              // block row of this lane
+  const bool live = i < nbr;
+  const int CH = (nbc + 63) / 64;
+
+  // ---- the row as bit masks
+  uint64_t nz[kTinyMaxChunks], full[kTinyMaxChunks];
+  {
+    const uint4* rowp = reinterpret_cast<const uint4*>(cls + ((int64_t)m * nbr + (live ? i : 0)) * nbc);
+    const int words = nbc / 16;
+    uint4 w[kTinyMaxChunks * 4];
+#pragma unroll
+    for (int t = 0; t < kTinyMaxChunks * 4; ++t) w[t] = (live && t < words) ? rowp[t] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int ch = 0; ch < kTinyMaxChunks; ++ch) {
+      nz[ch] = full[ch] = 0;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint32_t b = class_bits16(w[4 * ch + t]);
+        nz[ch] |= (uint64_t)(b & 0xffffu) << (16 * t);
+        full[ch] |= (uint64_t)(b >> 16) << (16 * t);
+      }
+    }
+  }
+  int c = 0;
+#pragma unroll
+  for (int ch = 0; ch < kTinyMaxChunks; ++ch) c += __popcll(nz[ch]);
+
+  // ---- list: position by a scan over the rows of the plane, entries written row by row
+  const int start = wave_excl_scan(c, lane);
+  if (live) {
+    row_ptr[(int64_t)m * (nbr + 1) + i] = start;
+    if (i == nbr - 1) row_ptr[(int64_t)m * (nbr + 1) + nbr] = start + c;
+    uint32_t* out = col_idx + (int64_t)m * nbr * nbc + start;
+#pragma unroll
+    for (int ch = 0; ch < kTinyMaxChunks; ++ch) {
+      uint64_t x = nz[ch];
+      while (x) {
+        const int b = ctz64(x);
+        *out++ = (uint32_t)(64 * ch + b) | (((full[ch] >> b) & 1ull) ? 0x80000000u : 0u);
+        x &= x - 1;
+      }
+    }
+    if (offset) {  // run index
+      RunScan rs;
+      for (int ch = 0; ch < CH; ++ch) rs.feed(full[ch], nz[ch], 64 * ch);
+      rs.finish();
+      offset[m * nbr + i] = rs.best_start;
+      total_ones[m * nbr + i] = rs.best_len;
+      nz_lo[m * nbr + i] = rs.lo;
+      nz_hi[m * nbr + i] = rs.hi;
+      nz_cnt[m * nbr + i] = rs.cnt;
+    }
+  }
+  if (!sched) return;
+
+  // ---- schedule (same definition as sched_kernel)
+  const int plane_total = wave_sum(c), plane_nonempty = wave_sum(c > 0 ? 1 : 0);
+  if (lane == 0) {
+    tot_s[m][0] = plane_total;
+    tot_s[m][1] = plane_nonempty;
+  }
+  if (live) len_s[m][i] = c;
+  __syncthreads();
+  int total = 0, nonempty = 0;
+  for (int p = 0; p < Mb; ++p) {
+    total += tot_s[p][0];
+    nonempty += tot_s[p][1];
+  }
+  const int mean = nonempty > 0 ? (total + nonempty - 1) / nonempty : 0;
+  const int T = max(kSchedMinSplit, 2 * mean);
+  const int np = c > T ? (c + T - 1) / T : 0;
+  const int q_in_plane = wave_excl_scan(np, lane), rho_in_plane = wave_excl_scan(np > 0 ? 1 : 0, lane);
+  const int plane_parts = wave_sum(np), plane_cut = wave_sum(np > 0 ? 1 : 0);
+  if (lane == 0) {
+    part_s[m][0] = plane_parts;
+    part_s[m][1] = plane_cut;
+  }
+  const int gsz = launch_group_rows(T), ngp = (nbr + gsz - 1) / gsz;
+  if (lane < ngp) {
+    int t = 0;
+    for (int j = lane * gsz; j < min(nbr, (lane + 1) * gsz); ++j) t = max(t, len_s[m][j]);
+    gmax_s[m][lane] = t;
+  }
+  __syncthreads();
+  int q = q_in_plane, rho = rho_in_plane, parts_all = 0, cut_all = 0;
+  for (int p = 0; p < Mb; ++p) {
+    if (p < m) {
+      q += part_s[p][0];
+      rho += part_s[p][1];
+    }
+    parts_all += part_s[p][0];
+    cut_all += part_s[p][1];
+  }
+  if (threadIdx.x == 0) {
+    sched[kSchedNParts] = parts_all;
+    sched[kSchedSplitT] = T;
+    sched[kSchedNCutRows] = cut_all;
+    for (int x = 3; x < kSchedPartBase; ++x) sched[x] = 0;
+  }
+  if (!live) return;
+  // list entry number n of this row, from the masks (the same value the fill above stored)
+  auto entry_at = [&](int n) {
+#pragma unroll
+    for (int ch = 0; ch < kTinyMaxChunks; ++ch) {
+      uint64_t x = nz[ch];
+      const int cnt = __popcll(x);
+      if (n < cnt) {
+        for (int t = 0; t < n; ++t) x &= x - 1;
+        const int b = ctz64(x);
+        return (int)((uint32_t)(64 * ch + b) | (((full[ch] >> b) & 1ull) ? 0x80000000u : 0u));
+      }
+      n -= cnt;
+    }
+    return -1;
+  };
+  if (np > 0) {
+    const int chunk = (c + np - 1) / np;
+    for (int k = 0; k < np; ++k) {
+      int32_t* rec = sched + kSchedPartBase + (int64_t)kSchedPartInts * (q + k);
+      rec[0] = m * nbr + i;
+      rec[1] = start + k * chunk;
+      rec[2] = min(chunk, c - k * chunk);
+      rec[3] = k;
+      rec[4] = np;
+      rec[5] = q;
+      rec[6] = rho;
+      rec[7] = entry_at(k * chunk);
+    }
+  }
+  const int rank = launch_rank(len_s[m], gmax_s[m], nbr, gsz, i);
+  reinterpret_cast<int4*>(sched + sched_order_base(Mb, nbr))[(int64_t)m * nbr + rank] = make_int4(i, start, c, entry_at(0));
+}
+
 // Whole sparse index (row_ptr, col_idx and, if asked for, the schedule), and if asked for the run index as well,
 // in ONE launch of one work-group, for class matrices of at most kSmallPairs (row, 64-column chunk) pairs -- e.g. 4 planes of a 4096 x 4096 mask in 128 x 64
 // tiles.  At this size the four launches of the general path cost far more than the work itself.  Pair p = (row r,
@@ -498,15 +680,32 @@ int launch_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, 
 }
 
 bool is_small(int64_t Mb, int64_t nbr, int64_t nbc) { return Mb * nbr * bbm::ceil_div(nbc, (int64_t)64) <= kSmallPairs; }
+bool is_tiny(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc) {
+  return Mb <= kTinyMaxPlanes && nbr <= kTinyMaxRows && nbc <= 64 * kTinyMaxChunks && nbc % 16 == 0 && bbm::aligned(blk_class, 16);
+}
+
+// One-launch paths for small class matrices; returns false if neither applies.
+bool launch_one_kernel(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* row_ptr, uint32_t* col_idx,
+                       int32_t* sched, int32_t* offset, int32_t* total_ones, int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt,
+                       hipStream_t s) {
+  if (is_tiny(blk_class, Mb, nbr, nbc)) {
+    tiny_index_kernel<<<1, (unsigned)Mb * 64, 0, s>>>(blk_class, (int)Mb, (int)nbr, (int)nbc, row_ptr, col_idx, sched, offset,
+                                                       total_ones, nz_lo, nz_hi, nz_cnt);
+    return true;
+  }
+  if (is_small(Mb, nbr, nbc)) {
+    small_index_kernel<<<1, kSmallWaves * 64, 0, s>>>(blk_class, (int)Mb, (int)nbr, (int)nbc, row_ptr, col_idx, sched, offset,
+                                                      total_ones, nz_lo, nz_hi, nz_cnt);
+    return true;
+  }
+  return false;
+}
 
 int launch_list(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* row_ptr, uint32_t* col_idx,
                 int32_t* sched, hipStream_t s) {
   using namespace bbm;
-  if (is_small(Mb, nbr, nbc)) {
-    small_index_kernel<<<1, kSmallWaves * 64, 0, s>>>(blk_class, (int)Mb, (int)nbr, (int)nbc, row_ptr, col_idx, sched,
-                                                      nullptr, nullptr, nullptr, nullptr, nullptr);
-    return launch_status("bbm_build_sparse_index(small)");
-  }
+  if (launch_one_kernel(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, nullptr, nullptr, nullptr, nullptr, nullptr, s))
+    return launch_status("bbm_build_sparse_index(one launch)");
   const unsigned grid = (unsigned)ceil_div(Mb * nbr, kWavesPerWG);
   list_count_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr);
   int rc = launch_status("bbm_build_sparse_index(count)");
@@ -554,11 +753,8 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_index(const uint
   rc = check_list_args("bbm_build_index", blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched);
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (is_small(Mb, nbr, nbc)) {
-    small_index_kernel<<<1, kSmallWaves * 64, 0, s>>>(blk_class, (int)Mb, (int)nbr, (int)nbc, row_ptr, col_idx, sched, offset,
-                                                      total_ones, nz_lo, nz_hi, nz_cnt);
-    return launch_status("bbm_build_index(small)");
-  }
+  if (launch_one_kernel(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, offset, total_ones, nz_lo, nz_hi, nz_cnt, s))
+    return launch_status("bbm_build_index(one launch)");
   rc = launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, s);
   if (rc) return rc;
   return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, s);
