@@ -425,12 +425,40 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * P.scale + __logf(l_tot) : -INFINITY;
   };
 
-  const int split_T = SCHED ? P.sched[bbm::kSchedSplitT] : 0;  // requested early: needed only after other loads
+  // ---- which block row is this work-group's own?  Work-groups are handed to the 8 XCDs round-robin; give each XCD a
+  // contiguous range of logical ids so the row blocks of one head (which share K and V) meet in one XCD's L2.
+  // Launch order inside a group of G consecutive (batch, head) planes: rank-major, i.e. rank 0 of every plane of the
+  // group, then rank 1 of every plane, ...  The hardware starts work-groups in index order as slots free up, so
+  // with ranks sorted by length long rows start early everywhere and the short ones fill the tail.
+  int own_bh, own_m, own_rank;
+  {
+    const int wg = (int)blockIdx.x;
+    const int T = P.total_wgs;
+    const int xcd = wg & 7, slot = wg >> 3;
+    const int per = T >> 3, rem = T & 7;
+    const int logical = xcd * per + (xcd < rem ? xcd : rem) + slot;
+    const int grp = logical / (P.G * P.nbr), within = logical - grp * (P.G * P.nbr);
+    const int g_planes = min(P.G, T / P.nbr - grp * P.G);
+    own_rank = within / g_planes;
+    own_bh = grp * P.G + (within - own_rank * g_planes);
+    own_m = (P.Mb == 1) ? 0 : own_bh / P.H;
+  }
+  // LIST mode: the schedule's header (parts, split threshold) and this work-group's row record -- which block row has
+  // its rank, where its list lies and how it starts -- are requested together: one round trip, not three
+  int4 own_rec = make_int4(0, 0, 0, -1);
+  int nparts_all = 0, split_T = 0;
+  if (SCHED) {
+    static_assert(bbm::kSchedNParts == 0 && bbm::kSchedSplitT == 1, "the header is read as one 8-byte pair");
+    const int2 hdr = *reinterpret_cast<const int2*>(P.sched);
+    own_rec = *reinterpret_cast<const int4*>(P.sched + bbm::sched_order_base(P.Mb, P.nbr) +
+                                             bbm::kSchedRowInts * (int64_t)(own_m * P.nbr + own_rank));
+    nparts_all = hdr.x;
+    split_T = hdr.y;
+  }
   // ---- LIST mode, the first n_extra work-groups: before their own block row they serve the queue of cut-row parts
   // (nothing to do, and no cost, when the schedule cut no row)
   if (SCHED && (int)blockIdx.x < P.n_extra) {
     const int32_t* __restrict__ S = P.sched;
-  const int nparts_all = S[bbm::kSchedNParts];
   const int n_items = nparts_all * P.hbp;
   // The first item of a work-group is its own index; later ones come from the queue counter, which therefore stands
   // for "n_extra items already handed out".
@@ -498,34 +526,18 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   }
 
   {
-    // Work-groups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of logical ids so the
-    // row blocks of one head (which share K and V) meet in one XCD's L2.
-    const int wg = (int)blockIdx.x;
-    const int T = P.total_wgs;
-    const int xcd = wg & 7, slot = wg >> 3;
-    const int per = T >> 3, rem = T & 7;
-    const int logical = xcd * per + (xcd < rem ? xcd : rem) + slot;
-    // Launch order inside a group of G consecutive (batch, head) planes: rank-major, i.e. the longest row of every
-    // plane of the group, then the second longest of every plane, ...  The hardware starts work-groups in index
-    // order as slots free up, so long rows start early everywhere and the short ones fill the tail.
-    const int grp = logical / (P.G * P.nbr), within = logical - grp * (P.G * P.nbr);
-    const int g_planes = min(P.G, T / P.nbr - grp * P.G);
-    const int rank = within / g_planes;
-    bh = grp * P.G + (within - rank * g_planes);
-    m = (P.Mb == 1) ? 0 : bh / P.H;
+    bh = own_bh;
+    m = own_m;
     if (SCHED) {
-      // one record says which block row has this rank (longest list first), where its list lies and how it starts
-      const int4 rec = *reinterpret_cast<const int4*>(P.sched + bbm::sched_order_base(P.Mb, P.nbr) +
-                                                      bbm::kSchedRowInts * (int64_t)(m * P.nbr + rank));
-      i = rec.x;
-      const int n_list = rec.z;
+      i = own_rec.x;
+      const int n_list = own_rec.z;
       begin_item();
       if (n_list <= split_T) {  // a row the schedule cut belongs to the queue
-        if (n_list > 0) run_list(P.col_idx + (int64_t)m * P.nbr * P.nbc + rec.y, n_list, (uint32_t)rec.w);
+        if (n_list > 0) run_list(P.col_idx + (int64_t)m * P.nbr * P.nbc + own_rec.y, n_list, (uint32_t)own_rec.w);
         write_output();
       }
     } else {
-      i = P.nbr - 1 - rank;  // from the last row up: long rows first for causal-like masks
+      i = P.nbr - 1 - own_rank;  // from the last row up: long rows first for causal-like masks
       begin_item();
       const int nwin = num_windows(P, m, i);
       for (int win = 0; win < nwin; ++win) {
