@@ -196,6 +196,11 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   f32x16 oacc[DB];
   float m_run, l_run;
 
+  // Q through LDS needs a 32 x D staging slab per wave in the two buffers of parity 1 (two slabs each)
+  constexpr bool Q_VIA_LDS = NW <= 4;
+  bool q_pending = false;
+  const int g_row = lane / RC, g_chunk = lane % RC;  // row and 16-byte chunk this lane moves in a 1 KiB copy
+  auto q_stage = [&]() { return (wave / 2 == 0 ? k_s1 : v_s1) + (wave % 2) * 32 * D; };
   auto begin_item = [&]() {
     head_off = (int64_t)bh * N * D;
     Kg = P.k + head_off;
@@ -204,12 +209,32 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     q_ok = qrow < N;
     // packed mask words of this lane's query row (rows past N borrow row 0: their results are never stored)
     mrow = P.packed + (int64_t)m * P.W * N + (q_ok ? qrow : 0);
+    if constexpr (Q_VIA_LDS) {
+      // The wave's 32 x D slab of Q is one contiguous piece of memory: copy it asynchronously, 1 KiB per instruction,
+      // into this wave's staging slab (tile buffer 1, idle until the second tile is requested) and pick the MFMA
+      // fragments up from there in fetch_q.  Chunk j of row r lands at chunk position j ^ (r % RC) of row r.  Rows
+      // past N re-read row N-1 (their results are never stored).
+      const int64_t row0 = (int64_t)i * BR + wave * 32;
+      const char* slab = reinterpret_cast<const char*>(P.q + head_off + row0 * D);
+      const int last = (int)min<int64_t>(31, N - 1 - row0);  // >= 0 for every wave that owns a real row
+      __bf16* const stage = q_stage();
 #pragma unroll
-    for (int t = 0; t < KS; ++t) {
-      if (q_ok)
-        qf[t] = *reinterpret_cast<const bf16x8*>(P.q + head_off + qrow * D + 16 * t + 8 * hh);
-      else
-        for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)0.0f;
+      for (int n = 0; n < 32 / RPB; ++n) {
+        const int r = min(n * RPB + g_row, last);
+        const uint32_t off = (uint32_t)(r * D + ((g_chunk ^ (r % RC)) * 8)) * 2u;
+        if (last >= 0)
+          __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(slab + off),
+                                           (void __attribute__((address_space(3)))*)(stage + n * 512), 16, 0, 0);
+      }
+      q_pending = true;
+    } else {
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        if (q_ok)
+          qf[t] = *reinterpret_cast<const bf16x8*>(P.q + head_off + qrow * D + 16 * t + 8 * hh);
+        else
+          for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)0.0f;
+      }
     }
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -220,7 +245,6 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
 
   // Asynchronous global -> LDS copy (no registers in between).  One instruction moves 1 KiB per wave: lane l lands at
   // LDS base + 16*l, i.e. slot l / RC, chunk l % RC of the block, so it fetches row (block + NBLK * slot).
-  const int g_row = lane / RC, g_chunk = lane % RC;
   // Addresses are (uniform 64-bit tile base) + (32-bit per-lane byte offset): one register per lane, not a pair per copy.
   const uint32_t g_off = (uint32_t)(g_row * NBLK * D + g_chunk * 8) * 2u;
   auto load_tile_async = [&](const __bf16* __restrict__ src, int jt, __bf16* dst, int blk_stride) {
@@ -372,6 +396,13 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   // start_tile0 was already called for tiles_s[0].
   auto run_window = [&](int count, bool started) {
     if (!started) start_tile0(tiles_s[0]);
+    if (Q_VIA_LDS && q_pending) {  // first window of a block row: Q fragments out of the staging slab
+      __builtin_amdgcn_s_waitcnt(0);  // this wave's own copies have landed (no other wave touches its slab)
+      const __bf16* stage = q_stage();
+#pragma unroll
+      for (int t = 0; t < KS; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(stage + lq * D + (((2 * t + hh) ^ (lq % RC)) * 8));
+      q_pending = false;
+    }
     e1 = tiles_s[1];
     for (int it = 0; it < count; it += 2) {
       step(IntC<0>{}, it);
@@ -397,6 +428,11 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   // through LDS (the tile buffers are idle here: two slabs fit in each) so that the global stores are whole rows:
   // 16-byte chunk ch of row r sits at chunk position ch ^ (r % RC) of the row.
   auto write_output = [&]() {
+    if (Q_VIA_LDS && q_pending) {  // a block row without tiles: its Q copies still target the slabs staged in below
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      q_pending = false;
+    }
     const float l_tot = partner_sum(l_run);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     __bf16* const stage = ((wave >> 1) == 0 ? k_s0 : (wave >> 1) == 1 ? k_s1 : (wave >> 1) == 2 ? v_s0 : v_s1) + (wave & 1) * 32 * D;
