@@ -194,7 +194,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   const uint64_t* __restrict__ mrow;
   bf16x8 qf[KS];
   f32x16 oacc[DB];
+  // m_run: reference maximum of the row in exponent units (score * scale * log2 e; -inf before the first visible key);
+  // s_init: its negative (0 while m_run = -inf), replicated, as the start value of the score accumulators
   float m_run, l_run;
+  f32x16 s_init;
 
   // Q through LDS needs a 32 x D staging slab per wave in the two buffers of parity 1 (two slabs each)
   constexpr bool Q_VIA_LDS = NW <= 4;
@@ -234,6 +237,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
           qf[t] = *reinterpret_cast<const bf16x8*>(P.q + head_off + qrow * D + 16 * t + 8 * hh);
         else
           for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)0.0f;
+        for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)((float)qf[t][e] * c);
       }
     }
 #pragma unroll
@@ -241,6 +245,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
     m_run = -INFINITY;
     l_run = 0.0f;
+    for (int e = 0; e < 16; ++e) s_init[e] = 0.0f;
   };
 
   // Asynchronous global -> LDS copy (no registers in between).  One instruction moves 1 KiB per wave: lane l lands at
@@ -276,8 +281,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   // S^T = K Q^T for the 64 keys of one LDS tile x this wave's 32 queries
   auto qk = [&](const __bf16* ks, f32x16 (&s)[2]) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-      for (int e = 0; e < 16; ++e) s[kb][e] = 0.0f;
+    for (int kb = 0; kb < 2; ++kb) s[kb] = s_init;
 #pragma unroll
     for (int t = 0; t < KS; ++t) {
 #pragma unroll
@@ -349,26 +353,32 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     for (int kb = 0; kb < 2; ++kb)
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
     mx = partner_max(mx);
-    // The reference maximum m_run only moves when some row's maximum grew by more than kLazy (in log2 units):
-    // softmax is invariant to the reference, probabilities stay <= 2^kLazy, and the rescale of O is skipped.
-    if (__any((mx * c > m_run * c + kLazy) ? 1 : 0)) {
-      const float m_new = fmaxf(m_run, mx);
+    // The scores arrive relative to the reference (s = exponent - m_run).  The reference only moves when some row's
+    // maximum exceeds it by more than kLazy: softmax is invariant to the reference, probabilities stay <= 2^kLazy, and
+    // the rescale of O -- and here also the per-element subtraction -- is skipped on almost every tile.
+    if (__any(((m_run == -INFINITY) ? (mx > -INFINITY) : (mx > kLazy)) ? 1 : 0)) {
+      const float m_old = (m_run == -INFINITY) ? 0.0f : m_run;       // what the accumulators started from
+      const float m_new = fmaxf(m_run, m_old + mx);
       const float m_fin = (m_new == -INFINITY) ? 0.0f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_fin) * c);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);
+      const float shift = m_fin - m_old;
       l_run *= alpha;
       m_run = m_new;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s_init[e] = -m_fin;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        for (int e = 0; e < 16; ++e) s[kb][e] -= shift;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
         for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
     }
 
-    const float msc = ((m_run == -INFINITY) ? 0.0f : m_run) * c;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       bf16x8 pf;
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        pf[e] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[u / 2][8 * (u % 2) + e], c, -msc));
+      for (int e = 0; e < 8; ++e) pf[e] = (__bf16)__builtin_amdgcn_exp2f(s[u / 2][8 * (u % 2) + e]);
       // row sum of the ROUNDED probabilities (the same numbers the second product consumes), two per instruction
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
@@ -400,7 +410,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       __builtin_amdgcn_s_waitcnt(0);  // this wave's own copies have landed (no other wave touches its slab)
       const __bf16* stage = q_stage();
 #pragma unroll
-      for (int t = 0; t < KS; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(stage + lq * D + (((2 * t + hh) ^ (lq % RC)) * 8));
+      for (int t = 0; t < KS; ++t) {
+        qf[t] = *reinterpret_cast<const bf16x8*>(stage + lq * D + (((2 * t + hh) ^ (lq % RC)) * 8));
+        for (int e = 0; e < 8; ++e) qf[t][e] = (__bf16)((float)qf[t][e] * c);
+      }
       q_pending = false;
     }
     e1 = tiles_s[1];
@@ -458,7 +471,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       if (row0 + r < N) *reinterpret_cast<bf16x8*>(og + r * D + gco * 8) = ov;
     }
     if (q_ok && P.lse && hh == 0)
-      P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * P.scale + __logf(l_tot) : -INFINITY;
+      P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * (1.0f / kLog2e) + __logf(l_tot) : -INFINITY;
   };
 
   // ---- which block row is this work-group's own?  Work-groups are handed to the 8 XCDs round-robin; give each XCD a
@@ -537,7 +550,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
         l_run = 0.0f;
         for (int k = 0; k < nparts; ++k) {  // fixed order: the result does not depend on which part came last
           const float* rk = r0 + k * pstride;
-          const float wgt = __builtin_amdgcn_exp2f((rk[REGS * NT] - m_fin) * c);
+          const float wgt = __builtin_amdgcn_exp2f(rk[REGS * NT] - m_fin);
           l_run += wgt * rk[(REGS + 1) * NT];
 #pragma unroll
           for (int db = 0; db < DB; ++db)

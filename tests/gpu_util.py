@@ -52,7 +52,11 @@ def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
 
 
 # Tolerances for bf16 inputs/outputs against the fp64 oracle (max-abs, mean-abs on O; max-abs on finite lse).
-O_MAX_ABS, O_MEAN_ABS, LSE_MAX_ABS = 2e-2, 2e-3, 5e-3
+# lse: the kernel multiplies Q by scale*log2(e) and rounds it to bf16 once per block row (relative error <= 2^-9 per
+# element), which moves a score by at most 2^-9 * scale * sum_d |q_d k_d| (about 0.64 * sqrt(d) * 2^-9 = 1.0e-2 / 1.4e-2
+# for N(0,1) inputs at d = 64 / 128 if every rounding error had the same sign; a few 1e-3 in practice), and lse moves by
+# no more than the largest score error; the row sum adds bf16-rounded probabilities (<= 2^-9 relative, 2e-3).
+O_MAX_ABS, O_MEAN_ABS, LSE_MAX_ABS = 2e-2, 2e-3, 1.6e-2
 
 
 def assert_attention_close(o_gpu: torch.Tensor, lse_gpu: torch.Tensor, O_ref: np.ndarray, lse_ref: np.ndarray):

@@ -74,12 +74,21 @@ def test_ragged_sizes_with_empty_rows(N, d):
 
 
 def test_d128_small_tree_and_custom_scale():
+    """Other softmax scales.  The kernel rounds Q * scale * log2(e) to bf16, so a score moves by up to
+    2^-9 * scale * sum |q_d k_d|: the error bound grows with the scale, and the tolerances of a scale sharper than
+    1/sqrt(d) are widened by scale * sqrt(d)."""
     cfg = small_variant("C3", N=640, B=2, H=2)
+    d = cfg["q"].shape[-1]
     for scale in (None, 0.05, 0.3):
+        widen = 1.0 if scale is None else max(1.0, scale * d ** 0.5)
         O_ref, lse_ref = oracle.masked_attention(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], scale=scale)
         for mode in MODES:
             o, lse = _gpu_attn(cfg, 128, mode, scale=scale)
-            assert_attention_close(o, lse, O_ref, lse_ref)
+            err = np.abs(bf16_result_to_f64(o) - O_ref)
+            assert err.max() <= O_MAX_ABS * widen and err.mean() <= O_MEAN_ABS * widen
+            fin = np.isfinite(lse_ref)
+            got = lse.cpu().numpy().astype(np.float64)
+            assert np.array_equal(np.isfinite(got), fin) and np.abs(got[fin] - lse_ref[fin]).max() <= LSE_MAX_ABS * widen
 
 
 def test_key_permutation_changes_blocks_but_not_output():
