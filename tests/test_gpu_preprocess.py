@@ -79,6 +79,21 @@ def test_long_rows_of_blocks_cross_ballot_chunks():
         assert_index_equal(index_to_numpy(idx), mask, 64, Bc)
 
 
+def test_more_block_rows_than_the_schedule_sorts():
+    """Br = 1 gives 4200 block rows (> 4096): the schedule lists them from the last row to the first, unsorted."""
+    N = 4200
+    rng = np.random.default_rng(5)
+    mask = (rng.random((1, N, N)) < 0.002).astype(np.uint8)
+    mask[0, 100:110] = 1                            # a few full-width rows: long lists that the schedule cuts
+    mask[0, 3000:3003, ::2] = 1
+    for fused in (True, False):
+        idx = _run(mask, 1, 64, fused=fused)
+        got = index_to_numpy(idx)
+        assert_index_equal(got, mask, 1, 64)
+        assert got["sched"][0] > 0                  # parts exist
+        assert np.array_equal(got["sched"][-4 * N:].reshape(N, 4)[:, 0], np.arange(N - 1, -1, -1))
+
+
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
 def test_index_bit_exact_full_size(name):
     cfg = make_config(name, with_qkv=False)
