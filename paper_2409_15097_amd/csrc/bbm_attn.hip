@@ -325,13 +325,15 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     __bf16* const k_oth = PB ? k_s0 : k_s1;
     __bf16* const v_cur = PB ? v_s1 : v_s0;
     __bf16* const v_oth = PB ? v_s0 : v_s1;
+    f32x16 s[2];
+    qk(k_cur, s);
+    // the next tile's copies are requested behind the first product: their address arithmetic runs while the matrix
+    // pipe works (about 1 % on dense masks)
     if (e1 != kNoTile) {
       load_tile_async(Kg, tile_of(e1), k_oth, KBLK);
       load_tile_async(Vg, tile_of(e1), v_oth, VBLK);
       if ((e1 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e1) * N];
     }
-    f32x16 s[2];
-    qk(k_cur, s);
 
     // ---- element mask (only where the schedule cannot rule out zeros): keep s where the bit is set, else -inf
     if ((e0 >> 31) == 0) {
