@@ -188,8 +188,9 @@ size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
  *                    disturbed, so the same workspace can serve any number of later calls (of any shape that fits)
  *                    without being cleared again.  Two calls that overlap in time (different streams) must not
  *                    share a workspace.
- * Arithmetic: QK^T and PV on bf16 MFMA with fp32 accumulation; softmax statistics in fp32; P rounded to
- * bf16 before PV.  Deterministic: the same inputs give bit-identical outputs (in LIST mode the parts of a cut row
+ * Arithmetic: QK^T and PV on bf16 MFMA with fp32 accumulation; Q is multiplied by softmax_scale*log2(e) and
+ * rounded to bf16 once, so the first product yields base-2 exponents directly; softmax statistics in fp32; P rounded
+ * to bf16 before PV and the row sum adds the rounded P.  Deterministic: the same inputs give bit-identical outputs (in LIST mode the parts of a cut row
  * are taken from a queue in whatever order work-groups become free, but each part's arithmetic and the order in
  * which the parts are merged are fixed).
  * Errors: BBM_EINVAL, BBM_EUNSUPPORTED (d / Br / Bc without a kernel instance), BBM_EWORKSPACE, BBM_EHIP.
