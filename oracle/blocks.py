@@ -13,6 +13,9 @@ formulation) with the readings this build fixes where the paper is silent:
 * nz_lo / nz_hi / nz_cnt = first non-zero block, one past the last, and their number ((0,0,0) if none);
 * sparse list: row_ptr[i+1]-row_ptr[i] = nz_cnt[i]; col_idx ascending, bit 31 set iff the block is class 2;
   plane m of col_idx starts at m*nbr*nbc (fixed capacity), row_ptr is per plane and starts at 0;
+* column list (for the backward pass, which walks the queries of a key block): col_ptr[j+1]-col_ptr[j] = number of
+  non-zero blocks of block column j; row_idx ascending block rows, bit 31 set iff the block is class 2; plane m of
+  row_idx starts at m*nbr*nbc, col_ptr is per plane and starts at 0;
 * packed[m][w][r] bit t (little-endian in a uint64) = (mask[m][r][64*w + t] != 0), zero beyond column N.
 """
 import numpy as np
@@ -89,6 +92,23 @@ def sparse_index(cls):
                     p += 1
             row_ptr[m, i + 1] = p
     return row_ptr, col_idx
+
+
+def column_index(cls):
+    """cls [Mb,nbr,nbc] -> col_ptr int32 [Mb,nbc+1], row_idx uint32 [Mb*nbr*nbc] (unused tail entries = 0)."""
+    Mb, nbr, nbc = cls.shape
+    col_ptr = np.zeros((Mb, nbc + 1), dtype=np.int32)
+    row_idx = np.zeros(Mb * nbr * nbc, dtype=np.uint32)
+    for m in range(Mb):
+        p = 0
+        for j in range(nbc):
+            for i in range(nbr):
+                c = cls[m, i, j]
+                if c != 0:
+                    row_idx[m * nbr * nbc + p] = i | (0x80000000 if c == 2 else 0)
+                    p += 1
+            col_ptr[m, j + 1] = p
+    return col_ptr, row_idx
 
 
 def packed_bits(mask):
@@ -173,4 +193,5 @@ def block_index(mask, Br, Bc):
     idx.update(run_index(cls))
     idx["row_ptr"], idx["col_idx"] = sparse_index(cls)
     idx["sched"] = schedule(idx["row_ptr"], idx["col_idx"])
+    idx["col_ptr"], idx["row_idx"] = column_index(cls)
     return idx

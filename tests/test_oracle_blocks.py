@@ -130,6 +130,37 @@ def test_sparse_index_planes_have_fixed_capacity():
     assert ci[0] == 2 and ci[6] == 0x80000000 and ci[7] == 1 and ci.size == 12
 
 
+def test_column_index_hand_example_and_plane_capacity():
+    cls = np.array([[[2, 2, 0, 2],
+                     [1, 2, 0, 0],
+                     [0, 1, 0, 2]]], dtype=np.uint8)
+    cp, ri = oracle.column_index(cls)
+    F = 0x80000000
+    assert cp.tolist() == [[0, 2, 5, 5, 7]]
+    assert list(ri[:7]) == [0 | F, 1, 0 | F, 1 | F, 2, 0 | F, 2 | F] and ri.size == 12
+    two = np.stack([cls[0], cls[0][::-1]])
+    cp2, ri2 = oracle.column_index(two)
+    assert cp2[1].tolist() == [0, 2, 5, 5, 7] and list(ri2[12:19]) == [1, 2 | F, 0, 1 | F, 2 | F, 0 | F, 2 | F]
+
+
+def test_column_index_rebuilds_the_class_matrix_and_mirrors_the_row_list():
+    rng = np.random.default_rng(5)
+    cls = rng.integers(0, 3, size=(2, 7, 5)).astype(np.uint8)
+    cls[0, :, 2] = 0                                   # an empty column
+    cp, ri = oracle.column_index(cls)
+    back = np.zeros_like(cls)
+    for m in range(2):
+        for j in range(5):
+            ent = ri[m * 35 + cp[m, j]: m * 35 + cp[m, j + 1]]
+            rows = (ent & 0x7fffffff).astype(np.int64)
+            assert np.all(np.diff(rows) > 0)
+            back[m, rows, j] = np.where(ent >> 31, 2, 1)
+    assert np.array_equal(back, cls)
+    # the column list of a matrix is the row list of its transpose
+    rp, ci = oracle.sparse_index(np.ascontiguousarray(cls.transpose(0, 2, 1)))
+    assert np.array_equal(rp, cp) and np.array_equal(ci, ri)
+
+
 @pytest.mark.parametrize("N", [64, 200, 130])
 def test_packed_bits_roundtrip(N):
     mask = _rand_mask(N + 7, N, Mb=2)
