@@ -1,5 +1,5 @@
 /*
- * bbm.h -- C ABI of libbbm: Binary Block Masking flash-attention forward for AMD MI355X (gfx950).
+ * bbm.h -- C ABI of libbbm: Binary Block Masking flash attention (forward and backward) for AMD MI355X (gfx950).
  *
  * The library implements the two stages of the paper "Efficiently Dispatching Flash Attention For Partially
  * Filled Attention Masks" (Sec. 4, Method): (1) reduce an N x N binary attention mask to a block matrix at
@@ -66,6 +66,8 @@ typedef struct bbm_index {
   const int32_t* row_ptr;     /* [Mb, nbr + 1] list offsets within a plane, row_ptr[m][0] = 0        */
   const uint32_t* col_idx;    /* [Mb * nbr * nbc]; plane m starts at m*nbr*nbc; bit 31 = block full  */
   const int32_t* sched;       /* bbm_sched_bytes(Mb, nbr) bytes: tile schedule of LIST mode           */
+  const int32_t* col_ptr;     /* [Mb, nbc + 1] column-list offsets within a plane (backward pass)    */
+  const uint32_t* row_idx;    /* [Mb * nbr * nbc]; plane m starts at m*nbr*nbc; bit 31 = block full  */
 } bbm_index;
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
@@ -198,6 +200,54 @@ size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
 int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t N,
                  int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask, const bbm_index* idx, int mode,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Per-column list of non-zero blocks, the transpose of the list of bbm_build_sparse_index: what the dK/dV step of
+ * the backward pass walks (a block of keys visits the query blocks that may attend it; paper Sec. 4: only non-zero
+ * blocks are processed, in the backward pass as in the forward).
+ *
+ *   blk_class        device in, uint8 [Mb][nbr][nbc].
+ *   col_ptr          device out, int32 [Mb][nbc + 1]; col_ptr[m][0] = 0, col_ptr[m][j+1] - col_ptr[m][j] = number of
+ *                    non-zero blocks of block column j.
+ *   row_idx          device out, uint32, capacity Mb*nbr*nbc entries; the list of plane m starts at entry m*nbr*nbc;
+ *                    block rows ascending within a column; bit 31 set iff the block is full.  Entries past
+ *                    col_ptr[m][nbc] are left untouched.
+ * Requires nbr*nbc < 2^31.  Errors: BBM_EINVAL, BBM_EHIP.
+ */
+int bbm_build_col_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* col_ptr,
+                        uint32_t* row_idx, void* stream);
+
+/* Bytes of device workspace bbm_attn_bwd needs (0 for sizes < 1). */
+size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N);
+
+/*
+ * Backward pass of bbm_attn_fwd (paper Sec. 3 "Flash Attention": the attention matrix is recomputed block by block
+ * from the stored log-sum-exp; Sec. 4: only non-zero blocks are visited, the element mask is applied on partial ones
+ * only; Sec. 5 and the appendix on forward and backward runtimes time both passes).  For an upstream gradient dO and
+ * p_ij = exp(softmax_scale * <q_i, k_j> - lse_i) for j in A_i, 0 elsewhere:
+ *     dV_j = sum_i p_ij dO_i,   D_i = <dO_i, O_i>,   dS_ij = p_ij (<dO_i, v_j> - D_i),
+ *     dQ_i = softmax_scale * sum_j dS_ij k_j,        dK_j = softmax_scale * sum_i dS_ij q_i.
+ * A query with A_i empty (lse = -inf) contributes nothing and gets dQ = 0; a key nobody attends gets dK = dV = 0.
+ *
+ *   q, k, v, o, d_o  device in, bf16 [B][H][N][d] contiguous, 16-byte aligned; o and lse as bbm_attn_fwd returned them.
+ *   lse              device in, fp32 [B][H][N] (required).
+ *   dq, dk, dv       device out, bf16 [B][H][N][d] contiguous (round-to-nearest-even), 16-byte aligned; every element
+ *                    is written.
+ *   d, softmax_scale, Mb, packed_mask   as for bbm_attn_fwd (the same values as in the forward call).
+ *   idx              host pointer; Br, Bc, Mb, nbr, nbc as for bbm_attn_fwd; needs row_ptr, col_idx (the dQ step walks
+ *                    block rows), col_ptr, row_idx (the dK/dV step walks block columns); sched is used for the launch
+ *                    order of the block rows if present.
+ *   workspace        device scratch of at least bbm_attn_bwd_workspace_bytes(B, H, N) bytes, 16-byte aligned; holds D
+ *                    and the log-sum-exp in the form the second kernel consumes.  Needs no initialisation.
+ * Arithmetic: all five products on bf16 MFMA with fp32 accumulation; Q (dQ step) resp. K (dK/dV step) is multiplied by
+ * softmax_scale*log2(e) and rounded to bf16 once; P and dS are rounded to bf16 before the products that consume them.
+ * Two kernels, no atomics: the same inputs give bit-identical outputs.
+ * Errors: BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EWORKSPACE, BBM_EHIP.
+ */
+int bbm_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
+                 void* dk, void* dv, int64_t B, int64_t H, int64_t N, int d, float softmax_scale, int64_t Mb,
+                 const uint64_t* packed_mask, const bbm_index* idx, void* workspace, size_t workspace_bytes,
+                 void* stream);
 
 #ifdef __cplusplus
 }

@@ -83,9 +83,9 @@ def masked_attention_bwd_rows(q, k, v, mask, do, rows, scale=None):
     return out
 
 
-def masked_attention_bwd_cols(q, k, v, mask, do, cols, scale=None, row_chunk=1024):
-    """dK and dV of sampled key rows (b, h, j): sums over the queries that may attend key j, each of which needs its
-    own full softmax row.  Returns (dK [len(cols), d], dV [len(cols), d])."""
+def masked_attention_bwd_cols(q, k, v, mask, do, cols, scale=None):
+    """dK and dV of sampled key rows (b, h, j): sums over the queries i that may attend key j, each evaluated from its
+    own row of the definition (softmax over A_i only).  Returns (dK [len(cols), d], dV [len(cols), d])."""
     B, H, N, d = q.shape
     Mb = mask.shape[0]
     scale = 1.0 / np.sqrt(float(d)) if scale is None else float(scale)
@@ -93,15 +93,15 @@ def masked_attention_bwd_cols(q, k, v, mask, do, cols, scale=None, row_chunk=102
     dV = np.zeros((len(cols), d), dtype=np.float64)
     for n, (b, h, j) in enumerate(cols):
         mb = mask[b if Mb == B else 0]
-        I = np.flatnonzero(mb[:, j])
         kk, vv = _as_f64(k[b, h]), _as_f64(v[b, h])
-        for c0 in range(0, I.size, row_chunk):
-            Ic = I[c0:c0 + row_chunk]
-            qq, dd = _as_f64(q[b, h, Ic]), _as_f64(do[b, h, Ic])
-            p = _row_softmax(scale * (qq @ kk.T), mb[Ic] != 0)                        # [|Ic|, N]
-            dP = dd @ vv.T
-            D = (p * dP).sum(axis=1)
-            dS_j = p[:, j] * (dP[:, j] - D)
-            dV[n] += p[:, j] @ dd
-            dK[n] += scale * (dS_j @ qq)
+        for i in np.flatnonzero(mb[:, j]):
+            idx = np.flatnonzero(mb[i])
+            at = int(np.searchsorted(idx, j))                       # position of key j among the allowed keys of row i
+            qi, di = _as_f64(q[b, h, i]), _as_f64(do[b, h, i])
+            s = scale * (kk[idx] @ qi)
+            p = np.exp(s - s.max())
+            p /= p.sum()
+            dP = vv[idx] @ di
+            dV[n] += p[at] * di
+            dK[n] += scale * p[at] * (dP[at] - p @ dP) * qi
     return dK, dV

@@ -1,4 +1,4 @@
-"""Binary Block Masking flash-attention forward for AMD MI355X: thin Python binding over libbbm.so.
+"""Binary Block Masking flash attention (forward and backward) for AMD MI355X: thin Python binding over libbbm.so.
 
 The functions below carry the names of the C ABI (include/bbm.h) and only marshal arguments: device memory
 and the stream come from PyTorch, every computation runs in the library's HIP kernels.  There is no CPU
@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     BBM_OK, BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EWORKSPACE, BBM_EHIP,
     BbmError, BlockIndex, lib, library_path,
     bbm_last_error, bbm_version, bbm_build_block_mask, bbm_build_runs, bbm_build_sparse_index,
-    bbm_build_index,
+    bbm_build_index, bbm_build_col_index, bbm_attn_bwd_workspace_bytes, bbm_attn_bwd,
     bbm_attn_fwd_workspace_bytes, bbm_attn_fwd, bbm_sched_bytes, build_index, bf16_from_bits,
 )

@@ -22,7 +22,8 @@ class _CIndex(C.Structure):
     _fields_ = [("Br", C.c_int32), ("Bc", C.c_int32), ("Mb", C.c_int64), ("nbr", C.c_int64), ("nbc", C.c_int64),
                 ("blk_class", C.c_void_p), ("bin_blk_mat", C.c_void_p), ("offset", C.c_void_p),
                 ("total_ones", C.c_void_p), ("nz_lo", C.c_void_p), ("nz_hi", C.c_void_p), ("nz_cnt", C.c_void_p),
-                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("sched", C.c_void_p)]
+                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("sched", C.c_void_p),
+                ("col_ptr", C.c_void_p), ("row_idx", C.c_void_p)]
 
 
 def library_path() -> str:
@@ -54,6 +55,13 @@ def _load():
     L.bbm_attn_fwd.restype = ci
     L.bbm_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, C.c_float, i64, vp, C.POINTER(_CIndex), ci,
                                vp, C.c_size_t, vp]
+    L.bbm_build_col_index.restype = ci
+    L.bbm_build_col_index.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    L.bbm_attn_bwd_workspace_bytes.restype = C.c_size_t
+    L.bbm_attn_bwd_workspace_bytes.argtypes = [i64, i64, i64]
+    L.bbm_attn_bwd.restype = ci
+    L.bbm_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, C.c_float, i64, vp,
+                               C.POINTER(_CIndex), vp, C.c_size_t, vp]
     return L
 
 
@@ -107,12 +115,14 @@ class BlockIndex:
     row_ptr: Optional[torch.Tensor] = None
     col_idx: Optional[torch.Tensor] = None
     sched: Optional[torch.Tensor] = None
+    col_ptr: Optional[torch.Tensor] = None
+    row_idx: Optional[torch.Tensor] = None
 
     def c_struct(self) -> _CIndex:
         g = lambda t: None if t is None else t.data_ptr()
         return _CIndex(self.Br, self.Bc, self.Mb, self.nbr, self.nbc, g(self.blk_class), g(self.bin_blk_mat),
                        g(self.offset), g(self.total_ones), g(self.nz_lo), g(self.nz_hi), g(self.nz_cnt),
-                       g(self.row_ptr), g(self.col_idx), g(self.sched))
+                       g(self.row_ptr), g(self.col_idx), g(self.sched), g(self.col_ptr), g(self.row_idx))
 
 
 def bbm_build_block_mask(mask: torch.Tensor, Br: int, Bc: int, idx: Optional[BlockIndex] = None,
@@ -180,15 +190,31 @@ def bbm_build_index(idx: BlockIndex, stream=None) -> BlockIndex:
     return idx
 
 
+def bbm_build_col_index(idx: BlockIndex, stream=None) -> BlockIndex:
+    """Per-column block list (what the backward pass walks for dK and dV) from idx.blk_class."""
+    dev = idx.blk_class.device
+    if idx.col_ptr is None:
+        idx.col_ptr = torch.empty((idx.Mb, idx.nbc + 1), dtype=torch.int32, device=dev)
+    if idx.row_idx is None:
+        idx.row_idx = torch.zeros(idx.Mb * idx.nbr * idx.nbc, dtype=torch.int32, device=dev)
+    _check(lib.bbm_build_col_index(_ptr(idx.blk_class), idx.Mb, idx.nbr, idx.nbc, _ptr(idx.col_ptr), _ptr(idx.row_idx),
+                                   _stream(stream)))
+    return idx
+
+
 def build_index(mask: torch.Tensor, Br: int, Bc: int = 64, idx: Optional[BlockIndex] = None, stream=None,
-                fused: bool = True) -> BlockIndex:
+                fused: bool = True, columns: bool = False) -> BlockIndex:
     """The whole preprocessing stage: block classes, then run index + block list + schedule (through the one-call
-    entry point, or with fused=False through the two separate ones)."""
+    entry point, or with fused=False through the two separate ones); columns=True adds the per-column list the
+    backward pass needs."""
     idx = bbm_build_block_mask(mask, Br, Bc, idx=idx, stream=stream)
     if fused:
-        return bbm_build_index(idx, stream=stream)
-    bbm_build_runs(idx, stream=stream)
-    bbm_build_sparse_index(idx, stream=stream)
+        bbm_build_index(idx, stream=stream)
+    else:
+        bbm_build_runs(idx, stream=stream)
+        bbm_build_sparse_index(idx, stream=stream)
+    if columns:
+        bbm_build_col_index(idx, stream=stream)
     return idx
 
 
@@ -223,3 +249,31 @@ def bbm_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIn
                             _ptr(idx.packed_mask), C.byref(cs), mode, _ptr(workspace),
                             0 if workspace is None else workspace.numel(), _stream(stream)))
     return out, lse
+
+
+def bbm_attn_bwd_workspace_bytes(B, H, N) -> int:
+    return int(lib.bbm_attn_bwd_workspace_bytes(B, H, N))
+
+
+def bbm_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor, d_o: torch.Tensor,
+                 lse: torch.Tensor, idx: BlockIndex, softmax_scale: Optional[float] = None,
+                 dq: Optional[torch.Tensor] = None, dk: Optional[torch.Tensor] = None,
+                 dv: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """q, k, v, o, d_o: bf16 CUDA tensors [B,H,N,d], contiguous; lse fp32 [B,H,N] from bbm_attn_fwd; idx built with
+    the column list.  Returns (dQ, dK, dV), bf16 [B,H,N,d]."""
+    for t in (q, k, v, o, d_o):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == q.shape
+    B, H, N, d = q.shape
+    assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.shape == (B, H, N)
+    if softmax_scale is None:
+        softmax_scale = float(d) ** -0.5
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(q) if dk is None else dk
+    dv = torch.empty_like(q) if dv is None else dv
+    if workspace is None:
+        workspace = torch.empty(bbm_attn_bwd_workspace_bytes(B, H, N), dtype=torch.uint8, device=q.device)
+    cs = idx.c_struct()
+    _check(lib.bbm_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv),
+                            B, H, N, d, softmax_scale, idx.Mb, _ptr(idx.packed_mask), C.byref(cs), _ptr(workspace),
+                            workspace.numel(), _stream(stream)))
+    return dq, dk, dv

@@ -1,0 +1,617 @@
+// Backward pass of the fused masked attention (paper Sec. 3 "Flash Attention": the attention matrix is recomputed in
+// the backward pass; Sec. 4: only non-zero blocks are visited and the element mask is applied only on partial ones).
+//
+// With P = softmax over the allowed keys (recomputed from the stored log-sum-exp), dP = dO V^T, D_i = <dO_i, O_i>,
+// dS = P o (dP - D):   dV = P^T dO,   dK = scale * dS^T Q,   dQ = scale * dS K.
+//
+// Two kernels, both deterministic (no atomics):
+//   dq kernel   one work-group per block row of Br = 32*NW queries, one lane per query (the layout of the forward
+//               kernel): walks the row's list of key tiles, S^T = K Q^T and dP^T = V dO^T with the tile rows as the
+//               A operand, dQ^T += K^T dS^T with K read through transposing LDS reads.  It also computes D_i and
+//               leaves -D_i and -lse_i*log2(e) in the workspace for the second kernel.
+//   dkv kernel  one work-group (2 waves) per block column of 64 keys, one lane per key: walks the column's list of
+//               query blocks in sub-tiles of 64 queries, S = Q K^T and dP = dO V^T with the tile rows as A operand,
+//               dV^T += dO^T P and dK^T += Q^T dS with transposing LDS reads of the same two tiles.
+// Both start the score accumulators at -lse (in exponent units) and the dP accumulators at -D, so that exp2 and one
+// multiplication per element give P and dS.
+#include "bbm_internal.h"
+
+#include <algorithm>
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kWin = 256;                   // list entries per LDS window
+constexpr uint32_t kNoTile = 0xffffffffu;
+
+struct BwdParams {
+  const __bf16* q;
+  const __bf16* k;
+  const __bf16* v;
+  const __bf16* o;
+  const __bf16* d_o;
+  const float* lse;
+  __bf16* dq;
+  __bf16* dk;
+  __bf16* dv;
+  float* nl2;      // workspace [B*H*N]: -lse*log2(e), -inf for fully masked rows
+  float* ndelta;   // workspace [B*H*N]: -<dO_i, O_i>
+  const uint64_t* packed;  // [Mb][W][N]
+  const int32_t* row_ptr;
+  const uint32_t* col_idx;
+  const int32_t* sched;    // may be NULL: block rows are then started from the last to the first
+  const int32_t* col_ptr;
+  const uint32_t* row_idx;
+  int64_t N;
+  int32_t H, Mb, nbr, nbc, W;
+  int32_t total_wgs;
+  int32_t G;
+  int32_t br;       // query rows per block row
+  float scale;
+};
+
+__device__ __forceinline__ float partner_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// LDS layout of a 64-row x D tile, shared by every tile of both kernels.  One asynchronous copy instruction of a wave
+// fills one 1 KiB block with RPB rows that lie NBLK rows apart: row r sits in block r % NBLK at slot r / NBLK; blocks
+// are 1 KiB + 64 B apart, and the 16-byte chunk c of row r sits at chunk position c ^ ((r >> 2) & 3).  With that both
+// access patterns are free of bank conflicts: 16 lanes reading the same chunk of 16 consecutive rows (A operand from
+// tile rows), and 32 lanes reading 64 contiguous bytes of 4 consecutive rows (transposing read).
+template <int D>
+struct TL {
+  static constexpr int RC = D / 8;          // 16-byte chunks per row
+  static constexpr int RPB = 64 / RC;       // rows per 1 KiB block
+  static constexpr int NBLK = 64 / RPB;     // blocks per tile
+  static constexpr int TBLK = 512 + 32;     // block stride in elements
+  static constexpr int ELEMS = NBLK * TBLK;
+};
+
+// Asynchronous global -> LDS copy of rows row0 .. row0+63 of a [N][D] matrix.  Lane l of a copy instruction lands at
+// block base + 16*l, i.e. slot l / RC, chunk position l % RC.  Rows past N re-read row N-1 (callers make sure such
+// rows contribute nothing).
+template <int D, int NW>
+__device__ __forceinline__ void tile_copy_async(const __bf16* __restrict__ src, int64_t row0, int64_t N, __bf16* dst, int wave, int lane) {
+  using L = TL<D>;
+  constexpr int LPW = L::NBLK / NW;
+  static_assert(L::NBLK % NW == 0, "tile must split evenly over the waves");
+  const int slot = lane / L::RC, pos = lane % L::RC;
+  const int64_t first = min(row0, N - 1);  // a tile that starts past N re-reads row N-1 throughout
+  const char* tile = reinterpret_cast<const char*>(src + first * D);
+  const int last = (int)min<int64_t>(63, N - 1 - first);
+#pragma unroll
+  for (int n = 0; n < LPW; ++n) {
+    const int blk = n * NW + wave;
+    const int row = blk + L::NBLK * slot;
+    const int c = pos ^ ((row >> 2) & 3);
+    const uint32_t off = (uint32_t)(min(row, last) * D + c * 8) * 2u;
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(tile + off),
+                                     (void __attribute__((address_space(3)))*)(dst + blk * L::TBLK), 16, 0, 0);
+  }
+}
+
+// Per-lane base addresses (in elements) of the two read patterns.
+template <int D>
+struct TileAddr {
+  int ra[2];  // A operand from tile rows: row 32*blk + lane%32, chunk 2t + lane/32; ra[t & 1] + (t >> 1)*32 + blk*(32/NBLK)*D
+  int ta[2];  // transposing read of 16-row step u, half a, column block db: ta[a] + u*(D == 64 ? 2*D : D) + db*32
+  __device__ __forceinline__ void init(int lane) {
+    using L = TL<D>;
+    const int lq = lane & 31, hh = lane >> 5;
+    const int hq = (lq >> 2) & 3;
+    const int rowbase = (lq % L::NBLK) * L::TBLK + (lq / L::NBLK) * D;
+    const int x = hh ^ (hq & 1), y = hq >> 1;
+    ra[0] = rowbase + (2 * y + x) * 8;
+    ra[1] = rowbase + (2 * (1 ^ y) + x) * 8;
+    const int vy = (lane & 15) >> 2, vg = (lane >> 4) & 1, vx = (lane & 3) >> 1;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      const int blockrow = D == 64 ? (4 * hh + vy) * L::TBLK + a * D : (8 * a + 4 * hh + vy) * L::TBLK;
+      ta[a] = blockrow + (2 * (vg ^ a) + (vx ^ hh)) * 8 + 4 * (lane & 1);
+    }
+  }
+  __device__ __forceinline__ bf16x8 row_frag(const __bf16* tile, int blk, int t) const {
+    using L = TL<D>;
+    return *reinterpret_cast<const bf16x8*>(tile + ra[t & 1] + (t >> 1) * 32 + blk * (32 / L::NBLK) * D);
+  }
+  // rows 16u + 8a + 4*(lane/32) + 0..3 (a = 0, 1) of column 32*db + lane%32: the order in which a lane's accumulator
+  // registers 8*(u%2) .. 8*(u%2)+7 of row block u/2 list the rows of a 32x32 product
+  __device__ __forceinline__ bf16x8 tr_frag(const __bf16* tile, int u, int db) const {
+    s16x4 part[2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+      part[a] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (s16x4 __attribute__((address_space(3)))*)(tile + ta[a] + u * (D == 64 ? 2 * D : D) + db * 32));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7));
+  }
+};
+
+// acc * mult, rounded to bf16, to rows row0 .. of a [N][D] matrix: lane l holds row l%32 of the wave's 32-row slab,
+// columns 32*db + 8*(e/4) + 4*(l/32) + e%4.  The slab is staged in LDS (`stage`, 32*D elements, this wave's own) so
+// that the global stores are whole rows: 16-byte chunk ch of row r sits at chunk position ch ^ (r % RC).
+template <int D>
+__device__ __forceinline__ void store_slab(const f32x16 (&acc)[D / 32], float mult, __bf16* stage, __bf16* __restrict__ dst,
+                                           int64_t row0, int64_t N, int lane) {
+  using L = TL<D>;
+  const int lq = lane & 31, hh = lane >> 5, gro = lane / L::RC, gco = lane % L::RC;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 ov;
+      for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc[db][4 * g + e] * mult);
+      *reinterpret_cast<bf16x4*>(stage + lq * D + (((4 * db + g) ^ (lq % L::RC)) * 8) + 4 * hh) = ov;
+    }
+  }
+  __bf16* og = dst + row0 * D;
+#pragma unroll
+  for (int n = 0; n < 32 / L::RPB; ++n) {
+    const int r = n * L::RPB + gro;
+    const bf16x8 ov = *reinterpret_cast<const bf16x8*>(stage + r * D + ((gco ^ (r % L::RC)) * 8));
+    if (row0 + r < N) *reinterpret_cast<bf16x8*>(og + r * D + gco * 8) = ov;
+  }
+}
+
+template <int V>
+struct IntC {
+  static constexpr int value = V;
+};
+
+// XCD-aware logical work-group id: work-groups are handed to the 8 XCDs round-robin; give each XCD a contiguous range
+// of logical ids so that the work-groups of one head (which share its tensors) meet in one XCD's L2.
+__device__ __forceinline__ int logical_wg(int wg, int total) {
+  const int xcd = wg & 7, slot = wg >> 3;
+  const int per = total >> 3, rem = total & 7;
+  return xcd * per + (xcd < rem ? xcd : rem) + slot;
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// dQ (and D, and the negated statistics for the dK/dV kernel)
+// ------------------------------------------------------------------------------------------------------------------
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P) {
+  using L = TL<D>;
+  constexpr int NT = NW * 64;
+  constexpr int BR = NW * 32;
+  constexpr int KS = D / 16;
+  constexpr int DB = D / 32;
+  static_assert(2 * 32 * D <= L::ELEMS && NW <= 8, "two 32 x D output slabs must fit in each tile buffer");
+
+  __shared__ __attribute__((aligned(16))) __bf16 k_s0[L::ELEMS];
+  __shared__ __attribute__((aligned(16))) __bf16 k_s1[L::ELEMS];
+  __shared__ __attribute__((aligned(16))) __bf16 v_s0[L::ELEMS];
+  __shared__ __attribute__((aligned(16))) __bf16 v_s1[L::ELEMS];
+  __shared__ uint32_t tiles_s[kWin + 4];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lq = lane & 31, hh = lane >> 5;
+  const int64_t N = P.N;
+  const float c = P.scale * kLog2e;
+
+  // ---- which block row: rank-major interleave of G (batch, head) planes, as in the forward kernel
+  int bh, m, rank;
+  {
+    const int logical = logical_wg((int)blockIdx.x, P.total_wgs);
+    const int grp = logical / (P.G * P.nbr), within = logical - grp * (P.G * P.nbr);
+    const int g_planes = min(P.G, P.total_wgs / P.nbr - grp * P.G);
+    rank = within / g_planes;
+    bh = grp * P.G + (within - rank * g_planes);
+    m = (P.Mb == 1) ? 0 : bh / P.H;
+  }
+  int i, list_pos, n_list;
+  if (P.sched) {
+    const int4 rec = *reinterpret_cast<const int4*>(P.sched + bbm::sched_order_base(P.Mb, P.nbr) +
+                                                    bbm::kSchedRowInts * (int64_t)(m * P.nbr + rank));
+    i = rec.x;
+    list_pos = rec.y;
+    n_list = rec.z;
+  } else {
+    i = P.nbr - 1 - rank;
+    list_pos = P.row_ptr[(int64_t)m * (P.nbr + 1) + i];
+    n_list = P.row_ptr[(int64_t)m * (P.nbr + 1) + i + 1] - list_pos;
+  }
+  const uint32_t* __restrict__ list = P.col_idx + (int64_t)m * P.nbr * P.nbc + list_pos;
+
+  const int64_t head_off = (int64_t)bh * N * D;
+  const __bf16* __restrict__ Kg = P.k + head_off;
+  const __bf16* __restrict__ Vg = P.v + head_off;
+  const int64_t qrow = (int64_t)i * BR + wave * 32 + lq;
+  const bool q_ok = qrow < N;
+  const uint64_t* __restrict__ mrow = P.packed + (int64_t)m * P.W * N + (q_ok ? qrow : 0);
+
+  // ---- this lane's query: Q * scale * log2(e) and dO as B operands, D = <dO, O>, the negated statistics
+  bf16x8 qf[KS], dof[KS];
+  float dsum = 0.0f;
+#pragma unroll
+  for (int t = 0; t < KS; ++t) {
+    bf16x8 of;
+    if (q_ok) {
+      const int64_t at = head_off + qrow * D + 16 * t + 8 * hh;
+      qf[t] = *reinterpret_cast<const bf16x8*>(P.q + at);
+      dof[t] = *reinterpret_cast<const bf16x8*>(P.d_o + at);
+      of = *reinterpret_cast<const bf16x8*>(P.o + at);
+    } else {
+      for (int e = 0; e < 8; ++e) qf[t][e] = dof[t][e] = of[e] = (__bf16)0.0f;
+    }
+    for (int e = 0; e < 8; ++e) {
+      dsum += (float)dof[t][e] * (float)of[e];
+      qf[t][e] = (__bf16)((float)qf[t][e] * c);
+    }
+  }
+  const float delta = partner_sum(dsum);
+  const float lse_i = q_ok ? P.lse[(int64_t)bh * N + qrow] : -INFINITY;
+  const float nl = (lse_i == -INFINITY) ? -INFINITY : -lse_i * kLog2e;
+  if (q_ok && hh == 0) {
+    P.nl2[(int64_t)bh * N + qrow] = nl;
+    P.ndelta[(int64_t)bh * N + qrow] = -delta;
+  }
+  f32x16 s_init, dp_init;
+  for (int e = 0; e < 16; ++e) {
+    s_init[e] = nl;
+    dp_init[e] = -delta;
+  }
+  f32x16 dq[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    for (int e = 0; e < 16; ++e) dq[db][e] = 0.0f;
+
+  TileAddr<D> A;
+  A.init(lane);
+
+  auto tile_of = [](uint32_t e) { return (int)(e & 0x7fffffffu); };
+  uint32_t e0, e1;
+  uint64_t mw_nxt = 0;
+  auto request = [&](uint32_t e, __bf16* kd, __bf16* vd) {
+    tile_copy_async<D, NW>(Kg, (int64_t)tile_of(e) * 64, N, kd, wave, lane);
+    tile_copy_async<D, NW>(Vg, (int64_t)tile_of(e) * 64, N, vd, wave, lane);
+    if ((e >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e) * N];
+  };
+
+  auto step = [&](auto pb, int it) {
+    constexpr int PB = decltype(pb)::value;
+    const uint64_t mw = mw_nxt;
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    __bf16* const k_cur = PB ? k_s1 : k_s0;
+    __bf16* const k_oth = PB ? k_s0 : k_s1;
+    __bf16* const v_cur = PB ? v_s1 : v_s0;
+    __bf16* const v_oth = PB ? v_s0 : v_s1;
+    f32x16 s[2], dp[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) s[kb] = s_init;
+#pragma unroll
+    for (int t = 0; t < KS; ++t)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(k_cur, kb, t), qf[t], s[kb], 0, 0, 0);
+    if (e1 != kNoTile) request(e1, k_oth, v_oth);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) dp[kb] = dp_init;
+#pragma unroll
+    for (int t = 0; t < KS; ++t)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(v_cur, kb, t), dof[t], dp[kb], 0, 0, 0);
+
+    // element mask where the list cannot rule out zeros: masked scores become -inf, i.e. probability 0
+    if ((e0 >> 31) == 0) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const uint32_t w = (uint32_t)(mw >> (32 * kb)) >> (4 * hh);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int bit = 8 * (e / 4) + (e % 4);
+          const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);
+          s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      bf16x8 dsf;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float p = __builtin_amdgcn_exp2f(s[u / 2][8 * (u % 2) + e]);
+        dsf[e] = (__bf16)(p * dp[u / 2][8 * (u % 2) + e]);
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(k_cur, u, db), dsf, dq[db], 0, 0, 0);
+    }
+    e0 = e1;
+    e1 = tiles_s[it + 2];
+  };
+
+  for (int w0 = 0; w0 < n_list; w0 += kWin) {
+    const int count = min(kWin, n_list - w0);
+    for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
+    if (tid < 3) tiles_s[count + tid] = kNoTile;
+    __syncthreads();
+    e0 = tiles_s[0];
+    e1 = tiles_s[1];
+    request(e0, k_s0, v_s0);
+    for (int it = 0; it < count; it += 2) {
+      step(IntC<0>{}, it);
+      if (it + 1 < count) step(IntC<1>{}, it + 1);
+    }
+    __syncthreads();  // the next window rewrites the tile list and the buffers; the epilogue stages into them
+  }
+
+  __bf16* const stage = ((wave >> 1) == 0 ? k_s0 : (wave >> 1) == 1 ? k_s1 : (wave >> 1) == 2 ? v_s0 : v_s1) + (wave & 1) * 32 * D;
+  store_slab<D>(dq, P.scale, stage, P.dq + head_off, (int64_t)i * BR + wave * 32, N, lane);
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// dK, dV
+// ------------------------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
+  using L = TL<D>;
+  constexpr int NW = 2, NT = 128;
+  constexpr int KS = D / 16;
+  constexpr int DB = D / 32;
+  static_assert(2 * 32 * D <= L::ELEMS, "two 32 x D output slabs must fit in a tile buffer");
+
+  __shared__ __attribute__((aligned(16))) __bf16 q_s0[L::ELEMS];
+  __shared__ __attribute__((aligned(16))) __bf16 q_s1[L::ELEMS];
+  __shared__ __attribute__((aligned(16))) __bf16 g_s0[L::ELEMS];  // dO tiles
+  __shared__ __attribute__((aligned(16))) __bf16 g_s1[L::ELEMS];
+  __shared__ __attribute__((aligned(16))) float nl_s0[64];
+  __shared__ __attribute__((aligned(16))) float nl_s1[64];
+  __shared__ __attribute__((aligned(16))) float nd_s0[64];
+  __shared__ __attribute__((aligned(16))) float nd_s1[64];
+  __shared__ __attribute__((aligned(16))) uint32_t mk_s0[2][64];  // [key half][query row of the sub-tile]
+  __shared__ __attribute__((aligned(16))) uint32_t mk_s1[2][64];
+  __shared__ uint32_t tiles_s[kWin + 4];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // = key half of the column block
+  const int lq = lane & 31, hh = lane >> 5;
+  const int64_t N = P.N;
+  const float c = P.scale * kLog2e;
+
+  const int logical = logical_wg((int)blockIdx.x, P.total_wgs);
+  const int bh = logical / P.nbc;
+  const int j = logical - bh * P.nbc;
+  const int m = (P.Mb == 1) ? 0 : bh / P.H;
+  const int list_pos = P.col_ptr[(int64_t)m * (P.nbc + 1) + j];
+  const int n_list = P.col_ptr[(int64_t)m * (P.nbc + 1) + j + 1] - list_pos;
+  const uint32_t* __restrict__ list = P.row_idx + (int64_t)m * P.nbr * P.nbc + list_pos;
+
+  const int64_t head_off = (int64_t)bh * N * D;
+  const __bf16* __restrict__ Qg = P.q + head_off;
+  const __bf16* __restrict__ Gg = P.d_o + head_off;
+  const float* __restrict__ nlg = P.nl2 + (int64_t)bh * N;
+  const float* __restrict__ ndg = P.ndelta + (int64_t)bh * N;
+  // this wave's 32-bit half of the packed mask words of block column j (one word per query row)
+  const uint32_t* __restrict__ mcol = reinterpret_cast<const uint32_t*>(P.packed + ((int64_t)m * P.W + j) * N) + wave;
+
+  // ---- this lane's key: K * scale * log2(e) and V as B operands (keys past N: zeros, never stored)
+  const int64_t krow = (int64_t)j * 64 + wave * 32 + lq;
+  const bool k_ok = krow < N;
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int t = 0; t < KS; ++t) {
+    if (k_ok) {
+      const int64_t at = head_off + krow * D + 16 * t + 8 * hh;
+      kf[t] = *reinterpret_cast<const bf16x8*>(P.k + at);
+      vf[t] = *reinterpret_cast<const bf16x8*>(P.v + at);
+    } else {
+      for (int e = 0; e < 8; ++e) kf[t][e] = vf[t][e] = (__bf16)0.0f;
+    }
+    for (int e = 0; e < 8; ++e) kf[t][e] = (__bf16)((float)kf[t][e] * c);
+  }
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+    for (int e = 0; e < 16; ++e) dk[db][e] = dv[db][e] = 0.0f;
+
+  TileAddr<D> A;
+  A.init(lane);
+
+  const int qs_shift = P.br == 64 ? 0 : P.br == 128 ? 1 : 2;  // 64-query sub-tiles per block row: 1, 2, 4
+  // Requests sub-tile `sub` of list entry e into the buffers of one parity: Q and dO tiles, the negated statistics of
+  // its 64 queries (wave 0: -lse*log2 e, wave 1: -D), and this wave's half of the mask words if the block is partial.
+  // Query rows past N get -inf / 0 so that their probabilities are exactly 0.
+  auto request = [&](uint32_t e, int sub, __bf16* qd, __bf16* gd, float* nld, float* ndd, uint32_t (*mkd)[64]) {
+    const int64_t row0 = ((int64_t)(e & 0x7fffffffu) << qs_shift) * 64 + (int64_t)sub * 64;
+    tile_copy_async<D, NW>(Qg, row0, N, qd, wave, lane);
+    tile_copy_async<D, NW>(Gg, row0, N, gd, wave, lane);
+    const int64_t r = row0 + lane;
+    float* const sd = wave == 0 ? nld : ndd;
+    const float* const sg = wave == 0 ? nlg : ndg;
+    if (r < N)
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sg + r),
+                                       (void __attribute__((address_space(3)))*)sd, 4, 0, 0);
+    else
+      sd[lane] = wave == 0 ? -INFINITY : 0.0f;
+    if ((e >> 31) == 0) {
+      const int64_t rc = min(r, N - 1);
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(mcol + 2 * rc),
+                                       (void __attribute__((address_space(3)))*)mkd[wave], 4, 0, 0);
+    }
+  };
+
+  int n_steps = 0;
+  auto entry_of = [&](int s) { return tiles_s[s >> qs_shift]; };
+  auto step = [&](auto pb, int s) {
+    constexpr int PB = decltype(pb)::value;
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    __bf16* const q_cur = PB ? q_s1 : q_s0;
+    __bf16* const g_cur = PB ? g_s1 : g_s0;
+    const float* const nl_cur = PB ? nl_s1 : nl_s0;
+    const float* const nd_cur = PB ? nd_s1 : nd_s0;
+    const uint32_t(*mk_cur)[64] = PB ? mk_s1 : mk_s0;
+    const uint32_t e0 = entry_of(s);
+    if (s + 1 < n_steps) {
+      const uint32_t e1 = entry_of(s + 1);
+      const int sub1 = (s + 1) & ((1 << qs_shift) - 1);
+      if (PB)
+        request(e1, sub1, q_s0, g_s0, nl_s0, nd_s0, mk_s0);
+      else
+        request(e1, sub1, q_s1, g_s1, nl_s1, nd_s1, mk_s1);
+    }
+    const bool partial = (e0 >> 31) == 0;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      f32x16 sc, dp;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 a = *reinterpret_cast<const float4*>(nl_cur + 32 * qb + 8 * g + 4 * hh);
+        const float4 b = *reinterpret_cast<const float4*>(nd_cur + 32 * qb + 8 * g + 4 * hh);
+        sc[4 * g + 0] = a.x, sc[4 * g + 1] = a.y, sc[4 * g + 2] = a.z, sc[4 * g + 3] = a.w;
+        dp[4 * g + 0] = b.x, dp[4 * g + 1] = b.y, dp[4 * g + 2] = b.z, dp[4 * g + 3] = b.w;
+      }
+#pragma unroll
+      for (int t = 0; t < KS; ++t) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(q_cur, qb, t), kf[t], sc, 0, 0, 0);
+#pragma unroll
+      for (int t = 0; t < KS; ++t) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(g_cur, qb, t), vf[t], dp, 0, 0, 0);
+      float p[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) p[e] = __builtin_amdgcn_exp2f(sc[e]);
+      if (partial) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint4 w = *reinterpret_cast<const uint4*>(&mk_cur[wave][32 * qb + 8 * g + 4 * hh]);
+          const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)ww[e], lq, 1);  // all ones iff bit lq is set
+            p[4 * g + e] = __uint_as_float(__float_as_uint(p[4 * g + e]) & keep);
+          }
+        }
+      }
+#pragma unroll
+      for (int u2 = 0; u2 < 2; ++u2) {
+        bf16x8 pf, dsf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          pf[e] = (__bf16)p[8 * u2 + e];
+          dsf[e] = (__bf16)(p[8 * u2 + e] * dp[8 * u2 + e]);
+        }
+        const int u = 2 * qb + u2;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(g_cur, u, db), pf, dv[db], 0, 0, 0);
+          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(q_cur, u, db), dsf, dk[db], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  for (int w0 = 0; w0 < n_list; w0 += kWin) {
+    const int count = min(kWin, n_list - w0);
+    for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
+    __syncthreads();
+    n_steps = count << qs_shift;
+    request(tiles_s[0], 0, q_s0, g_s0, nl_s0, nd_s0, mk_s0);
+    for (int s = 0; s < n_steps; s += 2) {
+      step(IntC<0>{}, s);
+      if (s + 1 < n_steps) step(IntC<1>{}, s + 1);
+    }
+    __syncthreads();  // the next window rewrites the list and the buffers; the epilogue stages into them
+  }
+
+  const int64_t row0 = (int64_t)j * 64 + wave * 32;
+  store_slab<D>(dk, P.scale, q_s0 + wave * 32 * D, P.dk + head_off, row0, N, lane);
+  store_slab<D>(dv, 1.0f, g_s0 + wave * 32 * D, P.dv + head_off, row0, N, lane);
+}
+
+inline size_t stats_bytes(int64_t B, int64_t H, int64_t N) {
+  const size_t n = (size_t)(B * H * N) * sizeof(float);
+  return (n + 255) / 256 * 256;
+}
+
+template <int D>
+int launch_bwd(BwdParams& P, int64_t B, int64_t H, hipStream_t s) {
+  P.total_wgs = (int32_t)(B * H * P.nbr);
+  P.G = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, (B * H * P.nbr / 8) / P.nbr));
+  if (P.br == 64)
+    attn_bwd_dq_kernel<D, 2><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
+  else if (P.br == 128)
+    attn_bwd_dq_kernel<D, 4><<<(unsigned)P.total_wgs, 256, 0, s>>>(P);
+  else
+    attn_bwd_dq_kernel<D, 8><<<(unsigned)P.total_wgs, 512, 0, s>>>(P);
+  int rc = bbm::launch_status("bbm_attn_bwd (dq)");
+  if (rc != BBM_OK) return rc;
+  P.total_wgs = (int32_t)(B * H * P.nbc);
+  attn_bwd_dkv_kernel<D><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
+  return bbm::launch_status("bbm_attn_bwd (dk, dv)");
+}
+
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N) {
+  if (B < 1 || H < 1 || N < 1) return 0;
+  return 2 * stats_bytes(B, H, N);
+}
+
+extern "C" __attribute__((visibility("default"))) int bbm_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                                                                   const float* lse, void* dq, void* dk, void* dv, int64_t B, int64_t H,
+                                                                   int64_t N, int d, float softmax_scale, int64_t Mb,
+                                                                   const uint64_t* packed_mask, const bbm_index* idx, void* workspace,
+                                                                   size_t workspace_bytes, void* stream) {
+  using namespace bbm;
+  clear_error();
+  if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv)
+    return fail(BBM_EINVAL, "bbm_attn_bwd: q, k, v, o, d_o, lse, dq, dk, dv must not be NULL");
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(d_o, 16) || !aligned(dq, 16) ||
+      !aligned(dk, 16) || !aligned(dv, 16))
+    return fail(BBM_EINVAL, "bbm_attn_bwd: q, k, v, o, d_o, dq, dk, dv must be 16-byte aligned");
+  if (!aligned(lse, 4)) return fail(BBM_EINVAL, "bbm_attn_bwd: lse must be 4-byte aligned");
+  if (B < 1 || H < 1 || N < 1) return fail(BBM_EINVAL, "bbm_attn_bwd: B=%lld, H=%lld, N=%lld must be >= 1", (long long)B, (long long)H, (long long)N);
+  if (!(softmax_scale > 0.0f) || !(softmax_scale < INFINITY)) return fail(BBM_EINVAL, "bbm_attn_bwd: softmax_scale must be finite and > 0");
+  if (Mb != 1 && Mb != B) return fail(BBM_EINVAL, "bbm_attn_bwd: Mb=%lld must be 1 or B=%lld", (long long)Mb, (long long)B);
+  if (!idx) return fail(BBM_EINVAL, "bbm_attn_bwd: idx must not be NULL");
+  if (!packed_mask || !aligned(packed_mask, 8)) return fail(BBM_EINVAL, "bbm_attn_bwd: packed_mask must be a non-NULL 8-byte aligned pointer");
+  if (d != 64 && d != 128) return fail(BBM_EUNSUPPORTED, "bbm_attn_bwd: d=%d has no kernel instance (64, 128)", d);
+  if (idx->Bc != 64 || (idx->Br != 64 && idx->Br != 128 && idx->Br != 256))
+    return fail(BBM_EUNSUPPORTED, "bbm_attn_bwd: tile (Br=%d, Bc=%d) has no kernel instance (Br in {64,128,256}, Bc = 64)", idx->Br, idx->Bc);
+  const int64_t nbr = ceil_div(N, idx->Br), nbc = ceil_div(N, idx->Bc);
+  if (idx->Mb != Mb || idx->nbr != nbr || idx->nbc != nbc)
+    return fail(BBM_EINVAL, "bbm_attn_bwd: index (Mb=%lld, nbr=%lld, nbc=%lld) does not match the problem (Mb=%lld, nbr=%lld, nbc=%lld)",
+                (long long)idx->Mb, (long long)idx->nbr, (long long)idx->nbc, (long long)Mb, (long long)nbr, (long long)nbc);
+  if (!idx->row_ptr || !idx->col_idx || !idx->col_ptr || !idx->row_idx)
+    return fail(BBM_EINVAL, "bbm_attn_bwd: the index needs row_ptr, col_idx (block list) and col_ptr, row_idx (column list)");
+  if (nbr * nbc >= (1ll << 31) || B * H * nbr >= (1ll << 31) || B * H * nbc >= (1ll << 31) || N >= (1ll << 31))
+    return fail(BBM_EUNSUPPORTED, "bbm_attn_bwd: problem too large for 32-bit tile counters");
+  const size_t need = bbm_attn_bwd_workspace_bytes(B, H, N);
+  if (!workspace || workspace_bytes < need)
+    return fail(BBM_EWORKSPACE, "bbm_attn_bwd: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+  if (!aligned(workspace, 16)) return fail(BBM_EINVAL, "bbm_attn_bwd: workspace must be 16-byte aligned");
+
+  BwdParams P;
+  P.q = static_cast<const __bf16*>(q);
+  P.k = static_cast<const __bf16*>(k);
+  P.v = static_cast<const __bf16*>(v);
+  P.o = static_cast<const __bf16*>(o);
+  P.d_o = static_cast<const __bf16*>(d_o);
+  P.lse = lse;
+  P.dq = static_cast<__bf16*>(dq);
+  P.dk = static_cast<__bf16*>(dk);
+  P.dv = static_cast<__bf16*>(dv);
+  P.nl2 = static_cast<float*>(workspace);
+  P.ndelta = reinterpret_cast<float*>(static_cast<char*>(workspace) + stats_bytes(B, H, N));
+  P.packed = packed_mask;
+  P.row_ptr = idx->row_ptr;
+  P.col_idx = idx->col_idx;
+  P.sched = idx->sched;
+  P.col_ptr = idx->col_ptr;
+  P.row_idx = idx->row_idx;
+  P.N = N;
+  P.H = (int32_t)H;
+  P.Mb = (int32_t)Mb;
+  P.nbr = (int32_t)nbr;
+  P.nbc = (int32_t)nbc;
+  P.W = (int32_t)ceil_div(N, 64);
+  P.br = idx->Br;
+  P.scale = softmax_scale;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  return d == 64 ? launch_bwd<64>(P, B, H, s) : launch_bwd<128>(P, B, H, s);
+}

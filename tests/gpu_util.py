@@ -17,10 +17,11 @@ def bf16_result_to_f64(t: torch.Tensor) -> np.ndarray:
 
 def index_to_numpy(idx):
     out = {}
-    for name in ("blk_class", "bin_blk_mat", "offset", "total_ones", "nz_lo", "nz_hi", "nz_cnt", "row_ptr"):
+    for name in ("blk_class", "bin_blk_mat", "offset", "total_ones", "nz_lo", "nz_hi", "nz_cnt", "row_ptr", "col_ptr"):
         t = getattr(idx, name)
         out[name] = None if t is None else t.cpu().numpy()
     out["col_idx"] = None if idx.col_idx is None else idx.col_idx.cpu().numpy().view(np.uint32)
+    out["row_idx"] = None if idx.row_idx is None else idx.row_idx.cpu().numpy().view(np.uint32)
     out["sched"] = None if idx.sched is None else idx.sched.cpu().numpy()
     out["packed_mask"] = None if idx.packed_mask is None else idx.packed_mask.cpu().numpy().view(np.uint64)
     return out
@@ -47,6 +48,13 @@ def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
         assert np.array_equal(got["sched"][:n], want["sched"][:n])
         Mb, nbr, _ = want["cls"].shape
         assert np.array_equal(got["sched"][-4 * Mb * nbr:], want["sched"][-4 * Mb * nbr:])       # longest-first row records
+    if got.get("col_ptr") is not None:
+        assert np.array_equal(got["col_ptr"], want["col_ptr"])
+        Mb, nbr, nbc = want["cls"].shape
+        for m in range(Mb):
+            n = int(want["col_ptr"][m, -1])
+            lo = m * nbr * nbc
+            assert np.array_equal(got["row_idx"][lo:lo + n], want["row_idx"][lo:lo + n])
     if got["packed_mask"] is not None:
         assert np.array_equal(got["packed_mask"], oracle.packed_bits(mask))
 
@@ -71,4 +79,18 @@ def assert_attention_close(o_gpu: torch.Tensor, lse_gpu: torch.Tensor, O_ref: np
     assert np.all(l[~fin] == -np.inf)
     if fin.any():
         assert np.abs(l[fin] - lse_ref[fin]).max() <= LSE_MAX_ABS
+    return err.max(), err.mean()
+
+
+# Gradients (bf16 outputs against the fp64 oracle).  The forward bar (2e-2 max-abs, 2e-3 mean-abs) is stated for O, a
+# convex combination of N(0,1) values; dQ, dK, dV are sums over keys resp. queries whose magnitude grows with the
+# number of terms, and every error source is relative to the terms (bf16 rounding of P, dS and of the result: 2^-9
+# each; the rounding of Q*scale*log2(e) resp. K*scale*log2(e), which moves a probability by up to about 1 %).  So
+# the same two bars are applied relative to the size of the tensor: G = max(1, max |reference|).
+def assert_grad_close(name: str, got_f64: np.ndarray, ref: np.ndarray):
+    assert not np.isnan(got_f64).any(), name
+    G = max(1.0, float(np.abs(ref).max()))
+    err = np.abs(got_f64 - ref)
+    assert err.max() <= O_MAX_ABS * G, f"{name}: max-abs {err.max()} at scale {G}"
+    assert err.mean() <= O_MEAN_ABS * G, f"{name}: mean-abs {err.mean()} at scale {G}"
     return err.max(), err.mean()

@@ -21,7 +21,7 @@ def test_every_declared_symbol_is_exported(bbm):
     names = set(re.findall(r"\b(bbm_[a-z_]+)\s*\(", hdr))
     assert names == {"bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs",
                      "bbm_build_sparse_index", "bbm_build_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes",
-                     "bbm_attn_fwd"}
+                     "bbm_attn_fwd", "bbm_build_col_index", "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd"}
     raw = C.CDLL(bbm.library_path())
     for n in names:
         assert getattr(raw, n) is not None
@@ -31,7 +31,8 @@ def test_every_declared_symbol_is_exported(bbm):
 def test_binding_has_the_same_names(bbm):
     for n in ("bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs", "bbm_build_sparse_index",
               "bbm_build_index",
-              "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd"):
+              "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd", "bbm_build_col_index",
+              "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd"):
         assert callable(getattr(bbm, n))
 
 
@@ -71,7 +72,7 @@ def test_index_builders_reject_bad_arguments(bbm):
 
 def _idx(bbm, Br=128, Bc=64, Mb=1, N=256, **ptrs):
     from paper_2409_15097_amd.binding import _CIndex
-    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), *([None] * 10))
+    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), *([None] * 12))
     for k, v in ptrs.items():
         setattr(s, k, v)
     return s
@@ -114,3 +115,33 @@ def test_workspace_query_and_check(bbm):
     idx = _idx(bbm, row_ptr=0x2000, col_idx=0x3000, sched=0x4000)
     assert _attn(bbm, idx, mode=bbm.BBM_MODE_LIST) == bbm.BBM_EWORKSPACE          # no workspace given
     assert "workspace" in bbm.bbm_last_error()
+
+
+def _bwd(bbm, idx, q=FAKE, do=FAKE, lse=FAKE, dk=FAKE, B=1, H=1, N=256, d=64, scale=0.125, Mb=1, packed=FAKE, ws=FAKE,
+         ws_bytes=1 << 20):
+    return bbm.lib.bbm_attn_bwd(q, FAKE, FAKE, FAKE, do, lse, FAKE, dk, FAKE, B, H, N, d, scale, Mb, packed,
+                                C.byref(idx) if idx else None, ws, ws_bytes, None)
+
+
+def test_attn_bwd_and_col_index_reject_bad_arguments(bbm):
+    L = bbm.lib
+    assert L.bbm_build_col_index(None, 1, 4, 4, FAKE, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_col_index(FAKE, 1, 4, 4, None, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_col_index(FAKE, 1, 4, 0, FAKE, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_col_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None) == bbm.BBM_EINVAL
+    assert bbm.bbm_attn_bwd_workspace_bytes(2, 3, 100) >= 2 * 4 * 600 and bbm.bbm_attn_bwd_workspace_bytes(0, 3, 100) == 0
+    full = _idx(bbm, row_ptr=0x2000, col_idx=0x3000, col_ptr=0x4000, row_idx=0x5000)
+    assert _bwd(bbm, full, q=None) == bbm.BBM_EINVAL
+    assert _bwd(bbm, full, lse=None) == bbm.BBM_EINVAL
+    assert _bwd(bbm, full, dk=C.c_void_p(0x1008)) == bbm.BBM_EINVAL and "aligned" in bbm.bbm_last_error()
+    assert _bwd(bbm, full, scale=0.0) == bbm.BBM_EINVAL
+    assert _bwd(bbm, full, B=4, Mb=2) == bbm.BBM_EINVAL
+    assert _bwd(bbm, None) == bbm.BBM_EINVAL
+    assert _bwd(bbm, full, packed=None) == bbm.BBM_EINVAL
+    assert _bwd(bbm, full, d=96) == bbm.BBM_EUNSUPPORTED
+    assert _bwd(bbm, _idx(bbm, Br=32, row_ptr=0x2000, col_idx=0x3000, col_ptr=0x4000, row_idx=0x5000)) == bbm.BBM_EUNSUPPORTED
+    assert _bwd(bbm, _idx(bbm, N=512, row_ptr=0x2000, col_idx=0x3000, col_ptr=0x4000, row_idx=0x5000)) == bbm.BBM_EINVAL
+    assert _bwd(bbm, _idx(bbm, row_ptr=0x2000, col_idx=0x3000)) == bbm.BBM_EINVAL and "column list" in bbm.bbm_last_error()
+    assert _bwd(bbm, full, ws=None) == bbm.BBM_EWORKSPACE
+    assert _bwd(bbm, full, ws_bytes=16) == bbm.BBM_EWORKSPACE
+    assert _bwd(bbm, full, ws=C.c_void_p(0x1008)) == bbm.BBM_EINVAL

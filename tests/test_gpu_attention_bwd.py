@@ -1,0 +1,187 @@
+"""GPU parity: backward pass of the fused masked attention (dQ, dK, dV) against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import masks, make_qkv, small_variant, make_config
+from gpu_util import bf16_tensor, bf16_result_to_f64, assert_grad_close, assert_index_equal, index_to_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+def _bbm():
+    import paper_2409_15097_amd as bbm
+    return bbm
+
+
+def _d_o(B, H, N, d, seed=991):
+    return make_qkv(B, H, N, d, seed=seed)[0]          # upstream gradient: seeded bf16 N(0,1), like the inputs
+
+
+def _gpu_grads(cfg, do_bits, Br, scale=None, idx=None):
+    bbm = _bbm()
+    if idx is None:
+        idx = bbm.build_index(torch.from_numpy(cfg["mask"]).cuda(), Br, 64, columns=True)
+    q, k, v = (bf16_tensor(cfg[x]) for x in "qkv")
+    o, lse = bbm.bbm_attn_fwd(q, k, v, idx, softmax_scale=scale)
+    dq, dk, dv = bbm.bbm_attn_bwd(q, k, v, o, bf16_tensor(do_bits), lse, idx, softmax_scale=scale)
+    torch.cuda.synchronize()
+    return dq, dk, dv
+
+
+def _check(grads, ref):
+    for name, g, r in zip(("dQ", "dK", "dV"), grads, ref):
+        assert_grad_close(name, bf16_result_to_f64(g), r)
+
+
+@pytest.mark.parametrize("Br", [64, 128, 256])
+@pytest.mark.parametrize("N", [200, 1000, 77])
+def test_column_index_matches_oracle(N, Br):
+    bbm = _bbm()
+    mask = np.stack([masks.random_blocks(64 * (-(-N // 64)), N + s, blk=32, p_empty=0.5, p_full=0.3)[0][:N, :N] for s in (1, 2)])
+    idx = bbm.build_index(torch.from_numpy(np.ascontiguousarray(mask)).cuda(), Br, 64, columns=True)
+    torch.cuda.synchronize()
+    assert_index_equal(index_to_numpy(idx), mask, Br, 64)
+
+
+SMALL = [("C1", 256, 1, 2), ("C2", 1024, 2, 2), ("C3", 640, 1, 2), ("C4", 2048, 1, 2), ("C5", 2048, 1, 2),
+         ("C0d", 512, 1, 2), ("C0c", 512, 1, 2)]
+
+
+@pytest.mark.parametrize("name,N,B,H", SMALL)
+def test_small_variants(name, N, B, H):
+    cfg = small_variant(name, N=N, B=B, H=H)
+    do = _d_o(*cfg["q"].shape)
+    ref = oracle.masked_attention_bwd(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], do)
+    first = None
+    for Br in (64, 128, 256):
+        print(f"bwd case {name} N={N} Br={Br}", flush=True)
+        grads = _gpu_grads(cfg, do, Br)
+        _check(grads, ref)
+        # one lane owns one query (dQ) resp. one key (dK, dV) and walks its tiles in ascending order whatever the
+        # block height; blocks that are skipped or unmasked at one height and not at another contribute exact zeros
+        bits = [g.view(torch.int16) for g in grads]
+        if first is None:
+            first = bits
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(bits, first))
+
+
+@pytest.mark.parametrize("N", [200, 333, 77, 1, 65, 1000])
+@pytest.mark.parametrize("d", [64, 128])
+def test_ragged_sizes_with_empty_rows_and_unattended_keys(N, d):
+    B, H = 2, 3
+    q, k, v = make_qkv(B, H, N, d, seed=N + d)
+    do = _d_o(B, H, N, d, seed=N + d + 5)
+    rng = np.random.default_rng(N)
+    m = masks.random_blocks(64 * (-(-N // 64)), N + 1, blk=32, p_empty=0.4, p_full=0.3)[0][:N, :N].copy()
+    empty = rng.integers(0, N, size=max(1, N // 10))
+    m[empty] = 0                                             # fully masked query rows
+    dead = rng.integers(0, N, size=max(1, N // 10))
+    mask = np.stack([m, np.roll(m, 3, axis=1)])
+    mask[:, :, dead] = 0                                     # keys nobody attends
+    cfg = dict(q=q, k=k, v=v, mask=mask)
+    ref = oracle.masked_attention_bwd(q, k, v, mask, do)
+    for Br in (64, 128, 256):
+        print(f"bwd ragged N={N} d={d} Br={Br}", flush=True)
+        dq, dk, dv = _gpu_grads(cfg, do, Br)
+        _check((dq, dk, dv), ref)
+        assert torch.all(dq[0, :, empty] == 0)
+        assert torch.all(dk[:, :, dead] == 0) and torch.all(dv[:, :, dead] == 0)
+
+
+def test_custom_scale_d128():
+    """Sharper scales move the probabilities more when Q resp. K times scale*log2(e) is rounded to bf16: as in the
+    forward test, the bars of a scale above 1/sqrt(d) are widened by scale*sqrt(d)."""
+    cfg = small_variant("C3", N=640, B=2, H=2)
+    d = cfg["q"].shape[-1]
+    do = _d_o(*cfg["q"].shape)
+    for scale in (0.05, 0.3):
+        widen = max(1.0, scale * d ** 0.5)
+        ref = oracle.masked_attention_bwd(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], do, scale=scale)
+        grads = _gpu_grads(cfg, do, 128, scale=scale)
+        for g, r in zip(grads, ref):
+            err = np.abs(bf16_result_to_f64(g) - r)
+            G = max(1.0, np.abs(r).max())
+            assert err.max() <= 2e-2 * G * widen and err.mean() <= 2e-3 * G * widen
+
+
+def test_single_allowed_key_routes_dO_to_dV():
+    """One allowed key per query: P = 1 exactly, so dS = 0 and dV_j is the sum of the dO rows that chose key j."""
+    B, H, N, d = 1, 2, 320, 64
+    q, k, v = make_qkv(B, H, N, d, seed=3)
+    do = _d_o(B, H, N, d)
+    pi = np.random.default_rng(3).permutation(N)
+    mask = np.zeros((1, N, N), dtype=np.uint8)
+    mask[0, np.arange(N), pi] = 1
+    dq, dk, dv = _gpu_grads(dict(q=q, k=k, v=v, mask=mask), do, 64)
+    want = np.zeros((B, H, N, d))
+    want[:, :, pi] = oracle.bf16_bits_to_f64(do)
+    # the stored lse carries the rounding of Q*scale*log2(e): P = exp(s' - lse) is 1 up to that, not bit-exactly
+    assert np.abs(bf16_result_to_f64(dv) - want).max() <= 2e-2 * np.abs(want).max()
+    assert np.abs(bf16_result_to_f64(dq)).max() <= 2e-2 and np.abs(bf16_result_to_f64(dk)).max() <= 2e-2
+
+
+def test_deterministic():
+    cfg = small_variant("C4", N=2048, B=1, H=2)
+    do = _d_o(*cfg["q"].shape)
+    a = _gpu_grads(cfg, do, 128)
+    b = _gpu_grads(cfg, do, 128)
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_sampled_rows_and_columns(name):
+    """At the benchmark sizes the oracle evaluates sampled query rows (dQ) and sampled keys (dK, dV) one by one."""
+    bbm = _bbm()
+    cfg = make_config(name)
+    B, H, N, d = cfg["B"], cfg["H"], cfg["N"], cfg["d"]
+    do = _d_o(B, H, N, d)
+    rng = np.random.default_rng(17)
+    rows = [(int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(N))) for _ in range(96)]
+    empty = np.flatnonzero(cfg["mask"][0].sum(axis=1) == 0)
+    rows += [(0, 0, int(r)) for r in empty[:4]] + [(B - 1, H - 1, N - 1), (0, 0, 0)]
+    cols = [(int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(N))) for _ in range(24)] + [(0, 0, 0), (B - 1, H - 1, N - 1)]
+    print(f"bwd full {name}: oracle", flush=True)
+    dq_ref = oracle.masked_attention_bwd_rows(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], do, rows)
+    dk_ref, dv_ref = oracle.masked_attention_bwd_cols(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], do, cols)
+    print(f"bwd full {name}: gpu", flush=True)
+    dq, dk, dv = _gpu_grads(cfg, do, 128)
+    bi, hi, ri = (torch.tensor(x, device="cuda") for x in zip(*rows))
+    assert_grad_close("dQ", bf16_result_to_f64(dq[bi, hi, ri]), dq_ref)
+    bi, hi, ci = (torch.tensor(x, device="cuda") for x in zip(*cols))
+    assert_grad_close("dK", bf16_result_to_f64(dk[bi, hi, ci]), dk_ref)
+    assert_grad_close("dV", bf16_result_to_f64(dv[bi, hi, ci]), dv_ref)
+    for g in (dq, dk, dv):
+        assert not torch.isnan(g.float()).any()
+    if empty.size:
+        assert torch.all(dq[0, :, torch.from_numpy(empty).cuda()] == 0)
+
+
+def test_lists_longer_than_one_window():
+    """A block row and a block column with more entries than one LDS list window (256): global query rows that see
+    every key, global keys that every query sees, a band elsewhere; ragged N."""
+    B, H, N, d, Br = 1, 1, 16500, 64, 64
+    q, k, v = make_qkv(B, H, N, d, seed=31)
+    do = _d_o(B, H, N, d, seed=32)
+    i = np.arange(N)
+    mask = (np.abs(i[:, None] - i[None, :]) <= 40).astype(np.uint8)
+    mask[:, :64] = 1
+    mask[100:132] = 1
+    cfg = dict(q=q, k=k, v=v, mask=mask[None])
+    bbm = _bbm()
+    idx = bbm.build_index(torch.from_numpy(cfg["mask"]).cuda(), Br, 64, columns=True)
+    rp, cp = idx.row_ptr.cpu().numpy()[0], idx.col_ptr.cpu().numpy()[0]
+    assert (rp[1:] - rp[:-1]).max() == 258 and (cp[1:] - cp[:-1]).max() == 258
+    rows = [(0, 0, r) for r in (0, 100, 131, 132, 5000, 16447, 16448, 16499)]
+    cols = [(0, 0, c) for c in (0, 63, 64, 120, 9000, 16499)]
+    dq_ref = oracle.masked_attention_bwd_rows(q, k, v, cfg["mask"], do, rows)
+    dk_ref, dv_ref = oracle.masked_attention_bwd_cols(q, k, v, cfg["mask"], do, cols)
+    dq, dk, dv = _gpu_grads(cfg, do, Br, idx=idx)
+    assert_grad_close("dQ", bf16_result_to_f64(dq[0, 0, [r for _, _, r in rows]]), dq_ref)
+    assert_grad_close("dK", bf16_result_to_f64(dk[0, 0, [c for _, _, c in cols]]), dk_ref)
+    assert_grad_close("dV", bf16_result_to_f64(dv[0, 0, [c for _, _, c in cols]]), dv_ref)
+    for g in (dq, dk, dv):
+        assert not torch.isnan(g.float()).any()

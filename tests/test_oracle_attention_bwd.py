@@ -139,7 +139,7 @@ def test_sampled_rows_and_columns_match_full():
     dQ, dK, dV = oracle.masked_attention_bwd(q, k, v, mask, do, scale=0.2)
     picks = [(0, 0, 0), (0, 1, 3), (1, 0, 17), (1, 1, 23), (1, 0, 5)]
     r = oracle.masked_attention_bwd_rows(q, k, v, mask, do, picks, scale=0.2)
-    ck, cv = oracle.masked_attention_bwd_cols(q, k, v, mask, do, picks, scale=0.2, row_chunk=5)
+    ck, cv = oracle.masked_attention_bwd_cols(q, k, v, mask, do, picks, scale=0.2)
     for n, (b, h, i) in enumerate(picks):
         assert np.abs(r[n] - dQ[b, h, i]).max() < 1e-13
         assert np.abs(ck[n] - dK[b, h, i]).max() < 1e-13
