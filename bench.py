@@ -49,7 +49,10 @@ def parse():
                     help="comma list of extra workloads measured the same way and reported under per_mask, or 'all' "
                          "(C3,C4,C5,C0d,C0c,C0d128,C0c128); default: the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only-kernel", default="", help="profile helper: run only 'attn', 'preprocess' or 'copy' (256 MiB device copy) launches")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time the backward pass (column list + dQ and dK/dV kernels) per mask; reported beside the "
+                         "forward figures, the headline value stays the forward step")
+    ap.add_argument("--only-kernel", default="", help="profile helper: run only 'attn', 'bwd', 'preprocess' or 'copy' (256 MiB device copy) launches")
     return ap.parse_args()
 
 
@@ -75,7 +78,7 @@ def visited_tiles(idx, B, H):
     return int(per_batch.sum()) * H
 
 
-def measure_mask(bbm, name, Br, warmup, steps, torch):
+def measure_mask(bbm, name, Br, warmup, steps, torch, backward=False):
     from workloads import make_config
     cfg = make_config(name)
     B, H, N, d, Mb = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["Mb"]
@@ -119,6 +122,22 @@ def measure_mask(bbm, name, Br, warmup, steps, torch):
     res["preprocess_gbs"] = pre_bytes / (pre_ms * 1e-3) / 1e9
     res["preprocess_hbm_frac"] = res["preprocess_gbs"] / HBM_PEAK_GBS
     res["index_ms"] = time_gpu(lambda: bbm.bbm_build_index(idx), warmup, steps)
+    if backward:
+        # backward pass: 5 products per visited tile are needed (S, dP, dV, dK, dQ); the two-kernel split executes 7
+        # (S and dP are recomputed by both kernels)
+        d_o = bbm.bf16_from_bits(cfg["q"][..., ::-1].copy())             # any seeded bf16 tensor of the right shape
+        dq, dk, dv = (torch.empty_like(q) for _ in range(3))
+        ws_b = torch.zeros(bbm.bbm_attn_bwd_workspace_bytes(B, H, N, d, Br), dtype=torch.uint8, device="cuda")
+        bbm.bbm_build_col_index(idx)
+        bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws)
+        res["col_index_ms"] = time_gpu(lambda: bbm.bbm_build_col_index(idx), warmup, steps)
+        res["bwd_ms"] = time_gpu(lambda: bbm.bbm_attn_bwd(q, k, v, out, d_o, lse, idx, dq=dq, dk=dk, dv=dv, workspace=ws_b),
+                                 warmup, steps)
+        res["bwd_tflops_visited"] = 2.5 * flops / (res["bwd_ms"] * 1e-3) / 1e12
+        res["bwd_mfma_frac"] = res["bwd_tflops_visited"] / MFMA_BF16_PEAK_TFLOPS
+        res["bwd_executed_tflops"] = 3.5 * flops / (res["bwd_ms"] * 1e-3) / 1e12
+        res["fwd_bwd_ms"] = res["attn_ms"] + res["bwd_ms"]
+        del d_o, dq, dk, dv, ws_b
     # algorithmic HBM bytes of the attention kernel: Q, K, V read once, O written once, lse, packed words of partial tiles
     res["attn_algo_bytes"] = 4.0 * B * H * N * d * 2 + 4.0 * B * H * N + census["partial"] * (B // Mb) * Br * 8.0
     del mask, q, k, v, idx, out, lse, ws
@@ -176,16 +195,22 @@ def main():
         from workloads import make_config
         cfg = make_config(a.workload)
         mask = torch.from_numpy(cfg["mask"]).cuda()
-        idx = bbm.build_index(mask, a.Br, 64)
+        idx = bbm.build_index(mask, a.Br, 64, columns=True)
         q, k, v = (bbm.bf16_from_bits(cfg[x]) for x in "qkv")
         out = torch.empty_like(q)
         lse = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+        d_o = bbm.bf16_from_bits(cfg["q"][..., ::-1].copy())
+        dq, dk, dv = (torch.empty_like(q) for _ in range(3))
+        ws_b = torch.zeros(bbm.bbm_attn_bwd_workspace_bytes(*q.shape, a.Br), dtype=torch.uint8, device="cuda")
         ws = torch.zeros(max(16, bbm.bbm_attn_fwd_workspace_bytes(*q.shape, a.Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
         src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda").fill_(1)     # 256 MiB copy for counter calibration
         dst = torch.empty_like(src)
+        bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws)
         torch.cuda.synchronize()
         for _ in range(a.warmup + a.steps):
-            if a.only_kernel == "attn":
+            if a.only_kernel == "bwd":
+                bbm.bbm_attn_bwd(q, k, v, out, d_o, lse, idx, dq=dq, dk=dk, dv=dv, workspace=ws_b)
+            elif a.only_kernel == "attn":
                 bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws)
             elif a.only_kernel == "preprocess":
                 bbm.bbm_build_block_mask(mask, a.Br, 64, idx=idx)
@@ -196,11 +221,11 @@ def main():
         torch.cuda.synchronize()
         return 0
 
-    main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch)
+    main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch, a.backward)
     rows = [main_res]
     extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128" if a.masks == "all" else a.masks
     for name in [m for m in extra.split(",") if m and m != a.workload]:
-        r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch)
+        r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch, a.backward)
         rows.append(r)
 
     flops = main_res["visited_tflop"] * 1e12

@@ -68,6 +68,7 @@ typedef struct bbm_index {
   const int32_t* sched;       /* bbm_sched_bytes(Mb, nbr) bytes: tile schedule of LIST mode           */
   const int32_t* col_ptr;     /* [Mb, nbc + 1] column-list offsets within a plane (backward pass)    */
   const uint32_t* row_idx;    /* [Mb * nbr * nbc]; plane m starts at m*nbr*nbc; bit 31 = block full  */
+  const int32_t* col_sched;   /* bbm_col_sched_bytes(Mb, nbc) bytes: split schedule of the column walk */
 } bbm_index;
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
@@ -212,13 +213,24 @@ int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* ls
  *   row_idx          device out, uint32, capacity Mb*nbr*nbc entries; the list of plane m starts at entry m*nbr*nbc;
  *                    block rows ascending within a column; bit 31 set iff the block is full.  Entries past
  *                    col_ptr[m][nbc] are left untouched.
- * Requires nbr*nbc < 2^31.  Errors: BBM_EINVAL, BBM_EHIP.
+ *   col_sched        device out, bbm_col_sched_bytes(Mb, nbc) bytes, 32-byte aligned; may be NULL.  The split schedule
+ *                    that keeps one very long block column (a block of global keys, say) from becoming the critical
+ *                    path of the dK/dV step: columns with more than T = max(16, 2 * mean entries per non-empty
+ *                    column) list entries are cut into ceil(n/T) near-equal parts.  int32 layout as the part table of
+ *                    bbm_build_sparse_index's schedule: [0] parts, [1] T, [2] cut columns, [3..7] 0, then 8 ints per
+ *                    part ordered by (column, part): plane*nbc + block column, first entry (position in the plane's
+ *                    list), entries, part, parts of the column, number of the column's first part, index of the column
+ *                    among the cut columns, the list entry at the part's first position.  (No launch-order records.)
+ * Requires nbr*nbc < 2^31, and Mb*nbc < 2^24 if col_sched is given.  Errors: BBM_EINVAL, BBM_EHIP.
  */
 int bbm_build_col_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* col_ptr,
-                        uint32_t* row_idx, void* stream);
+                        uint32_t* row_idx, int32_t* col_sched, void* stream);
 
-/* Bytes of device workspace bbm_attn_bwd needs (0 for sizes < 1). */
-size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N);
+/* Bytes of the column schedule bbm_build_col_index writes for Mb planes of nbc block columns (0 for sizes < 1). */
+size_t bbm_col_sched_bytes(int64_t Mb, int64_t nbc);
+
+/* Bytes of device workspace bbm_attn_bwd needs for this problem (0 for sizes < 1 or a (d, Br) without a kernel). */
+size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int Br);
 
 /*
  * Backward pass of bbm_attn_fwd (paper Sec. 3 "Flash Attention": the attention matrix is recomputed block by block
@@ -235,13 +247,18 @@ size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N);
  *                    is written.
  *   d, softmax_scale, Mb, packed_mask   as for bbm_attn_fwd (the same values as in the forward call).
  *   idx              host pointer; Br, Bc, Mb, nbr, nbc as for bbm_attn_fwd; needs row_ptr, col_idx (the dQ step walks
- *                    block rows), col_ptr, row_idx (the dK/dV step walks block columns); sched is used for the launch
- *                    order of the block rows if present.
- *   workspace        device scratch of at least bbm_attn_bwd_workspace_bytes(B, H, N) bytes, 16-byte aligned; holds D
- *                    and the log-sum-exp in the form the second kernel consumes.  Needs no initialisation.
+ *                    block rows), col_ptr, row_idx (the dK/dV step walks block columns).  If sched resp. col_sched is
+ *                    present, block rows resp. columns the schedule cut are computed part by part by the leading
+ *                    work-groups and summed in part order (and sched gives the launch order of the block rows).
+ *   workspace        device scratch of at least bbm_attn_bwd_workspace_bytes(B, H, N, d, idx->Br) bytes, 16-byte
+ *                    aligned; holds the queue counters, D and the log-sum-exp in the form the second kernel consumes,
+ *                    and the fp32 partial sums of cut rows and columns (an upper bound: most of it is never touched).
+ *                    Like the forward workspace it must be ZERO-FILLED ONCE after it is allocated; every call puts
+ *                    back the zeros it disturbed.  Two calls that overlap in time must not share a workspace.
  * Arithmetic: all five products on bf16 MFMA with fp32 accumulation; Q (dQ step) resp. K (dK/dV step) is multiplied by
  * softmax_scale*log2(e) and rounded to bf16 once; P and dS are rounded to bf16 before the products that consume them.
- * Two kernels, no atomics: the same inputs give bit-identical outputs.
+ * Two kernels, no floating-point atomics: the same inputs give bit-identical outputs (parts of a cut row or column are
+ * taken from a queue in whatever order work-groups become free, but are summed in part order).
  * Errors: BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EWORKSPACE, BBM_EHIP.
  */
 int bbm_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,

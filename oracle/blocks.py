@@ -186,6 +186,44 @@ def schedule(row_ptr, col_idx):
     return out
 
 
+COL_SCHED_MIN_SPLIT = 16
+
+
+def column_schedule(col_ptr, row_idx):
+    """Split schedule of the backward pass's column walk (this build's own layout, stated in the library header).
+
+    col_ptr int32 [Mb, nbc+1], row_idx uint32 [Mb*nbr*nbc] (as column_index returns them) -> int32 array of
+    8 + 8*Mb*nbc entries: [0] parts, [1] split threshold T = max(16, 2*ceil(mean list length of the non-empty
+    columns)), [2] cut columns, [3..7] 0, then 8 ints per part in (column, part) order: column (= plane*nbc + block
+    column), first entry (position in the plane's list), entries, part, parts of the column, number of the column's
+    first part, index of the column among the cut columns, the list entry at the part's first position (as int32).
+    A column with n > T entries is cut into ceil(n/T) parts of ceil(n/parts) entries (the last part takes the rest);
+    columns with n <= T are not listed.  Table entries past the last part are unspecified."""
+    Mb, nbc1 = col_ptr.shape
+    nbc = nbc1 - 1
+    counts = [int(col_ptr[m, j + 1] - col_ptr[m, j]) for m in range(Mb) for j in range(nbc)]
+    nonempty = sum(1 for c in counts if c > 0)
+    mean = -(-sum(counts) // nonempty) if nonempty else 0
+    T = max(COL_SCHED_MIN_SPLIT, 2 * mean)
+    out = np.zeros(SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbc, dtype=np.int32)
+    lists = np.asarray(row_idx, dtype=np.uint32).reshape(Mb, -1)
+    q, rho = 0, 0
+    for col, c in enumerate(counts):
+        if c <= T:
+            continue
+        parts = -(-c // T)
+        chunk = -(-c // parts)
+        m = col // nbc
+        for k in range(parts):
+            first = int(col_ptr[m, col % nbc]) + k * chunk
+            o = SCHED_PART_BASE + SCHED_PART_INTS * (q + k)
+            out[o:o + 8] = (col, first, min(chunk, c - k * chunk), k, parts, q, rho, int(lists[m, first].astype(np.int32)))
+        q += parts
+        rho += 1
+    out[0], out[1], out[2] = q, T, rho
+    return out
+
+
 def block_index(mask, Br, Bc):
     """Everything the preprocessing stage produces, as a dict."""
     cls = block_class(mask, Br, Bc)
@@ -194,4 +232,5 @@ def block_index(mask, Br, Bc):
     idx["row_ptr"], idx["col_idx"] = sparse_index(cls)
     idx["sched"] = schedule(idx["row_ptr"], idx["col_idx"])
     idx["col_ptr"], idx["row_idx"] = column_index(cls)
+    idx["col_sched"] = column_schedule(idx["col_ptr"], idx["row_idx"])
     return idx

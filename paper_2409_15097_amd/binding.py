@@ -23,7 +23,7 @@ class _CIndex(C.Structure):
                 ("blk_class", C.c_void_p), ("bin_blk_mat", C.c_void_p), ("offset", C.c_void_p),
                 ("total_ones", C.c_void_p), ("nz_lo", C.c_void_p), ("nz_hi", C.c_void_p), ("nz_cnt", C.c_void_p),
                 ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("sched", C.c_void_p),
-                ("col_ptr", C.c_void_p), ("row_idx", C.c_void_p)]
+                ("col_ptr", C.c_void_p), ("row_idx", C.c_void_p), ("col_sched", C.c_void_p)]
 
 
 def library_path() -> str:
@@ -56,9 +56,11 @@ def _load():
     L.bbm_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, C.c_float, i64, vp, C.POINTER(_CIndex), ci,
                                vp, C.c_size_t, vp]
     L.bbm_build_col_index.restype = ci
-    L.bbm_build_col_index.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    L.bbm_build_col_index.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
+    L.bbm_col_sched_bytes.restype = C.c_size_t
+    L.bbm_col_sched_bytes.argtypes = [i64, i64]
     L.bbm_attn_bwd_workspace_bytes.restype = C.c_size_t
-    L.bbm_attn_bwd_workspace_bytes.argtypes = [i64, i64, i64]
+    L.bbm_attn_bwd_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
     L.bbm_attn_bwd.restype = ci
     L.bbm_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, C.c_float, i64, vp,
                                C.POINTER(_CIndex), vp, C.c_size_t, vp]
@@ -117,12 +119,13 @@ class BlockIndex:
     sched: Optional[torch.Tensor] = None
     col_ptr: Optional[torch.Tensor] = None
     row_idx: Optional[torch.Tensor] = None
+    col_sched: Optional[torch.Tensor] = None
 
     def c_struct(self) -> _CIndex:
         g = lambda t: None if t is None else t.data_ptr()
         return _CIndex(self.Br, self.Bc, self.Mb, self.nbr, self.nbc, g(self.blk_class), g(self.bin_blk_mat),
                        g(self.offset), g(self.total_ones), g(self.nz_lo), g(self.nz_hi), g(self.nz_cnt),
-                       g(self.row_ptr), g(self.col_idx), g(self.sched), g(self.col_ptr), g(self.row_idx))
+                       g(self.row_ptr), g(self.col_idx), g(self.sched), g(self.col_ptr), g(self.row_idx), g(self.col_sched))
 
 
 def bbm_build_block_mask(mask: torch.Tensor, Br: int, Bc: int, idx: Optional[BlockIndex] = None,
@@ -197,9 +200,15 @@ def bbm_build_col_index(idx: BlockIndex, stream=None) -> BlockIndex:
         idx.col_ptr = torch.empty((idx.Mb, idx.nbc + 1), dtype=torch.int32, device=dev)
     if idx.row_idx is None:
         idx.row_idx = torch.zeros(idx.Mb * idx.nbr * idx.nbc, dtype=torch.int32, device=dev)
+    if idx.col_sched is None:
+        idx.col_sched = torch.empty(bbm_col_sched_bytes(idx.Mb, idx.nbc) // 4, dtype=torch.int32, device=dev)
     _check(lib.bbm_build_col_index(_ptr(idx.blk_class), idx.Mb, idx.nbr, idx.nbc, _ptr(idx.col_ptr), _ptr(idx.row_idx),
-                                   _stream(stream)))
+                                   _ptr(idx.col_sched), _stream(stream)))
     return idx
+
+
+def bbm_col_sched_bytes(Mb: int, nbc: int) -> int:
+    return int(lib.bbm_col_sched_bytes(Mb, nbc))
 
 
 def build_index(mask: torch.Tensor, Br: int, Bc: int = 64, idx: Optional[BlockIndex] = None, stream=None,
@@ -251,8 +260,8 @@ def bbm_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIn
     return out, lse
 
 
-def bbm_attn_bwd_workspace_bytes(B, H, N) -> int:
-    return int(lib.bbm_attn_bwd_workspace_bytes(B, H, N))
+def bbm_attn_bwd_workspace_bytes(B, H, N, d, Br) -> int:
+    return int(lib.bbm_attn_bwd_workspace_bytes(B, H, N, d, Br))
 
 
 def bbm_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor, d_o: torch.Tensor,
@@ -270,8 +279,8 @@ def bbm_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Ten
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(q) if dk is None else dk
     dv = torch.empty_like(q) if dv is None else dv
-    if workspace is None:
-        workspace = torch.empty(bbm_attn_bwd_workspace_bytes(B, H, N), dtype=torch.uint8, device=q.device)
+    if workspace is None:   # the library wants it zero-filled once
+        workspace = torch.zeros(bbm_attn_bwd_workspace_bytes(B, H, N, d, idx.Br), dtype=torch.uint8, device=q.device)
     cs = idx.c_struct()
     _check(lib.bbm_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv),
                             B, H, N, d, softmax_scale, idx.Mb, _ptr(idx.packed_mask), C.byref(cs), _ptr(workspace),

@@ -26,7 +26,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kWin = 256;                   // list entries per LDS window
+constexpr int kWin = 128;                   // list entries per LDS window
 constexpr uint32_t kNoTile = 0xffffffffu;
 
 struct BwdParams {
@@ -53,6 +53,16 @@ struct BwdParams {
   int32_t G;
   int32_t br;       // query rows per block row
   float scale;
+  // Cut block rows (dQ) and cut block columns (dK, dV): the split schedules (read-only), and in the caller's workspace
+  // the work-queue state and the fp32 partial results of the parts.  Counters: [0] part items handed out, [1] leading
+  // work-groups done, [8 + rho*hbp + hb] finished parts of cut row/column rho; all zero between calls.
+  const int32_t* csched;   // column schedule; may be NULL (no column is cut then)
+  int32_t* row_queue;
+  int32_t* col_queue;
+  float* row_partials;     // [(cut part)*hbp + hb][Br*D]
+  float* col_partials;     // [(cut part)*hbp + hb][2][64*D]
+  int32_t hbp;             // (batch, head) pairs per mask plane
+  int32_t n_extra;         // leading work-groups that serve the queue of parts before their own row/column
 };
 
 __device__ __forceinline__ float partner_sum(float x) {
@@ -175,6 +185,10 @@ __device__ __forceinline__ int logical_wg(int wg, int total) {
 // ------------------------------------------------------------------------------------------------------------------
 // dQ (and D, and the negated statistics for the dK/dV kernel)
 // ------------------------------------------------------------------------------------------------------------------
+// One work-group per (block row, batch, head).  The first P.n_extra work-groups, before turning to their own block
+// row, take the parts of the block rows which the split schedule cut from a queue; the work-group that completes a
+// row's last part adds the parts up in part order and writes the row, and the row's own work-group only writes the
+// statistics.
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P) {
   using L = TL<D>;
@@ -182,6 +196,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P)
   constexpr int BR = NW * 32;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
+  constexpr int REGS = DB * 16;
   static_assert(2 * 32 * D <= L::ELEMS && NW <= 8, "two 32 x D output slabs must fit in each tile buffer");
 
   __shared__ __attribute__((aligned(16))) __bf16 k_s0[L::ELEMS];
@@ -189,6 +204,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P)
   __shared__ __attribute__((aligned(16))) __bf16 v_s0[L::ELEMS];
   __shared__ __attribute__((aligned(16))) __bf16 v_s1[L::ELEMS];
   __shared__ uint32_t tiles_s[kWin + 4];
+  __shared__ int item_s[2];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -196,72 +212,55 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P)
   const int64_t N = P.N;
   const float c = P.scale * kLog2e;
 
-  // ---- which block row: rank-major interleave of G (batch, head) planes, as in the forward kernel
-  int bh, m, rank;
-  {
-    const int logical = logical_wg((int)blockIdx.x, P.total_wgs);
-    const int grp = logical / (P.G * P.nbr), within = logical - grp * (P.G * P.nbr);
-    const int g_planes = min(P.G, P.total_wgs / P.nbr - grp * P.G);
-    rank = within / g_planes;
-    bh = grp * P.G + (within - rank * g_planes);
-    m = (P.Mb == 1) ? 0 : bh / P.H;
-  }
-  int i, list_pos, n_list;
-  if (P.sched) {
-    const int4 rec = *reinterpret_cast<const int4*>(P.sched + bbm::sched_order_base(P.Mb, P.nbr) +
-                                                    bbm::kSchedRowInts * (int64_t)(m * P.nbr + rank));
-    i = rec.x;
-    list_pos = rec.y;
-    n_list = rec.z;
-  } else {
-    i = P.nbr - 1 - rank;
-    list_pos = P.row_ptr[(int64_t)m * (P.nbr + 1) + i];
-    n_list = P.row_ptr[(int64_t)m * (P.nbr + 1) + i + 1] - list_pos;
-  }
-  const uint32_t* __restrict__ list = P.col_idx + (int64_t)m * P.nbr * P.nbc + list_pos;
-
-  const int64_t head_off = (int64_t)bh * N * D;
-  const __bf16* __restrict__ Kg = P.k + head_off;
-  const __bf16* __restrict__ Vg = P.v + head_off;
-  const int64_t qrow = (int64_t)i * BR + wave * 32 + lq;
-  const bool q_ok = qrow < N;
-  const uint64_t* __restrict__ mrow = P.packed + (int64_t)m * P.W * N + (q_ok ? qrow : 0);
-
-  // ---- this lane's query: Q * scale * log2(e) and dO as B operands, D = <dO, O>, the negated statistics
+  // ---- per-item state
+  int bh, m, i;
+  int64_t head_off;
+  const __bf16* __restrict__ Kg;
+  const __bf16* __restrict__ Vg;
+  const uint64_t* __restrict__ mrow;
   bf16x8 qf[KS], dof[KS];
-  float dsum = 0.0f;
+  f32x16 s_init, dp_init, dq[DB];
+
+  // this lane's query: Q * scale * log2(e) and dO as B operands, D = <dO, O>, the negated statistics
+  auto begin_item = [&](bool write_stats) {
+    head_off = (int64_t)bh * N * D;
+    Kg = P.k + head_off;
+    Vg = P.v + head_off;
+    const int64_t qrow = (int64_t)i * BR + wave * 32 + lq;
+    const bool q_ok = qrow < N;
+    mrow = P.packed + (int64_t)m * P.W * N + (q_ok ? qrow : 0);
+    float dsum = 0.0f;
 #pragma unroll
-  for (int t = 0; t < KS; ++t) {
-    bf16x8 of;
-    if (q_ok) {
-      const int64_t at = head_off + qrow * D + 16 * t + 8 * hh;
-      qf[t] = *reinterpret_cast<const bf16x8*>(P.q + at);
-      dof[t] = *reinterpret_cast<const bf16x8*>(P.d_o + at);
-      of = *reinterpret_cast<const bf16x8*>(P.o + at);
-    } else {
-      for (int e = 0; e < 8; ++e) qf[t][e] = dof[t][e] = of[e] = (__bf16)0.0f;
+    for (int t = 0; t < KS; ++t) {
+      bf16x8 of;
+      if (q_ok) {
+        const int64_t at = head_off + qrow * D + 16 * t + 8 * hh;
+        qf[t] = *reinterpret_cast<const bf16x8*>(P.q + at);
+        dof[t] = *reinterpret_cast<const bf16x8*>(P.d_o + at);
+        of = *reinterpret_cast<const bf16x8*>(P.o + at);
+      } else {
+        for (int e = 0; e < 8; ++e) qf[t][e] = dof[t][e] = of[e] = (__bf16)0.0f;
+      }
+      for (int e = 0; e < 8; ++e) {
+        dsum += (float)dof[t][e] * (float)of[e];
+        qf[t][e] = (__bf16)((float)qf[t][e] * c);
+      }
     }
-    for (int e = 0; e < 8; ++e) {
-      dsum += (float)dof[t][e] * (float)of[e];
-      qf[t][e] = (__bf16)((float)qf[t][e] * c);
+    const float delta = partner_sum(dsum);
+    const float lse_i = q_ok ? P.lse[(int64_t)bh * N + qrow] : -INFINITY;
+    const float nl = (lse_i == -INFINITY) ? -INFINITY : -lse_i * kLog2e;
+    if (write_stats && q_ok && hh == 0) {
+      P.nl2[(int64_t)bh * N + qrow] = nl;
+      P.ndelta[(int64_t)bh * N + qrow] = -delta;
     }
-  }
-  const float delta = partner_sum(dsum);
-  const float lse_i = q_ok ? P.lse[(int64_t)bh * N + qrow] : -INFINITY;
-  const float nl = (lse_i == -INFINITY) ? -INFINITY : -lse_i * kLog2e;
-  if (q_ok && hh == 0) {
-    P.nl2[(int64_t)bh * N + qrow] = nl;
-    P.ndelta[(int64_t)bh * N + qrow] = -delta;
-  }
-  f32x16 s_init, dp_init;
-  for (int e = 0; e < 16; ++e) {
-    s_init[e] = nl;
-    dp_init[e] = -delta;
-  }
-  f32x16 dq[DB];
+    for (int e = 0; e < 16; ++e) {
+      s_init[e] = nl;
+      dp_init[e] = -delta;
+    }
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-    for (int e = 0; e < 16; ++e) dq[db][e] = 0.0f;
+    for (int db = 0; db < DB; ++db)
+      for (int e = 0; e < 16; ++e) dq[db][e] = 0.0f;
+  };
 
   TileAddr<D> A;
   A.init(lane);
@@ -284,77 +283,174 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P)
     __bf16* const k_oth = PB ? k_s0 : k_s1;
     __bf16* const v_cur = PB ? v_s1 : v_s0;
     __bf16* const v_oth = PB ? v_s0 : v_s1;
-    f32x16 s[2], dp[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) s[kb] = s_init;
-#pragma unroll
-    for (int t = 0; t < KS; ++t)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(k_cur, kb, t), qf[t], s[kb], 0, 0, 0);
     if (e1 != kNoTile) request(e1, k_oth, v_oth);
+    // a partial tile in which none of this wave's 32 queries sees a key contributes exact zeros: skip it
+    if ((e0 >> 31) != 0 || __ballot(mw != 0ull) != 0ull) {
+      f32x16 s[2], dp[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) dp[kb] = dp_init;
+      for (int kb = 0; kb < 2; ++kb) s[kb] = s_init;
 #pragma unroll
-    for (int t = 0; t < KS; ++t)
+      for (int t = 0; t < KS; ++t)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(v_cur, kb, t), dof[t], dp[kb], 0, 0, 0);
+        for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(k_cur, kb, t), qf[t], s[kb], 0, 0, 0);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) dp[kb] = dp_init;
+#pragma unroll
+      for (int t = 0; t < KS; ++t)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(v_cur, kb, t), dof[t], dp[kb], 0, 0, 0);
 
-    // element mask where the list cannot rule out zeros: masked scores become -inf, i.e. probability 0
-    if ((e0 >> 31) == 0) {
+      // element mask where the list cannot rule out zeros: masked scores become -inf, i.e. probability 0
+      if ((e0 >> 31) == 0) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const uint32_t w = (uint32_t)(mw >> (32 * kb)) >> (4 * hh);
+        for (int kb = 0; kb < 2; ++kb) {
+          const uint32_t w = (uint32_t)(mw >> (32 * kb)) >> (4 * hh);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int bit = 8 * (e / 4) + (e % 4);
-          const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);
-          s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
+          for (int e = 0; e < 16; ++e) {
+            const int bit = 8 * (e / 4) + (e % 4);
+            const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);
+            s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
+          }
         }
       }
-    }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      bf16x8 dsf;
+      for (int u = 0; u < 4; ++u) {
+        bf16x8 dsf;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float p = __builtin_amdgcn_exp2f(s[u / 2][8 * (u % 2) + e]);
-        dsf[e] = (__bf16)(p * dp[u / 2][8 * (u % 2) + e]);
+        for (int e = 0; e < 8; ++e) {
+          const float p = __builtin_amdgcn_exp2f(s[u / 2][8 * (u % 2) + e]);
+          dsf[e] = (__bf16)(p * dp[u / 2][8 * (u % 2) + e]);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(k_cur, u, db), dsf, dq[db], 0, 0, 0);
       }
-#pragma unroll
-      for (int db = 0; db < DB; ++db) dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(k_cur, u, db), dsf, dq[db], 0, 0, 0);
     }
     e0 = e1;
     e1 = tiles_s[it + 2];
   };
 
-  for (int w0 = 0; w0 < n_list; w0 += kWin) {
-    const int count = min(kWin, n_list - w0);
-    for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
-    if (tid < 3) tiles_s[count + tid] = kNoTile;
-    __syncthreads();
-    e0 = tiles_s[0];
-    e1 = tiles_s[1];
-    request(e0, k_s0, v_s0);
-    for (int it = 0; it < count; it += 2) {
-      step(IntC<0>{}, it);
-      if (it + 1 < count) step(IntC<1>{}, it + 1);
+  // the tiles list[0 .. n_list), window by window
+  auto run_list = [&](const uint32_t* __restrict__ list, int n_list) {
+    for (int w0 = 0; w0 < n_list; w0 += kWin) {
+      const int count = min(kWin, n_list - w0);
+      for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
+      if (tid < 3) tiles_s[count + tid] = kNoTile;
+      __syncthreads();
+      e0 = tiles_s[0];
+      e1 = tiles_s[1];
+      request(e0, k_s0, v_s0);
+      for (int it = 0; it < count; it += 2) {
+        step(IntC<0>{}, it);
+        if (it + 1 < count) step(IntC<1>{}, it + 1);
+      }
+      __syncthreads();  // the next window rewrites the tile list and the buffers; the epilogue stages into them
     }
-    __syncthreads();  // the next window rewrites the tile list and the buffers; the epilogue stages into them
+  };
+
+  auto write_dq = [&]() {
+    __bf16* const stage = ((wave >> 1) == 0 ? k_s0 : (wave >> 1) == 1 ? k_s1 : (wave >> 1) == 2 ? v_s0 : v_s1) + (wave & 1) * 32 * D;
+    store_slab<D>(dq, P.scale, stage, P.dq + head_off, (int64_t)i * BR + wave * 32, N, lane);
+  };
+
+  // ---- which block row is this work-group's own: rank-major interleave of G (batch, head) planes, as in the forward
+  int own_bh, own_m, rank;
+  {
+    const int logical = logical_wg((int)blockIdx.x, P.total_wgs);
+    const int grp = logical / (P.G * P.nbr), within = logical - grp * (P.G * P.nbr);
+    const int g_planes = min(P.G, P.total_wgs / P.nbr - grp * P.G);
+    rank = within / g_planes;
+    own_bh = grp * P.G + (within - rank * g_planes);
+    own_m = (P.Mb == 1) ? 0 : own_bh / P.H;
+  }
+  int own_i, list_pos, n_list, nparts_all = 0, split_T = 0x7fffffff;
+  if (P.sched) {
+    const int2 hdr = *reinterpret_cast<const int2*>(P.sched);
+    const int4 rec = *reinterpret_cast<const int4*>(P.sched + bbm::sched_order_base(P.Mb, P.nbr) +
+                                                    bbm::kSchedRowInts * (int64_t)(own_m * P.nbr + rank));
+    nparts_all = hdr.x;
+    split_T = hdr.y;
+    own_i = rec.x;
+    list_pos = rec.y;
+    n_list = rec.z;
+  } else {
+    own_i = P.nbr - 1 - rank;
+    list_pos = P.row_ptr[(int64_t)own_m * (P.nbr + 1) + own_i];
+    n_list = P.row_ptr[(int64_t)own_m * (P.nbr + 1) + own_i + 1] - list_pos;
   }
 
-  __bf16* const stage = ((wave >> 1) == 0 ? k_s0 : (wave >> 1) == 1 ? k_s1 : (wave >> 1) == 2 ? v_s0 : v_s1) + (wave & 1) * 32 * D;
-  store_slab<D>(dq, P.scale, stage, P.dq + head_off, (int64_t)i * BR + wave * 32, N, lane);
+  // ---- the first n_extra work-groups serve the queue of cut-row parts (nothing to do when no row was cut)
+  if (nparts_all > 0 && (int)blockIdx.x < P.n_extra) {
+    const int32_t* __restrict__ S = P.sched;
+    const int n_items = nparts_all * P.hbp;
+    int item = blockIdx.x;  // the first item is the work-group's own index; later ones come from the counter
+    while (item < n_items) {
+      int next_item = 0;
+      if (tid == 0) next_item = P.n_extra + atomicAdd(P.row_queue, 1);
+      const int hb = item / nparts_all;
+      const int32_t* seg = S + bbm::kSchedPartBase + (int64_t)bbm::kSchedPartInts * (item - hb * nparts_all);
+      const int row = seg[0], p0 = seg[1], nt = seg[2], part = seg[3], nparts = seg[4], q_first = seg[5], rho = seg[6];
+      m = row / P.nbr;
+      i = row - m * P.nbr;
+      bh = (P.Mb == 1) ? hb : m * P.H + hb;
+      begin_item(false);
+      run_list(P.col_idx + (int64_t)m * P.nbr * P.nbc + p0, nt);
+      // park the partial sums; the last part of the row to arrive adds them all up in part order
+      float* rec = P.row_partials + ((int64_t)(q_first + part) * P.hbp + hb) * (REGS * NT) + tid;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        for (int e = 0; e < 16; ++e) rec[(db * 16 + e) * NT] = dq[db][e];
+      __threadfence();
+      __syncthreads();
+      if (tid == 0) item_s[1] = atomicAdd(P.row_queue + 8 + rho * P.hbp + hb, 1);
+      __syncthreads();
+      if (item_s[1] == nparts - 1) {
+        __threadfence();
+        const float* r0 = P.row_partials + ((int64_t)q_first * P.hbp + hb) * (REGS * NT) + tid;
+        const int64_t pstride = (int64_t)P.hbp * (REGS * NT);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          for (int e = 0; e < 16; ++e) dq[db][e] = 0.0f;
+        for (int k = 0; k < nparts; ++k) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+            for (int e = 0; e < 16; ++e) dq[db][e] += r0[k * pstride + (db * 16 + e) * NT];
+        }
+        write_dq();
+        if (tid == 0) P.row_queue[8 + rho * P.hbp + hb] = 0;  // last user of this counter: zero for the next call
+      }
+      if (tid == 0) item_s[0] = next_item;
+      __syncthreads();
+      item = item_s[0];
+      __syncthreads();
+    }
+    if (tid == 0 && atomicAdd(P.row_queue + 1, 1) == P.n_extra - 1) {  // the last leading work-group to leave
+      P.row_queue[0] = 0;
+      P.row_queue[1] = 0;
+    }
+  }
+
+  bh = own_bh;
+  m = own_m;
+  i = own_i;
+  begin_item(true);
+  if (n_list <= split_T) {  // a row the schedule cut belongs to the queue
+    run_list(P.col_idx + (int64_t)m * P.nbr * P.nbc + list_pos, n_list);
+    write_dq();
+  }
 }
 
 // ------------------------------------------------------------------------------------------------------------------
 // dK, dV
 // ------------------------------------------------------------------------------------------------------------------
+// One work-group (2 waves) per (block column, batch, head); the first P.n_extra work-groups first serve the queue of
+// the parts of cut block columns, as the dQ kernel does for cut block rows.
 template <int D>
 __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
   using L = TL<D>;
   constexpr int NW = 2, NT = 128;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
+  constexpr int REGS = DB * 16;
   static_assert(2 * 32 * D <= L::ELEMS, "two 32 x D output slabs must fit in a tile buffer");
 
   __shared__ __attribute__((aligned(16))) __bf16 q_s0[L::ELEMS];
@@ -367,7 +463,8 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
   __shared__ __attribute__((aligned(16))) float nd_s1[64];
   __shared__ __attribute__((aligned(16))) uint32_t mk_s0[2][64];  // [key half][query row of the sub-tile]
   __shared__ __attribute__((aligned(16))) uint32_t mk_s1[2][64];
-  __shared__ uint32_t tiles_s[kWin + 4];
+  __shared__ uint32_t tiles_s[kWin];
+  __shared__ int item_s[2];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // = key half of the column block
@@ -375,41 +472,43 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
   const int64_t N = P.N;
   const float c = P.scale * kLog2e;
 
-  const int logical = logical_wg((int)blockIdx.x, P.total_wgs);
-  const int bh = logical / P.nbc;
-  const int j = logical - bh * P.nbc;
-  const int m = (P.Mb == 1) ? 0 : bh / P.H;
-  const int list_pos = P.col_ptr[(int64_t)m * (P.nbc + 1) + j];
-  const int n_list = P.col_ptr[(int64_t)m * (P.nbc + 1) + j + 1] - list_pos;
-  const uint32_t* __restrict__ list = P.row_idx + (int64_t)m * P.nbr * P.nbc + list_pos;
-
-  const int64_t head_off = (int64_t)bh * N * D;
-  const __bf16* __restrict__ Qg = P.q + head_off;
-  const __bf16* __restrict__ Gg = P.d_o + head_off;
-  const float* __restrict__ nlg = P.nl2 + (int64_t)bh * N;
-  const float* __restrict__ ndg = P.ndelta + (int64_t)bh * N;
-  // this wave's 32-bit half of the packed mask words of block column j (one word per query row)
-  const uint32_t* __restrict__ mcol = reinterpret_cast<const uint32_t*>(P.packed + ((int64_t)m * P.W + j) * N) + wave;
-
-  // ---- this lane's key: K * scale * log2(e) and V as B operands (keys past N: zeros, never stored)
-  const int64_t krow = (int64_t)j * 64 + wave * 32 + lq;
-  const bool k_ok = krow < N;
+  // ---- per-item state
+  int bh, m, j;
+  int64_t head_off;
+  const __bf16* __restrict__ Qg;
+  const __bf16* __restrict__ Gg;
+  const float* __restrict__ nlg;
+  const float* __restrict__ ndg;
+  const uint32_t* __restrict__ mcol;
   bf16x8 kf[KS], vf[KS];
-#pragma unroll
-  for (int t = 0; t < KS; ++t) {
-    if (k_ok) {
-      const int64_t at = head_off + krow * D + 16 * t + 8 * hh;
-      kf[t] = *reinterpret_cast<const bf16x8*>(P.k + at);
-      vf[t] = *reinterpret_cast<const bf16x8*>(P.v + at);
-    } else {
-      for (int e = 0; e < 8; ++e) kf[t][e] = vf[t][e] = (__bf16)0.0f;
-    }
-    for (int e = 0; e < 8; ++e) kf[t][e] = (__bf16)((float)kf[t][e] * c);
-  }
   f32x16 dk[DB], dv[DB];
+
+  // this lane's key: K * scale * log2(e) and V as B operands (keys past N: zeros, never stored)
+  auto begin_item = [&]() {
+    head_off = (int64_t)bh * N * D;
+    Qg = P.q + head_off;
+    Gg = P.d_o + head_off;
+    nlg = P.nl2 + (int64_t)bh * N;
+    ndg = P.ndelta + (int64_t)bh * N;
+    // this wave's 32-bit half of the packed mask words of block column j (one word per query row)
+    mcol = reinterpret_cast<const uint32_t*>(P.packed + ((int64_t)m * P.W + j) * N) + wave;
+    const int64_t krow = (int64_t)j * 64 + wave * 32 + lq;
+    const bool k_ok = krow < N;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-    for (int e = 0; e < 16; ++e) dk[db][e] = dv[db][e] = 0.0f;
+    for (int t = 0; t < KS; ++t) {
+      if (k_ok) {
+        const int64_t at = head_off + krow * D + 16 * t + 8 * hh;
+        kf[t] = *reinterpret_cast<const bf16x8*>(P.k + at);
+        vf[t] = *reinterpret_cast<const bf16x8*>(P.v + at);
+      } else {
+        for (int e = 0; e < 8; ++e) kf[t][e] = vf[t][e] = (__bf16)0.0f;
+      }
+      for (int e = 0; e < 8; ++e) kf[t][e] = (__bf16)((float)kf[t][e] * c);
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      for (int e = 0; e < 16; ++e) dk[db][e] = dv[db][e] = 0.0f;
+  };
 
   TileAddr<D> A;
   A.init(lane);
@@ -458,6 +557,8 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
         request(e1, sub1, q_s1, g_s1, nl_s1, nd_s1, mk_s1);
     }
     const bool partial = (e0 >> 31) == 0;
+    // a partial sub-tile in which none of the 64 queries sees one of this wave's 32 keys contributes exact zeros
+    if (partial && __ballot(mk_cur[wave][lane] != 0u) == 0ull) return;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       f32x16 sc, dp;
@@ -505,32 +606,121 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
     }
   };
 
-  for (int w0 = 0; w0 < n_list; w0 += kWin) {
-    const int count = min(kWin, n_list - w0);
-    for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
-    __syncthreads();
-    n_steps = count << qs_shift;
-    request(tiles_s[0], 0, q_s0, g_s0, nl_s0, nd_s0, mk_s0);
-    for (int s = 0; s < n_steps; s += 2) {
-      step(IntC<0>{}, s);
-      if (s + 1 < n_steps) step(IntC<1>{}, s + 1);
+  // the query blocks list[0 .. n_list), window by window
+  auto run_list = [&](const uint32_t* __restrict__ list, int n_list) {
+    for (int w0 = 0; w0 < n_list; w0 += kWin) {
+      const int count = min(kWin, n_list - w0);
+      for (int t = tid; t < count; t += NT) tiles_s[t] = list[w0 + t];
+      __syncthreads();
+      n_steps = count << qs_shift;
+      request(tiles_s[0], 0, q_s0, g_s0, nl_s0, nd_s0, mk_s0);
+      for (int s = 0; s < n_steps; s += 2) {
+        step(IntC<0>{}, s);
+        if (s + 1 < n_steps) step(IntC<1>{}, s + 1);
+      }
+      __syncthreads();  // the next window rewrites the list and the buffers; the epilogue stages into them
     }
-    __syncthreads();  // the next window rewrites the list and the buffers; the epilogue stages into them
+  };
+
+  auto write_dkv = [&]() {
+    const int64_t row0 = (int64_t)j * 64 + wave * 32;
+    store_slab<D>(dk, P.scale, q_s0 + wave * 32 * D, P.dk + head_off, row0, N, lane);
+    store_slab<D>(dv, 1.0f, g_s0 + wave * 32 * D, P.dv + head_off, row0, N, lane);
+  };
+
+  int nparts_all = 0, split_T = 0x7fffffff;
+  if (P.csched) {
+    const int2 hdr = *reinterpret_cast<const int2*>(P.csched);
+    nparts_all = hdr.x;
+    split_T = hdr.y;
+  }
+  // ---- the first n_extra work-groups serve the queue of cut-column parts (nothing to do when no column was cut)
+  if (nparts_all > 0 && (int)blockIdx.x < P.n_extra) {
+    const int32_t* __restrict__ S = P.csched;
+    const int n_items = nparts_all * P.hbp;
+    int item = blockIdx.x;
+    while (item < n_items) {
+      int next_item = 0;
+      if (tid == 0) next_item = P.n_extra + atomicAdd(P.col_queue, 1);
+      const int hb = item / nparts_all;
+      const int32_t* seg = S + bbm::kSchedPartBase + (int64_t)bbm::kSchedPartInts * (item - hb * nparts_all);
+      const int col = seg[0], p0 = seg[1], nt = seg[2], part = seg[3], nparts = seg[4], q_first = seg[5], rho = seg[6];
+      m = col / P.nbc;
+      j = col - m * P.nbc;
+      bh = (P.Mb == 1) ? hb : m * P.H + hb;
+      begin_item();
+      run_list(P.row_idx + (int64_t)m * P.nbr * P.nbc + p0, nt);
+      float* rec = P.col_partials + ((int64_t)(q_first + part) * P.hbp + hb) * (2 * REGS * NT) + tid;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        for (int e = 0; e < 16; ++e) {
+          rec[(db * 16 + e) * NT] = dk[db][e];
+          rec[(REGS + db * 16 + e) * NT] = dv[db][e];
+        }
+      __threadfence();
+      __syncthreads();
+      if (tid == 0) item_s[1] = atomicAdd(P.col_queue + 8 + rho * P.hbp + hb, 1);
+      __syncthreads();
+      if (item_s[1] == nparts - 1) {
+        __threadfence();
+        const float* r0 = P.col_partials + ((int64_t)q_first * P.hbp + hb) * (2 * REGS * NT) + tid;
+        const int64_t pstride = (int64_t)P.hbp * (2 * REGS * NT);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          for (int e = 0; e < 16; ++e) dk[db][e] = dv[db][e] = 0.0f;
+        for (int k = 0; k < nparts; ++k) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+            for (int e = 0; e < 16; ++e) {
+              dk[db][e] += r0[k * pstride + (db * 16 + e) * NT];
+              dv[db][e] += r0[k * pstride + (REGS + db * 16 + e) * NT];
+            }
+        }
+        write_dkv();
+        if (tid == 0) P.col_queue[8 + rho * P.hbp + hb] = 0;
+      }
+      if (tid == 0) item_s[0] = next_item;
+      __syncthreads();
+      item = item_s[0];
+      __syncthreads();
+    }
+    if (tid == 0 && atomicAdd(P.col_queue + 1, 1) == P.n_extra - 1) {
+      P.col_queue[0] = 0;
+      P.col_queue[1] = 0;
+    }
   }
 
-  const int64_t row0 = (int64_t)j * 64 + wave * 32;
-  store_slab<D>(dk, P.scale, q_s0 + wave * 32 * D, P.dk + head_off, row0, N, lane);
-  store_slab<D>(dv, 1.0f, g_s0 + wave * 32 * D, P.dv + head_off, row0, N, lane);
+  {
+    const int logical = logical_wg((int)blockIdx.x, P.total_wgs);
+    bh = logical / P.nbc;
+    j = logical - bh * P.nbc;
+    m = (P.Mb == 1) ? 0 : bh / P.H;
+    const int list_pos = P.col_ptr[(int64_t)m * (P.nbc + 1) + j];
+    const int n_list = P.col_ptr[(int64_t)m * (P.nbc + 1) + j + 1] - list_pos;
+    if (n_list <= split_T) {  // a column the schedule cut belongs to the queue
+      begin_item();
+      run_list(P.row_idx + (int64_t)m * P.nbr * P.nbc + list_pos, n_list);
+      write_dkv();
+    }
+  }
 }
 
-inline size_t stats_bytes(int64_t B, int64_t H, int64_t N) {
-  const size_t n = (size_t)(B * H * N) * sizeof(float);
-  return (n + 255) / 256 * 256;
-}
+// Leading work-groups that serve a queue of parts before their own block row / column.
+constexpr int kExtraWGs = 256;
+
+inline size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+inline size_t stats_bytes(int64_t B, int64_t H, int64_t N) { return round256((size_t)(B * H * N) * sizeof(float)); }
+// counters of one queue: 8 + one per (cut row or column, (batch, head) of its plane); at most nb * B*H of those
+inline size_t queue_bytes(int64_t B, int64_t H, int64_t nb) { return round256((size_t)(8 + B * H * nb) * sizeof(int32_t)); }
+// at most Mb*nbr row parts and Mb*nbc column parts exist (the split thresholds are at least twice the mean length):
+// the partial results of all parts together are one fp32 copy of dQ, and of dK plus dV, each padded to whole blocks
+inline size_t row_partial_bytes(int64_t B, int64_t H, int64_t nbr, int Br, int d) { return (size_t)(B * H * nbr) * Br * d * sizeof(float); }
+inline size_t col_partial_bytes(int64_t B, int64_t H, int64_t nbc, int d) { return (size_t)(B * H * nbc) * 2 * 64 * d * sizeof(float); }
 
 template <int D>
 int launch_bwd(BwdParams& P, int64_t B, int64_t H, hipStream_t s) {
   P.total_wgs = (int32_t)(B * H * P.nbr);
+  P.n_extra = std::min<int32_t>(P.total_wgs, kExtraWGs);
   P.G = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, (B * H * P.nbr / 8) / P.nbr));
   if (P.br == 64)
     attn_bwd_dq_kernel<D, 2><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
@@ -541,17 +731,19 @@ int launch_bwd(BwdParams& P, int64_t B, int64_t H, hipStream_t s) {
   int rc = bbm::launch_status("bbm_attn_bwd (dq)");
   if (rc != BBM_OK) return rc;
   P.total_wgs = (int32_t)(B * H * P.nbc);
+  P.n_extra = std::min<int32_t>(P.total_wgs, kExtraWGs);
   attn_bwd_dkv_kernel<D><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
   return bbm::launch_status("bbm_attn_bwd (dk, dv)");
 }
 
 }  // namespace
 
-extern "C" __attribute__((visibility("default"))) size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N) {
-  if (B < 1 || H < 1 || N < 1) return 0;
-  return 2 * stats_bytes(B, H, N);
+extern "C" __attribute__((visibility("default"))) size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int Br) {
+  if (B < 1 || H < 1 || N < 1 || (d != 64 && d != 128) || (Br != 64 && Br != 128 && Br != 256)) return 0;
+  const int64_t nbr = (N + Br - 1) / Br, nbc = (N + 63) / 64;
+  return queue_bytes(B, H, nbr) + queue_bytes(B, H, nbc) + 2 * stats_bytes(B, H, N) + round256(row_partial_bytes(B, H, nbr, Br, d)) +
+         col_partial_bytes(B, H, nbc, d);
 }
-
 extern "C" __attribute__((visibility("default"))) int bbm_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                                                                    const float* lse, void* dq, void* dk, void* dv, int64_t B, int64_t H,
                                                                    int64_t N, int d, float softmax_scale, int64_t Mb,
@@ -581,7 +773,7 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_bwd(const void* q
     return fail(BBM_EINVAL, "bbm_attn_bwd: the index needs row_ptr, col_idx (block list) and col_ptr, row_idx (column list)");
   if (nbr * nbc >= (1ll << 31) || B * H * nbr >= (1ll << 31) || B * H * nbc >= (1ll << 31) || N >= (1ll << 31))
     return fail(BBM_EUNSUPPORTED, "bbm_attn_bwd: problem too large for 32-bit tile counters");
-  const size_t need = bbm_attn_bwd_workspace_bytes(B, H, N);
+  const size_t need = bbm_attn_bwd_workspace_bytes(B, H, N, d, idx->Br);
   if (!workspace || workspace_bytes < need)
     return fail(BBM_EWORKSPACE, "bbm_attn_bwd: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
   if (!aligned(workspace, 16)) return fail(BBM_EINVAL, "bbm_attn_bwd: workspace must be 16-byte aligned");
@@ -596,8 +788,22 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_bwd(const void* q
   P.dq = static_cast<__bf16*>(dq);
   P.dk = static_cast<__bf16*>(dk);
   P.dv = static_cast<__bf16*>(dv);
-  P.nl2 = static_cast<float*>(workspace);
-  P.ndelta = reinterpret_cast<float*>(static_cast<char*>(workspace) + stats_bytes(B, H, N));
+  // workspace: the two counter arrays first (they are what must be zero between calls), then statistics and partials
+  char* ws = static_cast<char*>(workspace);
+  P.row_queue = reinterpret_cast<int32_t*>(ws);
+  ws += queue_bytes(B, H, nbr);
+  P.col_queue = reinterpret_cast<int32_t*>(ws);
+  ws += queue_bytes(B, H, nbc);
+  P.nl2 = reinterpret_cast<float*>(ws);
+  ws += stats_bytes(B, H, N);
+  P.ndelta = reinterpret_cast<float*>(ws);
+  ws += stats_bytes(B, H, N);
+  P.row_partials = reinterpret_cast<float*>(ws);
+  ws += round256(row_partial_bytes(B, H, nbr, idx->Br, d));
+  P.col_partials = reinterpret_cast<float*>(ws);
+  P.csched = idx->col_sched;
+  P.hbp = (int32_t)(Mb == 1 ? B * H : H);
+  P.n_extra = 0;
   P.packed = packed_mask;
   P.row_ptr = idx->row_ptr;
   P.col_idx = idx->col_idx;

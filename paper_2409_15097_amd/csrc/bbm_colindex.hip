@@ -55,17 +55,125 @@ __global__ __launch_bounds__(kColThreads) void col_index_kernel(const uint8_t* _
   if (tid == 0) cp[nbc] = base;
 }
 
+// Split schedule of the column walk: columns with more than T = max(kColSchedMinSplit, 2 * mean entries per non-empty
+// column) list entries are cut into ceil(n/T) near-equal parts; one work-group scans all Mb*nbc columns.
+constexpr int kColSchedThreads = 256;
+
+__device__ __forceinline__ int wave_incl_scan(int x, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int up = __shfl_up(x, d);
+    if (lane >= d) x += up;
+  }
+  return x;
+}
+
+__global__ __launch_bounds__(kColSchedThreads) void col_sched_kernel(const int32_t* __restrict__ col_ptr,
+                                                                    const uint32_t* __restrict__ row_idx, int Mb, int nbr, int nbc,
+                                                                    int32_t* __restrict__ sched) {
+  constexpr int NWV = kColSchedThreads / 64;
+  __shared__ long long tot_s[NWV];
+  __shared__ int ne_s[NWV];
+  __shared__ int np_s[NWV], cut_s[NWV];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int C = Mb * nbc;
+  auto count_of = [&](int c) {
+    const int m = c / nbc, j = c - m * nbc;
+    const int32_t* p = col_ptr + (int64_t)m * (nbc + 1) + j;
+    return p[1] - p[0];
+  };
+  long long total = 0;
+  int nonempty = 0;
+  for (int c = tid; c < C; c += kColSchedThreads) {
+    const int n = count_of(c);
+    total += n;
+    nonempty += n > 0 ? 1 : 0;
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    total += __shfl_xor(total, d);
+    nonempty += __shfl_xor(nonempty, d);
+  }
+  if (lane == 0) {
+    tot_s[wave] = total;
+    ne_s[wave] = nonempty;
+  }
+  __syncthreads();
+  total = 0;
+  nonempty = 0;
+  for (int w = 0; w < NWV; ++w) {
+    total += tot_s[w];
+    nonempty += ne_s[w];
+  }
+  const int mean = nonempty > 0 ? (int)((total + nonempty - 1) / nonempty) : 0;
+  const int T = max(bbm::kColSchedMinSplit, 2 * mean);
+  int qbase = 0, rbase = 0;
+  for (int c0 = 0; c0 < C; c0 += kColSchedThreads) {
+    const int c = c0 + tid;
+    const int n = c < C ? count_of(c) : 0;
+    const int np = n > T ? (n + T - 1) / T : 0;
+    const int cut = np > 0 ? 1 : 0;
+    const int inp = wave_incl_scan(np, lane), icut = wave_incl_scan(cut, lane);
+    __syncthreads();  // the previous chunk's totals have been read
+    if (lane == 63) {
+      np_s[wave] = inp;
+      cut_s[wave] = icut;
+    }
+    __syncthreads();
+    int q = qbase + inp - np, rho = rbase + icut - cut, chunk_np = 0, chunk_cut = 0;
+    for (int w = 0; w < NWV; ++w) {
+      if (w < wave) {
+        q += np_s[w];
+        rho += cut_s[w];
+      }
+      chunk_np += np_s[w];
+      chunk_cut += cut_s[w];
+    }
+    if (np > 0) {
+      const int m = c / nbc, j = c - m * nbc;
+      const int first0 = col_ptr[(int64_t)m * (nbc + 1) + j];
+      const int chunk = (n + np - 1) / np;
+      for (int k = 0; k < np; ++k) {
+        int32_t* rec = sched + bbm::kSchedPartBase + (int64_t)bbm::kSchedPartInts * (q + k);
+        const int first = first0 + k * chunk;
+        rec[0] = c;
+        rec[1] = first;
+        rec[2] = min(chunk, n - k * chunk);
+        rec[3] = k;
+        rec[4] = np;
+        rec[5] = q;
+        rec[6] = rho;
+        rec[7] = (int32_t)row_idx[(int64_t)m * nbr * nbc + first];
+      }
+    }
+    qbase += chunk_np;
+    rbase += chunk_cut;
+  }
+  if (tid < bbm::kSchedPartBase) sched[tid] = tid == bbm::kSchedNParts ? qbase : tid == bbm::kSchedSplitT ? T : tid == bbm::kSchedNCutRows ? rbase : 0;
+}
+
 }  // namespace
 
+extern "C" __attribute__((visibility("default"))) size_t bbm_col_sched_bytes(int64_t Mb, int64_t nbc) {
+  if (Mb < 1 || nbc < 1) return 0;
+  return (size_t)(bbm::kSchedPartBase + bbm::kSchedPartInts * Mb * nbc) * sizeof(int32_t);
+}
+
 extern "C" __attribute__((visibility("default"))) int bbm_build_col_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc,
-                                                                         int32_t* col_ptr, uint32_t* row_idx, void* stream) {
+                                                                         int32_t* col_ptr, uint32_t* row_idx, int32_t* col_sched,
+                                                                         void* stream) {
   using namespace bbm;
   clear_error();
   if (!blk_class || !col_ptr || !row_idx) return fail(BBM_EINVAL, "bbm_build_col_index: blk_class, col_ptr, row_idx must not be NULL");
   if (Mb < 1 || nbr < 1 || nbc < 1)
     return fail(BBM_EINVAL, "bbm_build_col_index: Mb=%lld, nbr=%lld, nbc=%lld must be >= 1", (long long)Mb, (long long)nbr, (long long)nbc);
   if (!aligned(col_ptr, 4) || !aligned(row_idx, 4)) return fail(BBM_EINVAL, "bbm_build_col_index: col_ptr, row_idx must be 4-byte aligned");
+  if (col_sched && !aligned(col_sched, 32)) return fail(BBM_EINVAL, "bbm_build_col_index: col_sched must be 32-byte aligned");
+  if (col_sched && Mb * nbc >= (1ll << 24)) return fail(BBM_EINVAL, "bbm_build_col_index: Mb*nbc must be below 2^24 for a schedule");
   if (nbr * nbc >= (1ll << 31) || Mb >= (1ll << 31)) return fail(BBM_EINVAL, "bbm_build_col_index: nbr*nbc and Mb must be below 2^31");
   col_index_kernel<<<(unsigned)Mb, kColThreads, 0, static_cast<hipStream_t>(stream)>>>(blk_class, (int)nbr, (int)nbc, col_ptr, row_idx);
-  return launch_status("bbm_build_col_index");
+  int rc = launch_status("bbm_build_col_index");
+  if (rc != BBM_OK || !col_sched) return rc;
+  col_sched_kernel<<<1, kColSchedThreads, 0, static_cast<hipStream_t>(stream)>>>(col_ptr, row_idx, (int)Mb, (int)nbr, (int)nbc, col_sched);
+  return launch_status("bbm_build_col_index (schedule)");
 }

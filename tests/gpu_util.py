@@ -23,6 +23,7 @@ def index_to_numpy(idx):
     out["col_idx"] = None if idx.col_idx is None else idx.col_idx.cpu().numpy().view(np.uint32)
     out["row_idx"] = None if idx.row_idx is None else idx.row_idx.cpu().numpy().view(np.uint32)
     out["sched"] = None if idx.sched is None else idx.sched.cpu().numpy()
+    out["col_sched"] = None if idx.col_sched is None else idx.col_sched.cpu().numpy()
     out["packed_mask"] = None if idx.packed_mask is None else idx.packed_mask.cpu().numpy().view(np.uint64)
     return out
 
@@ -55,6 +56,9 @@ def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
             n = int(want["col_ptr"][m, -1])
             lo = m * nbr * nbc
             assert np.array_equal(got["row_idx"][lo:lo + n], want["row_idx"][lo:lo + n])
+    if got.get("col_sched") is not None:
+        n = oracle.blocks.SCHED_PART_BASE + oracle.blocks.SCHED_PART_INTS * int(want["col_sched"][0])
+        assert got["col_sched"].size == want["col_sched"].size and np.array_equal(got["col_sched"][:n], want["col_sched"][:n])
     if got["packed_mask"] is not None:
         assert np.array_equal(got["packed_mask"], oracle.packed_bits(mask))
 

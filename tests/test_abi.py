@@ -21,7 +21,8 @@ def test_every_declared_symbol_is_exported(bbm):
     names = set(re.findall(r"\b(bbm_[a-z_]+)\s*\(", hdr))
     assert names == {"bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs",
                      "bbm_build_sparse_index", "bbm_build_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes",
-                     "bbm_attn_fwd", "bbm_build_col_index", "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd"}
+                     "bbm_attn_fwd", "bbm_build_col_index", "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes",
+                     "bbm_attn_bwd"}
     raw = C.CDLL(bbm.library_path())
     for n in names:
         assert getattr(raw, n) is not None
@@ -32,7 +33,7 @@ def test_binding_has_the_same_names(bbm):
     for n in ("bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs", "bbm_build_sparse_index",
               "bbm_build_index",
               "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd", "bbm_build_col_index",
-              "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd"):
+              "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd"):
         assert callable(getattr(bbm, n))
 
 
@@ -72,7 +73,7 @@ def test_index_builders_reject_bad_arguments(bbm):
 
 def _idx(bbm, Br=128, Bc=64, Mb=1, N=256, **ptrs):
     from paper_2409_15097_amd.binding import _CIndex
-    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), *([None] * 12))
+    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), *([None] * 13))
     for k, v in ptrs.items():
         setattr(s, k, v)
     return s
@@ -118,18 +119,22 @@ def test_workspace_query_and_check(bbm):
 
 
 def _bwd(bbm, idx, q=FAKE, do=FAKE, lse=FAKE, dk=FAKE, B=1, H=1, N=256, d=64, scale=0.125, Mb=1, packed=FAKE, ws=FAKE,
-         ws_bytes=1 << 20):
+         ws_bytes=1 << 30):
     return bbm.lib.bbm_attn_bwd(q, FAKE, FAKE, FAKE, do, lse, FAKE, dk, FAKE, B, H, N, d, scale, Mb, packed,
                                 C.byref(idx) if idx else None, ws, ws_bytes, None)
 
 
 def test_attn_bwd_and_col_index_reject_bad_arguments(bbm):
     L = bbm.lib
-    assert L.bbm_build_col_index(None, 1, 4, 4, FAKE, FAKE, None) == bbm.BBM_EINVAL
-    assert L.bbm_build_col_index(FAKE, 1, 4, 4, None, FAKE, None) == bbm.BBM_EINVAL
-    assert L.bbm_build_col_index(FAKE, 1, 4, 0, FAKE, FAKE, None) == bbm.BBM_EINVAL
-    assert L.bbm_build_col_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None) == bbm.BBM_EINVAL
-    assert bbm.bbm_attn_bwd_workspace_bytes(2, 3, 100) >= 2 * 4 * 600 and bbm.bbm_attn_bwd_workspace_bytes(0, 3, 100) == 0
+    assert L.bbm_build_col_index(None, 1, 4, 4, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_col_index(FAKE, 1, 4, 4, None, FAKE, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_col_index(FAKE, 1, 4, 0, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_col_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_col_index(FAKE, 1, 4, 4, FAKE, FAKE, C.c_void_p(0x1004), None) == bbm.BBM_EINVAL
+    assert bbm.bbm_col_sched_bytes(2, 5) == 4 * (8 + 8 * 10) and bbm.bbm_col_sched_bytes(0, 5) == 0
+    need = bbm.bbm_attn_bwd_workspace_bytes(2, 3, 100, 64, 128)
+    assert need >= 2 * 4 * 600 + 3 * 4 * 600 * 64 and bbm.bbm_attn_bwd_workspace_bytes(0, 3, 100, 64, 128) == 0
+    assert bbm.bbm_attn_bwd_workspace_bytes(2, 3, 100, 96, 128) == 0 and bbm.bbm_attn_bwd_workspace_bytes(2, 3, 100, 64, 32) == 0
     full = _idx(bbm, row_ptr=0x2000, col_idx=0x3000, col_ptr=0x4000, row_idx=0x5000)
     assert _bwd(bbm, full, q=None) == bbm.BBM_EINVAL
     assert _bwd(bbm, full, lse=None) == bbm.BBM_EINVAL

@@ -272,3 +272,34 @@ def test_schedule_parts_tile_each_cut_row_exactly():
     assert np.array_equal(covered[cut], counts[cut]) and not covered[~cut].any()
     assert ncut == int(cut.sum()) and nparts <= counts.size          # the bound the workspace size relies on
     assert sorted(set(parts[:, 6].tolist())) == list(range(ncut))
+
+
+def test_column_schedule_hand_example_and_tiling():
+    # columns with 3, 0, 40, 5 entries: mean of non-empty = 16 -> T = 32 -> the 40-entry column is cut into 2 x 20
+    cp = np.array([[0, 3, 3, 43, 48]], dtype=np.int32)
+    s = oracle.column_schedule(cp, _fake_lists(cp, 512))
+    assert (s[0], s[1], s[2]) == (2, 32, 1) and not s[3:8].any() and s.size == 8 + 8 * 4
+    assert s[8:24].reshape(2, 8).tolist() == [[2, 3, 20, 0, 2, 0, 0, 3 - 2**31], [2, 23, 20, 1, 2, 0, 0, 23 - 2**31]]
+    # the floor of the threshold is 16 here: columns of 1, 1, 1, 20 -> mean 6 -> T = 16 -> 20 is cut into 2 x 10
+    cp2 = np.array([[0, 1, 2, 3, 23]], dtype=np.int32)
+    s2 = oracle.column_schedule(cp2, _fake_lists(cp2, 64))
+    assert s2[:3].tolist() == [2, 16, 1] and s2[8:24].reshape(2, 8)[:, :5].tolist() == [[3, 3, 10, 0, 2], [3, 13, 10, 1, 2]]
+    rng = np.random.default_rng(1)
+    counts = rng.integers(0, 200, size=(2, 29))
+    counts[rng.random(counts.shape) < 0.7] //= 25
+    cp3 = np.zeros((2, 30), dtype=np.int32)
+    cp3[:, 1:] = np.cumsum(counts, axis=1)
+    lists = _fake_lists(cp3, 29 * 200)
+    s3 = oracle.column_schedule(cp3, lists)
+    nparts, T, ncut = int(s3[0]), int(s3[1]), int(s3[2])
+    assert T == max(16, 2 * -(-int(counts.sum()) // int((counts > 0).sum())))
+    covered = np.zeros(counts.shape, dtype=np.int64)
+    for q, (c, first, nt, k, np_, qf, rho, e_first) in enumerate(s3[8:8 + 8 * nparts].reshape(nparts, 8)):
+        m, j = divmod(int(c), 29)
+        assert (int(e_first) & 0xffffffff) == int(lists.reshape(2, -1)[m, first])
+        assert counts[m, j] > T and np_ == -(-counts[m, j] // T) and 1 <= nt <= T and q == qf + k
+        assert first == cp3[m, j] + covered[m, j]
+        covered[m, j] += nt
+    cut = counts > T
+    assert np.array_equal(covered[cut], counts[cut]) and not covered[~cut].any()
+    assert ncut == int(cut.sum()) and nparts <= counts.size
