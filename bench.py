@@ -49,9 +49,9 @@ def parse():
                     help="comma list of extra workloads measured the same way and reported under per_mask, or 'all' "
                          "(C3,C4,C5,C0d,C0c,C0d128,C0c128); default: the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--backward", action="store_true",
-                    help="also time the backward pass (column list + dQ and dK/dV kernels) per mask; reported beside the "
-                         "forward figures, the headline value stays the forward step")
+    ap.add_argument("--no-backward", action="store_true",
+                    help="skip the backward pass (column list + dQ and dK/dV kernels), which is otherwise timed per mask and "
+                         "reported beside the forward figures; the headline value is the forward step either way")
     ap.add_argument("--only-kernel", default="", help="profile helper: run only 'attn', 'bwd', 'preprocess' or 'copy' (256 MiB device copy) launches")
     return ap.parse_args()
 
@@ -221,11 +221,11 @@ def main():
         torch.cuda.synchronize()
         return 0
 
-    main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch, a.backward)
+    main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch, not a.no_backward)
     rows = [main_res]
     extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128" if a.masks == "all" else a.masks
     for name in [m for m in extra.split(",") if m and m != a.workload]:
-        r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch, a.backward)
+        r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch, not a.no_backward)
         rows.append(r)
 
     flops = main_res["visited_tflop"] * 1e12
@@ -249,6 +249,15 @@ def main():
                      "hbm_frac_of_algo_bytes": main_res["attn_algo_bytes"] / (main_res["attn_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "per_mask": rows,
     }
+    if not a.no_backward:
+        # the next step of the path: backward pass over the same block index.  Algorithmic work: 5 products per visited
+        # tile (S, dP, dV, dK, dQ) = 2.5 x the forward; the two-kernel split executes 7 (S and dP twice).
+        out["backward"] = {
+            "bwd_ms": main_res["bwd_ms"], "col_index_ms": main_res["col_index_ms"], "fwd_bwd_ms": main_res["fwd_bwd_ms"],
+            "roofline": {"bound": "mfma", "kernel": "attn_bwd_dq_kernel + attn_bwd_dkv_kernel",
+                         "achieved": main_res["bwd_tflops_visited"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": main_res["bwd_mfma_frac"], "executed_tflops": main_res["bwd_executed_tflops"],
+                         "traffic": profiled_traffic_bytes("attn_bwd_kernels", a.workload)}}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(main_cfg, a.Br)
     print(json.dumps(out))
