@@ -220,7 +220,11 @@ int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* ls
  *                    bbm_build_sparse_index's schedule: [0] parts, [1] T, [2] cut columns, [3..7] 0, then 8 ints per
  *                    part ordered by (column, part): plane*nbc + block column, first entry (position in the plane's
  *                    list), entries, part, parts of the column, number of the column's first part, index of the column
- *                    among the cut columns, the list entry at the part's first position.  (No launch-order records.)
+ *                    among the cut columns, the list entry at the part's first position.  The last 4*Mb*nbc ints are one
+ *                    4-int record per (plane, rank) in the order in which the dK/dV step starts the block columns of a
+ *                    plane: by list length, longest first (ties: the higher column first; planes with more than 4096
+ *                    block columns: simply last column first); a record holds the block column, the position of its
+ *                    first entry in the plane's list, its number of entries and its first list entry (-1 if none).
  * Requires nbr*nbc < 2^31, and Mb*nbc < 2^24 if col_sched is given.  Errors: BBM_EINVAL, BBM_EHIP.
  */
 int bbm_build_col_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* col_ptr,

@@ -190,23 +190,38 @@ COL_SCHED_MIN_SPLIT = 16
 
 
 def column_schedule(col_ptr, row_idx):
-    """Split schedule of the backward pass's column walk (this build's own layout, stated in the library header).
+    """Split schedule and launch order of the backward pass's column walk (this build's own layout, stated in the
+    library header).
 
     col_ptr int32 [Mb, nbc+1], row_idx uint32 [Mb*nbr*nbc] (as column_index returns them) -> int32 array of
-    8 + 8*Mb*nbc entries: [0] parts, [1] split threshold T = max(16, 2*ceil(mean list length of the non-empty
+    8 + 12*Mb*nbc entries: [0] parts, [1] split threshold T = max(16, 2*ceil(mean list length of the non-empty
     columns)), [2] cut columns, [3..7] 0, then 8 ints per part in (column, part) order: column (= plane*nbc + block
     column), first entry (position in the plane's list), entries, part, parts of the column, number of the column's
     first part, index of the column among the cut columns, the list entry at the part's first position (as int32).
     A column with n > T entries is cut into ceil(n/T) parts of ceil(n/parts) entries (the last part takes the rest);
-    columns with n <= T are not listed.  Table entries past the last part are unspecified."""
+    columns with n <= T are not listed.  Table entries past the last part are unspecified.  The last 4*Mb*nbc entries
+    are one record of 4 ints per (plane, rank) in the order in which the block columns of a plane are started: by list
+    length, longest first (ties: the higher column first); planes of more than 4096 block columns are listed from the
+    last column to the first instead.  A record holds the block column, the position of its first list entry in the
+    plane's list, its number of entries, and its first list entry (-1 if it has none)."""
     Mb, nbc1 = col_ptr.shape
     nbc = nbc1 - 1
     counts = [int(col_ptr[m, j + 1] - col_ptr[m, j]) for m in range(Mb) for j in range(nbc)]
     nonempty = sum(1 for c in counts if c > 0)
     mean = -(-sum(counts) // nonempty) if nonempty else 0
     T = max(COL_SCHED_MIN_SPLIT, 2 * mean)
-    out = np.zeros(SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbc, dtype=np.int32)
+    order_base = SCHED_PART_BASE + SCHED_PART_INTS * Mb * nbc
+    out = np.zeros(order_base + SCHED_ROW_INTS * Mb * nbc, dtype=np.int32)
     lists = np.asarray(row_idx, dtype=np.uint32).reshape(Mb, -1)
+    entry = lambda m, pos: int(lists[m, pos].astype(np.int32))
+    for m in range(Mb):
+        cols = list(range(nbc - 1, -1, -1))
+        if nbc <= SCHED_MAX_SORT_ROWS:
+            cols.sort(key=lambda j: -counts[m * nbc + j])           # stable: equal lengths keep the higher column first
+        for rank, j in enumerate(cols):
+            o = order_base + SCHED_ROW_INTS * (m * nbc + rank)
+            c = counts[m * nbc + j]
+            out[o:o + 4] = (j, int(col_ptr[m, j]), c, entry(m, int(col_ptr[m, j])) if c > 0 else -1)
     q, rho = 0, 0
     for col, c in enumerate(counts):
         if c <= T:
@@ -217,7 +232,7 @@ def column_schedule(col_ptr, row_idx):
         for k in range(parts):
             first = int(col_ptr[m, col % nbc]) + k * chunk
             o = SCHED_PART_BASE + SCHED_PART_INTS * (q + k)
-            out[o:o + 8] = (col, first, min(chunk, c - k * chunk), k, parts, q, rho, int(lists[m, first].astype(np.int32)))
+            out[o:o + 8] = (col, first, min(chunk, c - k * chunk), k, parts, q, rho, entry(m, first))
         q += parts
         rho += 1
     out[0], out[1], out[2] = q, T, rho

@@ -50,7 +50,7 @@ struct BwdParams {
   int64_t N;
   int32_t H, Mb, nbr, nbc, W;
   int32_t total_wgs;
-  int32_t G;
+  int32_t G, Gc;    // (batch, head) planes whose block rows / block columns are interleaved in launch order
   int32_t br;       // query rows per block row
   float scale;
   // Cut block rows (dQ) and cut block columns (dK, dV): the split schedules (read-only), and in the caller's workspace
@@ -691,12 +691,28 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
   }
 
   {
+    // which block column is this work-group's own: rank-major interleave of G (batch, head) planes as in the dQ kernel,
+    // ranks by list length (longest first) from the schedule's records
     const int logical = logical_wg((int)blockIdx.x, P.total_wgs);
-    bh = logical / P.nbc;
-    j = logical - bh * P.nbc;
-    m = (P.Mb == 1) ? 0 : bh / P.H;
-    const int list_pos = P.col_ptr[(int64_t)m * (P.nbc + 1) + j];
-    const int n_list = P.col_ptr[(int64_t)m * (P.nbc + 1) + j + 1] - list_pos;
+    int list_pos, n_list;
+    if (P.csched) {
+      const int grp = logical / (P.Gc * P.nbc), within = logical - grp * (P.Gc * P.nbc);
+      const int g_planes = min(P.Gc, P.total_wgs / P.nbc - grp * P.Gc);
+      const int rank = within / g_planes;
+      bh = grp * P.Gc + (within - rank * g_planes);
+      m = (P.Mb == 1) ? 0 : bh / P.H;
+      const int4 rec = *reinterpret_cast<const int4*>(P.csched + bbm::kSchedPartBase + (int64_t)bbm::kSchedPartInts * P.Mb * P.nbc +
+                                                      bbm::kSchedRowInts * (int64_t)(m * P.nbc + rank));
+      j = rec.x;
+      list_pos = rec.y;
+      n_list = rec.z;
+    } else {
+      bh = logical / P.nbc;
+      j = logical - bh * P.nbc;
+      m = (P.Mb == 1) ? 0 : bh / P.H;
+      list_pos = P.col_ptr[(int64_t)m * (P.nbc + 1) + j];
+      n_list = P.col_ptr[(int64_t)m * (P.nbc + 1) + j + 1] - list_pos;
+    }
     if (n_list <= split_T) {  // a column the schedule cut belongs to the queue
       begin_item();
       run_list(P.row_idx + (int64_t)m * P.nbr * P.nbc + list_pos, n_list);
@@ -732,6 +748,7 @@ int launch_bwd(BwdParams& P, int64_t B, int64_t H, hipStream_t s) {
   if (rc != BBM_OK) return rc;
   P.total_wgs = (int32_t)(B * H * P.nbc);
   P.n_extra = std::min<int32_t>(P.total_wgs, kExtraWGs);
+  P.Gc = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, (B * H * P.nbc / 8) / P.nbc));
   attn_bwd_dkv_kernel<D><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
   return bbm::launch_status("bbm_attn_bwd (dk, dv)");
 }

@@ -56,7 +56,9 @@ __global__ __launch_bounds__(kColThreads) void col_index_kernel(const uint8_t* _
 }
 
 // Split schedule of the column walk: columns with more than T = max(kColSchedMinSplit, 2 * mean entries per non-empty
-// column) list entries are cut into ceil(n/T) near-equal parts; one work-group scans all Mb*nbc columns.
+// column) list entries are cut into ceil(n/T) near-equal parts; work-group 0 scans all Mb*nbc columns for that.
+// Work-group 1 + m writes the launch-order records of plane m: columns by list length, longest first (ties: the
+// higher column first), each with what a work-group needs to start (column, list position, entries, first entry).
 constexpr int kColSchedThreads = 256;
 
 __device__ __forceinline__ int wave_incl_scan(int x, int lane) {
@@ -75,8 +77,37 @@ __global__ __launch_bounds__(kColSchedThreads) void col_sched_kernel(const int32
   __shared__ long long tot_s[NWV];
   __shared__ int ne_s[NWV];
   __shared__ int np_s[NWV], cut_s[NWV];
+  __shared__ int len_s[bbm::kSchedMaxSortRows];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int C = Mb * nbc;
+  if (blockIdx.x > 0) {
+    const int m = blockIdx.x - 1;
+    int32_t* __restrict__ ord = sched + bbm::kSchedPartBase + (int64_t)bbm::kSchedPartInts * C + (int64_t)bbm::kSchedRowInts * m * nbc;
+    const int32_t* __restrict__ cp = col_ptr + (int64_t)m * (nbc + 1);
+    const uint32_t* __restrict__ lst = row_idx + (int64_t)m * nbr * nbc;
+    const bool sorted = nbc <= bbm::kSchedMaxSortRows;
+    if (sorted) {
+      for (int j = tid; j < nbc; j += kColSchedThreads) len_s[j] = cp[j + 1] - cp[j];
+      __syncthreads();
+    }
+    for (int j = tid; j < nbc; j += kColSchedThreads) {
+      const int pos = cp[j], n = cp[j + 1] - pos;
+      int rank = nbc - 1 - j;
+      if (sorted) {
+        rank = 0;
+        for (int x = 0; x < nbc; ++x) {
+          const int lx = len_s[x];
+          rank += (lx > n || (lx == n && x > j)) ? 1 : 0;
+        }
+      }
+      int32_t* rec = ord + bbm::kSchedRowInts * rank;
+      rec[0] = j;
+      rec[1] = pos;
+      rec[2] = n;
+      rec[3] = n > 0 ? (int32_t)lst[pos] : -1;
+    }
+    return;
+  }
   auto count_of = [&](int c) {
     const int m = c / nbc, j = c - m * nbc;
     const int32_t* p = col_ptr + (int64_t)m * (nbc + 1) + j;
@@ -156,7 +187,7 @@ __global__ __launch_bounds__(kColSchedThreads) void col_sched_kernel(const int32
 
 extern "C" __attribute__((visibility("default"))) size_t bbm_col_sched_bytes(int64_t Mb, int64_t nbc) {
   if (Mb < 1 || nbc < 1) return 0;
-  return (size_t)(bbm::kSchedPartBase + bbm::kSchedPartInts * Mb * nbc) * sizeof(int32_t);
+  return (size_t)(bbm::kSchedPartBase + (bbm::kSchedPartInts + bbm::kSchedRowInts) * Mb * nbc) * sizeof(int32_t);
 }
 
 extern "C" __attribute__((visibility("default"))) int bbm_build_col_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc,
@@ -174,6 +205,6 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_col_index(const 
   col_index_kernel<<<(unsigned)Mb, kColThreads, 0, static_cast<hipStream_t>(stream)>>>(blk_class, (int)nbr, (int)nbc, col_ptr, row_idx);
   int rc = launch_status("bbm_build_col_index");
   if (rc != BBM_OK || !col_sched) return rc;
-  col_sched_kernel<<<1, kColSchedThreads, 0, static_cast<hipStream_t>(stream)>>>(col_ptr, row_idx, (int)Mb, (int)nbr, (int)nbc, col_sched);
+  col_sched_kernel<<<(unsigned)(1 + Mb), kColSchedThreads, 0, static_cast<hipStream_t>(stream)>>>(col_ptr, row_idx, (int)Mb, (int)nbr, (int)nbc, col_sched);
   return launch_status("bbm_build_col_index (schedule)");
 }

@@ -44,7 +44,8 @@ constexpr int kSchedMaxSortRows = 4096;
 constexpr int kSchedRowInts = 4;
 constexpr int kSchedGroupRows = 4;
 // Column schedule of the backward pass (bbm_build_col_index writes it, bbm_attn_bwd reads it): the same header and
-// 8-int part records with block columns in place of block rows, no launch-order records, and a lower floor of the
+// 8-int part records with block columns in place of block rows, launch-order records of single columns (longest
+// first; ties: higher column first) after the Mb*nbc part slots, and a lower floor of the
 // split threshold (a column entry stands for Br/64 sub-tiles of twice the work of a forward tile).
 constexpr int kColSchedMinSplit = 16;
 __host__ __device__ inline int64_t sched_order_base(int64_t Mb, int64_t nbr) { return kSchedPartBase + kSchedPartInts * Mb * nbr; }

@@ -59,6 +59,8 @@ def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
     if got.get("col_sched") is not None:
         n = oracle.blocks.SCHED_PART_BASE + oracle.blocks.SCHED_PART_INTS * int(want["col_sched"][0])
         assert got["col_sched"].size == want["col_sched"].size and np.array_equal(got["col_sched"][:n], want["col_sched"][:n])
+        Mb, _, nbc = want["cls"].shape
+        assert np.array_equal(got["col_sched"][-4 * Mb * nbc:], want["col_sched"][-4 * Mb * nbc:])     # launch-order records
     if got["packed_mask"] is not None:
         assert np.array_equal(got["packed_mask"], oracle.packed_bits(mask))
 

@@ -131,7 +131,7 @@ def test_attn_bwd_and_col_index_reject_bad_arguments(bbm):
     assert L.bbm_build_col_index(FAKE, 1, 4, 0, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
     assert L.bbm_build_col_index(FAKE, 1, 1 << 20, 1 << 20, FAKE, FAKE, None, None) == bbm.BBM_EINVAL
     assert L.bbm_build_col_index(FAKE, 1, 4, 4, FAKE, FAKE, C.c_void_p(0x1004), None) == bbm.BBM_EINVAL
-    assert bbm.bbm_col_sched_bytes(2, 5) == 4 * (8 + 8 * 10) and bbm.bbm_col_sched_bytes(0, 5) == 0
+    assert bbm.bbm_col_sched_bytes(2, 5) == 4 * (8 + 12 * 10) and bbm.bbm_col_sched_bytes(0, 5) == 0
     need = bbm.bbm_attn_bwd_workspace_bytes(2, 3, 100, 64, 128)
     assert need >= 2 * 4 * 600 + 3 * 4 * 600 * 64 and bbm.bbm_attn_bwd_workspace_bytes(0, 3, 100, 64, 128) == 0
     assert bbm.bbm_attn_bwd_workspace_bytes(2, 3, 100, 96, 128) == 0 and bbm.bbm_attn_bwd_workspace_bytes(2, 3, 100, 64, 32) == 0

@@ -45,6 +45,29 @@ def test_column_index_matches_oracle(N, Br):
     assert_index_equal(index_to_numpy(idx), mask, Br, 64)
 
 
+def test_column_index_of_a_plane_with_more_than_4096_block_columns():
+    """The class matrix is given directly (a mask with that many block columns would not fit): columns are not sorted
+    by length then but listed from the last to the first."""
+    bbm = _bbm()
+    from paper_2409_15097_amd.binding import BlockIndex
+    rng = np.random.default_rng(41)
+    cls = rng.integers(0, 3, size=(2, 3, 4100)).astype(np.uint8)
+    cls[:, :, 7] = 0
+    idx = BlockIndex(128, 64, 2, 3, 4100, 4100 * 64, blk_class=torch.from_numpy(cls).cuda())
+    bbm.bbm_build_col_index(idx)
+    torch.cuda.synchronize()
+    cp, ri = oracle.column_index(cls)
+    cs = oracle.column_schedule(cp, ri)
+    assert np.array_equal(idx.col_ptr.cpu().numpy(), cp)
+    got_ri = idx.row_idx.cpu().numpy().view(np.uint32)
+    for m in range(2):
+        assert np.array_equal(got_ri[m * 12300: m * 12300 + cp[m, -1]], ri[m * 12300: m * 12300 + cp[m, -1]])
+    got = idx.col_sched.cpu().numpy()
+    n = 8 + 8 * int(cs[0])
+    assert np.array_equal(got[:n], cs[:n]) and np.array_equal(got[-4 * 2 * 4100:], cs[-4 * 2 * 4100:])
+    assert got[-4 * 4100:].reshape(4100, 4)[:, 0].tolist() == list(range(4099, -1, -1))
+
+
 SMALL = [("C1", 256, 1, 2), ("C2", 1024, 2, 2), ("C3", 640, 1, 2), ("C4", 2048, 1, 2), ("C5", 2048, 1, 2),
          ("C0d", 512, 1, 2), ("C0c", 512, 1, 2)]
 

@@ -278,8 +278,15 @@ def test_column_schedule_hand_example_and_tiling():
     # columns with 3, 0, 40, 5 entries: mean of non-empty = 16 -> T = 32 -> the 40-entry column is cut into 2 x 20
     cp = np.array([[0, 3, 3, 43, 48]], dtype=np.int32)
     s = oracle.column_schedule(cp, _fake_lists(cp, 512))
-    assert (s[0], s[1], s[2]) == (2, 32, 1) and not s[3:8].any() and s.size == 8 + 8 * 4
+    assert (s[0], s[1], s[2]) == (2, 32, 1) and not s[3:8].any() and s.size == 8 + 12 * 4
     assert s[8:24].reshape(2, 8).tolist() == [[2, 3, 20, 0, 2, 0, 0, 3 - 2**31], [2, 23, 20, 1, 2, 0, 0, 23 - 2**31]]
+    # launch order: longest column first; records (column, first position, entries, first entry), -1 for an empty one
+    assert s[-16:].reshape(4, 4).tolist() == [[2, 3, 40, 3 - 2**31], [3, 43, 5, 43 - 2**31], [0, 0, 3, 0], [1, 3, 0, -1]]
+    # equal lengths: the higher column first; every plane on its own
+    cpe = np.array([[0, 2, 4, 5, 7], [0, 1, 1, 1, 4]], dtype=np.int32)
+    se = oracle.column_schedule(cpe, _fake_lists(cpe, 16))
+    assert se[-32:].reshape(8, 4)[:, 0].tolist() == [3, 1, 0, 2, 3, 0, 2, 1]
+    assert se[-32:].reshape(8, 4)[4].tolist() == [3, 1, 3, 1001 - 2**31] and se[-4:].tolist() == [1, 1, 0, -1]
     # the floor of the threshold is 16 here: columns of 1, 1, 1, 20 -> mean 6 -> T = 16 -> 20 is cut into 2 x 10
     cp2 = np.array([[0, 1, 2, 3, 23]], dtype=np.int32)
     s2 = oracle.column_schedule(cp2, _fake_lists(cp2, 64))
