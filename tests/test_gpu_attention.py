@@ -33,7 +33,7 @@ def _gpu_attn(cfg, Br, mode, scale=None):
 
 
 SMALL = [("C1", 256, 1, 2), ("C2", 1024, 2, 2), ("C3", 640, 1, 2), ("C4", 2048, 1, 2), ("C5", 2048, 1, 2),
-         ("C0d", 512, 1, 2), ("C0c", 512, 1, 2)]
+         ("C0d", 512, 1, 2), ("C0c", 512, 1, 2), ("C2b", 1024, 2, 2), ("C4w", 1024, 1, 2), ("C4d", 1024, 1, 2)]
 
 
 @pytest.mark.parametrize("name,N,B,H", SMALL)
@@ -124,7 +124,7 @@ def test_deterministic():
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(l1, l2)
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "C2b", "C4d"])
 def test_full_size_sampled_rows(name):
     """At the benchmark sizes the oracle evaluates sampled query rows one by one (same launch configuration as bench.py)."""
     bbm = _bbm()

@@ -69,7 +69,7 @@ def test_column_index_of_a_plane_with_more_than_4096_block_columns():
 
 
 SMALL = [("C1", 256, 1, 2), ("C2", 1024, 2, 2), ("C3", 640, 1, 2), ("C4", 2048, 1, 2), ("C5", 2048, 1, 2),
-         ("C0d", 512, 1, 2), ("C0c", 512, 1, 2)]
+         ("C0d", 512, 1, 2), ("C0c", 512, 1, 2), ("C2b", 1024, 2, 2), ("C4w", 1024, 1, 2), ("C4d", 1024, 1, 2)]
 
 
 @pytest.mark.parametrize("name,N,B,H", SMALL)
@@ -159,7 +159,7 @@ def test_deterministic():
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "C2b", "C4d"])
 def test_full_size_sampled_rows_and_columns(name):
     """At the benchmark sizes the oracle evaluates sampled query rows (dQ) and sampled keys (dK, dV) one by one."""
     bbm = _bbm()

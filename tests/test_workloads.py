@@ -86,3 +86,27 @@ def test_config_table_matches_stated_shapes():
     assert CONFIGS["C2"] == dict(B=4, H=16, N=4096, d=64, Mb=4, family="packed")
     assert CONFIGS["C3"]["N"] == 1024 + 256 and CONFIGS["C3"]["d"] == 128
     assert CONFIGS["C4"]["N"] == 16384 and CONFIGS["C5"]["N"] == 32768
+
+
+def test_further_mask_families_of_the_evaluation():
+    """Input-bidirectional packing, plain and dilated windows (paper Sec. 5, ALPACA and Longformer masks)."""
+    m = masks.packed_sequences(512, 1, 5, bidirectional_prefix=0.4, mu=np.log(40.0), hi=128)[0]
+    lens = masks.packed_lengths(512, 5, mu=np.log(40.0), hi=128)
+    pos = 0
+    for L in lens:
+        p = int(round(0.4 * L))
+        blk = m[pos:pos + L, pos:pos + L]
+        assert np.all(blk[:p, :p] == 1)                              # inputs see each other
+        assert np.array_equal(blk[p:], np.tril(np.ones((L, L), dtype=np.uint8))[p:])   # outputs: causal over the sequence
+        assert not blk[:p, p:].any()                                 # inputs do not see outputs
+        assert not m[pos:pos + L, :pos].any() and not m[pos:pos + L, pos + L:].any()
+        pos += L
+    assert not m[pos:].any()
+    w = masks.sliding_window(100, 7)[0]
+    d = masks.dilated_window(100, 7, 2)[0]
+    assert np.array_equal(masks.dilated_window(100, 7, 1)[0], w)
+    assert w[50].sum() == 15 and d[50].sum() == 15 and d[50, 36] == 1 and d[50, 37] == 0 and d[50, 64] == 1 and d[50, 66] == 0
+    assert np.array_equal(d, d.T) and np.all(np.diag(d) == 1)
+    for name in ("C2b", "C4w", "C4d"):
+        cfg = small_variant(name, N=512, B=1, H=1, with_qkv=False)
+        assert cfg["mask"].shape[1:] == (512, 512) and cfg["mask"].any()

@@ -19,6 +19,11 @@ CONFIGS = {
     "C0c": dict(B=4, H=16, N=4096, d=64, Mb=1, family="causal"),
     "C0d128": dict(B=2, H=32, N=8192, d=128, Mb=1, family="all_ones"),
     "C0c128": dict(B=2, H=32, N=8192, d=128, Mb=1, family="causal"),
+    # further mask families of the paper's evaluation (Sec. 5: ALPACA "Input-Bidirectional" packing; Longformer
+    # "Windowed" and "Dilated" masks), at the shapes of the neighbouring configurations
+    "C2b": dict(B=4, H=16, N=4096, d=64, Mb=4, family="packed_bidir"),
+    "C4w": dict(B=1, H=16, N=16384, d=64, Mb=1, family="window"),
+    "C4d": dict(B=1, H=16, N=16384, d=64, Mb=1, family="dilated"),
 }
 _IDS = {k: i for i, k in enumerate(CONFIGS)}
 
@@ -30,6 +35,14 @@ def make_mask(family: str, N: int, Mb: int, seed: int) -> np.ndarray:
         hi = min(1024, max(16, N // 4))
         mu = 5.3 if N >= 4096 else np.log(max(20.0, N / 20.0))
         return masks.packed_sequences(N, Mb, seed, mu=mu, hi=hi)
+    if family == "packed_bidir":     # the first 40 % of every packed sequence (its "input") attends in both directions
+        hi = min(1024, max(16, N // 4))
+        mu = 5.3 if N >= 4096 else np.log(max(20.0, N / 20.0))
+        return masks.packed_sequences(N, Mb, seed, bidirectional_prefix=0.4, mu=mu, hi=hi)
+    if family == "window":           # +-256 keys, as the window of the long-context configuration
+        return masks.sliding_window(N, 256 if N >= 16384 else max(32, N // 32))
+    if family == "dilated":          # 256 keys on each side, every second position: every block of the band is partial
+        return masks.dilated_window(N, 256 if N >= 16384 else max(32, N // 32), 2)
     if family == "tree":
         tree = 256 if N >= 1280 else max(16, N // 5)
         return masks.tree_verification(N - tree, masks.random_subtree([10, 5, 3, 2], tree, seed))

@@ -25,6 +25,14 @@ def sliding_window(N: int, w: int) -> np.ndarray:
     return (np.abs(i[:, None] - i[None, :]) <= w).astype(np.uint8)[None]
 
 
+def dilated_window(N: int, w: int, dilation: int) -> np.ndarray:
+    """Longformer's dilated sliding window: |i - j| <= w * dilation and (i - j) divisible by the dilation, i.e. w keys
+    on each side with gaps of dilation - 1 between them (dilation = 1 is sliding_window)."""
+    i = np.arange(N)
+    diff = i[:, None] - i[None, :]
+    return ((np.abs(diff) <= w * dilation) & (diff % dilation == 0)).astype(np.uint8)[None]
+
+
 def random_blocks(N: int, seed: int, blk: int = 64, p_empty=0.4, p_full=0.3, p_elem=0.5) -> np.ndarray:
     """Grid of blk x blk blocks, each empty / full / partial (Bernoulli(p_elem) per element); diagonal forced on."""
     assert N % blk == 0
