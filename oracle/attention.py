@@ -9,7 +9,9 @@ expected result is the plain definition of Sec. 3 "Standard Attention" restricte
 
 Readings where the paper is silent: scale is an argument (1/sqrt(d) by default); a row with A_i empty gives
 O_i = 0 and lse_i = -inf; the mask has Mb = 1 (shared by the batch) or Mb = B planes and is always shared by
-the heads (Sec. 1, insight (2)).
+the heads (Sec. 1, insight (2)).  Queries and keys may differ in number (a block of new tokens attending a longer
+key/value cache, as when a candidate tree is verified against its prefix, Sec. 5): q is [B,H,Nq,d], k and v are
+[B,H,Nk,d], the mask [Mb,Nq,Nk]; the definition does not change.
 """
 import numpy as np
 
@@ -25,13 +27,13 @@ def _as_f64(x):
 
 
 def masked_attention(q, k, v, mask, scale=None, row_chunk=512):
-    """q, k, v: [B,H,N,d] (uint16 bf16 bit patterns or float arrays); mask: [Mb,N,N], non-zero = attend.
+    """q: [B,H,N,d], k, v: [B,H,Nk,d] (uint16 bf16 bit patterns or float arrays); mask: [Mb,N,Nk], non-zero = attend.
 
     Returns O float64 [B,H,N,d] and lse float64 [B,H,N] (natural log; -inf on fully masked rows)."""
     q, k, v = _as_f64(q), _as_f64(k), _as_f64(v)
     B, H, N, d = q.shape
     Mb = mask.shape[0]
-    assert mask.shape == (Mb, N, N) and Mb in (1, B)
+    assert k.shape == v.shape == (B, H, k.shape[2], d) and mask.shape == (Mb, N, k.shape[2]) and Mb in (1, B)
     scale = 1.0 / np.sqrt(float(d)) if scale is None else float(scale)
     O = np.zeros((B, H, N, d), dtype=np.float64)
     lse = np.full((B, H, N), -np.inf, dtype=np.float64)

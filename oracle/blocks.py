@@ -4,7 +4,8 @@ Definitions (paper Sec. 4 "Binary Block Masking", "Dense Binary Block Masking"; 
 formulation) with the readings this build fixes where the paper is silent:
 
 * the mask is zero-padded to nbr*Br x nbc*Bc with nbr = ceil(N/Br), nbc = ceil(N/Bc) (the paper assumes
-  divisibility); a block that contains padding can therefore never be "filled with ones";
+  divisibility); a block that contains padding can therefore never be "filled with ones"; the mask may be
+  rectangular, [Mb, Nq, Nk] (nbr from Nq, nbc from Nk), for queries that attend a longer key/value cache;
 * cnt[i][j]  = number of non-zero elements of block (i, j);   BinBlkMat[i][j] = (cnt > 0);
 * class[i][j] = 0 if cnt == 0, 2 if cnt == Br*Bc, else 1;
 * total_ones[i], offset[i] = length and first block of the LONGEST run of consecutive class-2 blocks in
@@ -22,13 +23,13 @@ import numpy as np
 
 
 def block_counts(mask, Br, Bc):
-    """mask [Mb,N,N] -> int64 [Mb,nbr,nbc] non-zero counts per block of the zero-padded mask."""
-    Mb, N, _ = mask.shape
-    nbr, nbc = -(-N // Br), -(-N // Bc)
+    """mask [Mb,Nq,Nk] -> int64 [Mb,nbr,nbc] non-zero counts per block of the zero-padded mask."""
+    Mb, N, Nk = mask.shape
+    nbr, nbc = -(-N // Br), -(-Nk // Bc)
     out = np.zeros((Mb, nbr, nbc), dtype=np.int64)
     for m in range(Mb):
         pad = np.zeros((nbr * Br, nbc * Bc), dtype=np.uint8)
-        pad[:N, :N] = mask[m] != 0
+        pad[:N, :Nk] = mask[m] != 0
         out[m] = pad.reshape(nbr, Br, nbc, Bc).sum(axis=(1, 3), dtype=np.int64)
     return out
 
@@ -43,8 +44,8 @@ def block_class(mask, Br, Bc):
 
 def bin_blk_mat(mask, Br, Bc):
     """The paper's BinBlkMat via its 'any element non-zero' wording (not via the counts)."""
-    Mb, N, _ = mask.shape
-    nbr, nbc = -(-N // Br), -(-N // Bc)
+    Mb, N, Nk = mask.shape
+    nbr, nbc = -(-N // Br), -(-Nk // Bc)
     out = np.zeros((Mb, nbr, nbc), dtype=np.uint8)
     for m in range(Mb):
         for i in range(nbr):
@@ -112,9 +113,9 @@ def column_index(cls):
 
 
 def packed_bits(mask):
-    """mask [Mb,N,N] -> uint64 [Mb, ceil(N/64), N]: word-column major, bit t of word (w, r) = mask[r][64w+t] != 0."""
-    Mb, N, _ = mask.shape
-    W = -(-N // 64)
+    """mask [Mb,N,Nk] -> uint64 [Mb, ceil(Nk/64), N]: word-column major, bit t of word (w, r) = mask[r][64w+t] != 0."""
+    Mb, N, Nk = mask.shape
+    W = -(-Nk // 64)
     out = np.zeros((Mb, W, N), dtype=np.uint64)
     for m in range(Mb):
         nzr, nzc = np.nonzero(mask[m])

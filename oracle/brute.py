@@ -8,7 +8,7 @@ import numpy as np
 
 
 def brute_attention(q, k, v, mask, scale):
-    """q,k,v float arrays [B,H,N,d]; mask [Mb,N,N]; pure Python loops.  Returns (O, lse) as float64 arrays."""
+    """q [B,H,N,d], k, v [B,H,Nk,d] float arrays; mask [Mb,N,Nk]; pure Python loops.  Returns (O, lse) as float64 arrays."""
     B, H, N, d = q.shape
     Mb = mask.shape[0]
     O = np.zeros((B, H, N, d))
@@ -17,7 +17,7 @@ def brute_attention(q, k, v, mask, scale):
         mb = mask[b if Mb == B else 0]
         for h in range(H):
             for i in range(N):
-                A = [j for j in range(N) if mb[i, j] != 0]
+                A = [j for j in range(k.shape[2]) if mb[i, j] != 0]
                 if not A:
                     continue
                 s = [scale * sum(float(q[b, h, i, c]) * float(k[b, h, j, c]) for c in range(d)) for j in A]
@@ -31,15 +31,15 @@ def brute_attention(q, k, v, mask, scale):
 
 
 def brute_block_counts(mask2d, Br, Bc):
-    """Count of non-zero elements in every Br x Bc block of one N x N mask, zero-padded; 4 nested loops."""
-    N = mask2d.shape[0]
-    nbr, nbc = -(-N // Br), -(-N // Bc)
+    """Count of non-zero elements in every Br x Bc block of one N x Nk mask, zero-padded; 4 nested loops."""
+    N, Nk = mask2d.shape
+    nbr, nbc = -(-N // Br), -(-Nk // Bc)
     cnt = [[0] * nbc for _ in range(nbr)]
     for bi in range(nbr):
         for bj in range(nbc):
             c = 0
             for r in range(bi * Br, min(N, (bi + 1) * Br)):
-                for s in range(bj * Bc, min(N, (bj + 1) * Bc)):
+                for s in range(bj * Bc, min(Nk, (bj + 1) * Bc)):
                     if mask2d[r, s] != 0:
                         c += 1
             cnt[bi][bj] = c

@@ -163,3 +163,33 @@ def test_softmax_weights_sum_to_one_and_lse_shift():
     fin = np.isfinite(l2)
     assert np.abs(O3 - O2).max() < 1e-12
     assert np.abs(l3[fin] - l2[fin] - 2.5).max() < 1e-12
+
+
+def test_rectangular_mask_new_queries_against_a_longer_key_cache():
+    """Nq != Nk: brute force, the library routine, and "the last Nq rows of the square problem"."""
+    rng = np.random.default_rng(14)
+    B, H, Nq, Nk, d = 2, 2, 7, 19, 8
+    q = rng.standard_normal((B, H, Nq, d))
+    k, v = (rng.standard_normal((B, H, Nk, d)) for _ in range(2))
+    mask = (rng.random((2, Nq, Nk)) < 0.5).astype(np.uint8)
+    mask[:, 3] = 0
+    O, lse = oracle.masked_attention(q, k, v, mask, scale=0.3, row_chunk=4)
+    Ob, lb = oracle.brute_attention(q, k, v, mask, 0.3)
+    fin = np.isfinite(lb)
+    assert O.shape == (B, H, Nq, d) and np.abs(O - Ob).max() < 1e-12 and np.array_equal(np.isfinite(lse), fin)
+    assert np.abs(lse[fin] - lb[fin]).max() < 1e-12 and not fin[:, :, 3].any()
+    rows = [(0, 0, 0), (1, 1, 6), (1, 0, 3)]
+    Or, lr = oracle.masked_attention_rows(q, k, v, mask, rows)
+    O2, l2 = oracle.masked_attention(q, k, v, mask)
+    for n, (b, h, i) in enumerate(rows):
+        assert np.abs(Or[n] - O2[b, h, i]).max() < 1e-13
+    mask[:, 3, 0] = 1
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        *(torch.from_numpy(x) for x in (q, k, v)), attn_mask=torch.from_numpy(mask != 0)[:, None], scale=0.3).numpy()
+    assert np.abs(oracle.masked_attention(q, k, v, mask, scale=0.3)[0] - ref).max() < 1e-12
+    # the new tokens are the last Nq rows of a square problem over all Nk tokens
+    qs = rng.standard_normal((B, H, Nk, d))
+    sq = (rng.random((2, Nk, Nk)) < 0.5).astype(np.uint8)
+    Os, ls = oracle.masked_attention(qs, k, v, sq)
+    Ot, lt = oracle.masked_attention(qs[:, :, -Nq:], k, v, sq[:, -Nq:])
+    assert np.array_equal(Ot, Os[:, :, -Nq:]) and np.array_equal(lt, ls[:, :, -Nq:])

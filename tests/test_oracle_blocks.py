@@ -310,3 +310,24 @@ def test_column_schedule_hand_example_and_tiling():
     cut = counts > T
     assert np.array_equal(covered[cut], counts[cut]) and not covered[~cut].any()
     assert ncut == int(cut.sum()) and nparts <= counts.size
+
+
+def test_rectangular_mask_blocks_index_and_packed_bits():
+    rng = np.random.default_rng(9)
+    mask = (rng.random((2, 70, 200)) < 0.3).astype(np.uint8)
+    mask[0, :64, 64:128] = 1
+    mask[1, :, 128:] = 0
+    cnt = oracle.block_counts(mask, 64, 64)
+    assert cnt.shape == (2, 2, 4)
+    for m in range(2):
+        assert np.array_equal(cnt[m], oracle.brute_block_counts(mask[m], 64, 64))
+    cls = oracle.block_class(mask, 64, 64)
+    assert cls[0, 0, 1] == 2 and np.all(cls[1, :, 2:] == 0) and cls[0, 1, 1] == 1       # the ragged block row is never full
+    assert np.array_equal(oracle.bin_blk_mat(mask, 64, 64), (cls != 0).astype(np.uint8))
+    pk = oracle.packed_bits(mask)
+    assert pk.shape == (2, 4, 70)
+    bits = np.unpackbits(pk.view(np.uint8).reshape(2, 4, 70, 8), axis=-1, bitorder="little").reshape(2, 4, 70, 64)
+    back = bits.transpose(0, 2, 1, 3).reshape(2, 70, 256)[:, :, :200]
+    assert np.array_equal(back, mask) and not bits.transpose(0, 2, 1, 3).reshape(2, 70, 256)[:, :, 200:].any()
+    idx = oracle.block_index(mask, 64, 64)
+    assert idx["row_ptr"].shape == (2, 3) and idx["col_ptr"].shape == (2, 5)
