@@ -82,42 +82,44 @@ def measure_mask(bbm, name, Br, warmup, steps, torch, backward=False):
     from workloads import make_config
     cfg = make_config(name)
     B, H, N, d, Mb = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["Mb"]
+    Nq = cfg.get("Nq", N)                 # queries per head (N keys): differs only for the decode-time configuration
+    backward = backward and Nq == N       # the backward entry point takes one sequence length
     mask = torch.from_numpy(cfg["mask"]).cuda()
     q, k, v = (bbm.bf16_from_bits(cfg[x]) for x in "qkv")
     idx = bbm.build_index(mask, Br, 64)
     out = torch.empty_like(q)
-    lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
-    ws = torch.zeros(max(16, bbm.bbm_attn_fwd_workspace_bytes(B, H, N, d, Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
+    lse = torch.empty((B, H, Nq), dtype=torch.float32, device="cuda")
+    ws = torch.zeros(max(16, bbm.bbm_attn_fwd_workspace_bytes(B, H, Nq, d, Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     tiles = visited_tiles(idx, B, H)
     cls = idx.blk_class
     census = dict(empty=int((cls == 0).sum()), partial=int((cls == 1).sum()), full=int((cls == 2).sum()))
     flops = 4.0 * Br * 64 * d * tiles
-    dense_flops = 4.0 * N * N * d * B * H
+    dense_flops = 4.0 * Nq * N * d * B * H
     useful_flops = 4.0 * float(np.count_nonzero(cfg["mask"])) * (B // Mb) * d * H
 
     def step():
-        bbm.bbm_build_block_mask(mask, Br, 64, idx=idx)
+        bbm.bbm_build_block_mask_rect(mask, Br, 64, idx=idx)
         bbm.bbm_build_index(idx)
-        bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws)
+        bbm.bbm_attn_fwd_rect(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws)
 
-    res = dict(workload=name, B=B, H=H, N=N, d=d, Mb=Mb, Br=Br, Bc=64, visited_tiles=tiles, blocks=census,
+    res = dict(workload=name, B=B, H=H, N=N, Nq=Nq, d=d, Mb=Mb, Br=Br, Bc=64, visited_tiles=tiles, blocks=census,
                visited_tflop=flops / 1e12, dense_tflop=dense_flops / 1e12, useful_tflop=useful_flops / 1e12)
     res["step_ms"] = time_gpu(step, warmup, steps)
     for mode_name in ("LIST", "RUNS", "BITMAP"):
         mode = getattr(bbm, "BBM_MODE_" + mode_name)
-        ms = time_gpu(lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=mode, out=out, lse=lse, workspace=ws), warmup, steps)
+        ms = time_gpu(lambda: bbm.bbm_attn_fwd_rect(q, k, v, idx, mode=mode, out=out, lse=lse, workspace=ws), warmup, steps)
         res[f"attn_{mode_name.lower()}_ms"] = ms
     res["attn_ms"] = res["attn_list_ms"]
     res["attn_tflops_visited"] = flops / (res["attn_ms"] * 1e-3) / 1e12
     res["attn_mfma_frac"] = res["attn_tflops_visited"] / MFMA_BF16_PEAK_TFLOPS
     dense_steps = max(3, min(steps, int(2000.0 / max(1.0, dense_flops / 1e12 / 0.1))))
     res["dense_tile_ms"] = time_gpu(
-        lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_DENSE_BASELINE, out=out, lse=lse), 2, dense_steps)
+        lambda: bbm.bbm_attn_fwd_rect(q, k, v, idx, mode=bbm.BBM_MODE_DENSE_BASELINE, out=out, lse=lse), 2, dense_steps)
     res["dense_tile_tflops"] = dense_flops / (res["dense_tile_ms"] * 1e-3) / 1e12
     res["speedup_vs_dense_tile"] = res["dense_tile_ms"] / res["attn_ms"]
-    pre_ms = time_gpu(lambda: bbm.bbm_build_block_mask(mask, Br, 64, idx=idx), warmup, steps)
-    pre_bytes = Mb * N * N * (1.0 + 1.0 / 8.0) + 2.0 * Mb * idx.nbr * idx.nbc
+    pre_ms = time_gpu(lambda: bbm.bbm_build_block_mask_rect(mask, Br, 64, idx=idx), warmup, steps)
+    pre_bytes = Mb * Nq * N * (1.0 + 1.0 / 8.0) + 2.0 * Mb * idx.nbr * idx.nbc
     res["preprocess_ms"] = pre_ms
     res["preprocess_gbs"] = pre_bytes / (pre_ms * 1e-3) / 1e9
     res["preprocess_hbm_frac"] = res["preprocess_gbs"] / HBM_PEAK_GBS
@@ -139,7 +141,7 @@ def measure_mask(bbm, name, Br, warmup, steps, torch, backward=False):
         res["fwd_bwd_ms"] = res["attn_ms"] + res["bwd_ms"]
         del d_o, dq, dk, dv, ws_b
     # algorithmic HBM bytes of the attention kernel: Q, K, V read once, O written once, lse, packed words of partial tiles
-    res["attn_algo_bytes"] = 4.0 * B * H * N * d * 2 + 4.0 * B * H * N + census["partial"] * (B // Mb) * Br * 8.0
+    res["attn_algo_bytes"] = 2.0 * B * H * (Nq + N) * d * 2 + 4.0 * B * H * Nq + census["partial"] * (B // Mb) * Br * 8.0
     del mask, q, k, v, idx, out, lse, ws
     torch.cuda.empty_cache()
     return res, cfg
@@ -223,7 +225,7 @@ def main():
 
     main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch, not a.no_backward)
     rows = [main_res]
-    extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128,C2b,C4w,C4d" if a.masks == "all" else a.masks
+    extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128,C2b,C4w,C4d,C3q" if a.masks == "all" else a.masks
     for name in [m for m in extra.split(",") if m and m != a.workload]:
         r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch, not a.no_backward)
         rows.append(r)

@@ -98,6 +98,16 @@ int bbm_build_block_mask(const uint8_t* mask, int64_t Mb, int64_t N, int64_t row
                          uint8_t* blk_class, uint8_t* bin_blk_mat, uint64_t* packed_mask, void* stream);
 
 /*
+ * The same reduction for a rectangular mask: Nq query rows x Nk key columns (a block of new tokens attending a longer
+ * key/value cache, e.g. a candidate tree verified against its prefix, paper Sec. 5).  mask is uint8
+ * [Mb][Nq][row_stride_bytes] with row_stride_bytes >= Nk; nbr = ceil(Nq/Br), nbc = ceil(Nk/Bc); packed_mask is
+ * uint64 [Mb][ceil(Nk/64)][Nq].  bbm_build_block_mask(.., N, ..) is this call with Nq = Nk = N; same errors.  The index
+ * builders below take nbr and nbc and need no rectangular form.
+ */
+int bbm_build_block_mask_rect(const uint8_t* mask, int64_t Mb, int64_t Nq, int64_t Nk, int64_t row_stride_bytes, int Br,
+                              int Bc, uint8_t* blk_class, uint8_t* bin_blk_mat, uint64_t* packed_mask, void* stream);
+
+/*
  * Stage 1b -- contiguous-run index (paper Sec. 4 "Dense Binary Block Masking": per block row, total_ones =
  * number of consecutive blocks filled with ones, offset = position of the first such block).
  * Reading fixed here: "filled with ones" = BBM_BLOCK_FULL; if a row has several runs the longest is kept,
@@ -201,6 +211,16 @@ size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
 int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t N,
                  int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask, const bbm_index* idx, int mode,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * bbm_attn_fwd for Nq queries against Nk keys per (batch, head): q and o are [B][H][Nq][d], k and v [B][H][Nk][d], lse
+ * [B][H][Nq], packed_mask [Mb][ceil(Nk/64)][Nq] from bbm_build_block_mask_rect, idx->nbr = ceil(Nq/Br), idx->nbc =
+ * ceil(Nk/Bc).  Everything else as bbm_attn_fwd, which is this call with Nq = Nk = N; the workspace size is
+ * bbm_attn_fwd_workspace_bytes(B, H, Nq, ...).
+ */
+int bbm_attn_fwd_rect(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t Nq,
+                      int64_t Nk, int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask,
+                      const bbm_index* idx, int mode, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Per-column list of non-zero blocks, the transpose of the list of bbm_build_sparse_index: what the dK/dV step of

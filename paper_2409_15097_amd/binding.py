@@ -42,6 +42,11 @@ def _load():
     L.bbm_version.argtypes = []
     L.bbm_build_block_mask.restype = ci
     L.bbm_build_block_mask.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp, vp, vp]
+    L.bbm_build_block_mask_rect.restype = ci
+    L.bbm_build_block_mask_rect.argtypes = [vp, i64, i64, i64, i64, ci, ci, vp, vp, vp, vp]
+    L.bbm_attn_fwd_rect.restype = ci
+    L.bbm_attn_fwd_rect.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, C.c_float, i64, vp, C.POINTER(_CIndex), ci,
+                                    vp, C.c_size_t, vp]
     L.bbm_build_runs.restype = ci
     L.bbm_build_runs.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
     L.bbm_build_sparse_index.restype = ci
@@ -105,7 +110,8 @@ class BlockIndex:
     Mb: int
     nbr: int
     nbc: int
-    N: int
+    N: int                      # query rows of the mask
+    Nk: Optional[int] = None    # key columns (None: square, = N)
     blk_class: Optional[torch.Tensor] = None
     bin_blk_mat: Optional[torch.Tensor] = None
     packed_mask: Optional[torch.Tensor] = None
@@ -132,20 +138,32 @@ def bbm_build_block_mask(mask: torch.Tensor, Br: int, Bc: int, idx: Optional[Blo
                          want_bin: bool = True, want_packed: bool = True, stream=None) -> BlockIndex:
     """mask: uint8 CUDA tensor [Mb,N,N] (row stride may exceed N).  Writes class / BinBlkMat / packed bits into
     idx's tensors (allocated here when idx is None) and returns idx."""
+    assert mask.shape[1] == mask.shape[2]
+    return bbm_build_block_mask_rect(mask, Br, Bc, idx=idx, want_bin=want_bin, want_packed=want_packed, stream=stream)
+
+
+def bbm_build_block_mask_rect(mask: torch.Tensor, Br: int, Bc: int, idx: Optional[BlockIndex] = None,
+                              want_bin: bool = True, want_packed: bool = True, stream=None) -> BlockIndex:
+    """mask: uint8 CUDA tensor [Mb,Nq,Nk] (row stride may exceed Nk).  As bbm_build_block_mask; a square mask goes
+    through the square entry point of the library."""
     assert mask.is_cuda and mask.dtype == torch.uint8 and mask.dim() == 3 and mask.stride(2) == 1
-    Mb, N, _ = mask.shape
-    assert mask.shape[2] == N and (Mb == 1 or mask.stride(0) == N * mask.stride(1))
-    nbr, nbc = _cdiv(N, Br), _cdiv(N, Bc)
+    Mb, N, Nk = mask.shape
+    assert Mb == 1 or mask.stride(0) == N * mask.stride(1)
+    nbr, nbc = _cdiv(N, Br), _cdiv(Nk, Bc)
     if idx is None:
         dev = mask.device
-        idx = BlockIndex(Br, Bc, Mb, nbr, nbc, N)
+        idx = BlockIndex(Br, Bc, Mb, nbr, nbc, N, Nk=None if Nk == N else Nk)
         idx.blk_class = torch.empty((Mb, nbr, nbc), dtype=torch.uint8, device=dev)
         if want_bin:
             idx.bin_blk_mat = torch.empty((Mb, nbr, nbc), dtype=torch.uint8, device=dev)
         if want_packed:
-            idx.packed_mask = torch.empty((Mb, _cdiv(N, 64), N), dtype=torch.int64, device=dev)
-    _check(lib.bbm_build_block_mask(_ptr(mask), Mb, N, mask.stride(1), Br, Bc, _ptr(idx.blk_class),
-                                    _ptr(idx.bin_blk_mat), _ptr(idx.packed_mask), _stream(stream)))
+            idx.packed_mask = torch.empty((Mb, _cdiv(Nk, 64), N), dtype=torch.int64, device=dev)
+    if Nk == N:
+        _check(lib.bbm_build_block_mask(_ptr(mask), Mb, N, mask.stride(1), Br, Bc, _ptr(idx.blk_class),
+                                        _ptr(idx.bin_blk_mat), _ptr(idx.packed_mask), _stream(stream)))
+    else:
+        _check(lib.bbm_build_block_mask_rect(_ptr(mask), Mb, N, Nk, mask.stride(1), Br, Bc, _ptr(idx.blk_class),
+                                             _ptr(idx.bin_blk_mat), _ptr(idx.packed_mask), _stream(stream)))
     return idx
 
 
@@ -216,7 +234,7 @@ def build_index(mask: torch.Tensor, Br: int, Bc: int = 64, idx: Optional[BlockIn
     """The whole preprocessing stage: block classes, then run index + block list + schedule (through the one-call
     entry point, or with fused=False through the two separate ones); columns=True adds the per-column list the
     backward pass needs."""
-    idx = bbm_build_block_mask(mask, Br, Bc, idx=idx, stream=stream)
+    idx = bbm_build_block_mask_rect(mask, Br, Bc, idx=idx, stream=stream)
     if fused:
         bbm_build_index(idx, stream=stream)
     else:
@@ -241,9 +259,21 @@ def bbm_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIn
                  softmax_scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
                  lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
     """q, k, v: bf16 CUDA tensors [B,H,N,d], contiguous.  Returns (O bf16 [B,H,N,d], lse fp32 [B,H,N])."""
+    assert k.shape == q.shape
+    return bbm_attn_fwd_rect(q, k, v, idx, mode=mode, softmax_scale=softmax_scale, out=out, lse=lse, workspace=workspace,
+                             stream=stream)
+
+
+def bbm_attn_fwd_rect(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIndex, mode: int = BBM_MODE_AUTO,
+                      softmax_scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
+                      lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """q: bf16 CUDA tensor [B,H,Nq,d], k, v: [B,H,Nk,d], contiguous.  Returns (O bf16 [B,H,Nq,d], lse fp32 [B,H,Nq]).
+    Equal Nq and Nk go through the square entry point of the library."""
     assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
-    assert k.shape == q.shape and v.shape == q.shape and k.dtype == q.dtype and v.dtype == q.dtype
+    assert v.shape == k.shape and k.shape[:2] == q.shape[:2] and k.shape[3] == q.shape[3]
+    assert k.dtype == q.dtype and v.dtype == q.dtype
     B, H, N, d = q.shape
+    Nk = k.shape[2]
     if softmax_scale is None:
         softmax_scale = float(d) ** -0.5
     if out is None:
@@ -254,9 +284,13 @@ def bbm_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIn
     if workspace is None and need > 0:
         workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)   # the library wants it zero-filled once
     cs = idx.c_struct()
-    _check(lib.bbm_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, N, d, softmax_scale, idx.Mb,
-                            _ptr(idx.packed_mask), C.byref(cs), mode, _ptr(workspace),
-                            0 if workspace is None else workspace.numel(), _stream(stream)))
+    ws_bytes = 0 if workspace is None else workspace.numel()
+    if Nk == N:
+        _check(lib.bbm_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, N, d, softmax_scale, idx.Mb,
+                                _ptr(idx.packed_mask), C.byref(cs), mode, _ptr(workspace), ws_bytes, _stream(stream)))
+    else:
+        _check(lib.bbm_attn_fwd_rect(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, N, Nk, d, softmax_scale, idx.Mb,
+                                     _ptr(idx.packed_mask), C.byref(cs), mode, _ptr(workspace), ws_bytes, _stream(stream)))
     return out, lse
 
 

@@ -43,7 +43,8 @@ struct AttnParams {
   const int32_t* nz_hi;
   const int32_t* row_ptr;
   const uint32_t* col_idx;
-  int64_t N;
+  int64_t N;   // queries per head
+  int64_t Nk;  // keys per head (= N for self-attention over one sequence)
   int32_t H, Mb, nbr, nbc, W;
   int32_t total_wgs;
   int32_t mode;
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction: keep it in a scalar register
   const int lq = lane & 31, hh = lane >> 5;
-  const int64_t N = P.N;
+  const int64_t N = P.N, Nk = P.Nk;
   const float c = P.scale * kLog2e;
 
   // ---- per-item state (SCHED = false: exactly one item, derived from blockIdx)
@@ -206,8 +207,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   auto q_stage = [&]() { return (wave / 2 == 0 ? k_s1 : v_s1) + (wave % 2) * 32 * D; };
   auto begin_item = [&]() {
     head_off = (int64_t)bh * N * D;
-    Kg = P.k + head_off;
-    Vg = P.v + head_off;
+    Kg = P.k + (int64_t)bh * Nk * D;
+    Vg = P.v + (int64_t)bh * Nk * D;
     qrow = (int64_t)i * BR + wave * 32 + lq;
     q_ok = qrow < N;
     // packed mask words of this lane's query row (rows past N borrow row 0: their results are never stored)
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   auto load_tile_async = [&](const __bf16* __restrict__ src, int jt, __bf16* dst, int blk_stride) {
     const int64_t key0 = (int64_t)jt * kBc;
     const char* tile = reinterpret_cast<const char*>(src + key0 * D);
-    if (key0 + kBc <= N) {
+    if (key0 + kBc <= Nk) {
 #pragma unroll
       for (int n = 0; n < LPW; ++n) {
         const int q = n * NW + wave;  // block filled by this instruction
@@ -263,9 +264,9 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
                                          (void __attribute__((address_space(3)))*)(dst + q * blk_stride), 16, 0, 0);
       }
     } else {
-      // Last tile of a ragged N.  Rows past N re-read row N-1: such keys sit in a tile that is never "full", the
+      // Last tile of a ragged key count Nk.  Rows past Nk re-read row Nk-1: such keys sit in a tile that is never "full", the
       // element mask gives them probability exactly 0, and a finite duplicate row then adds nothing.
-      const int last = (int)(N - 1 - key0);  // last real row of the tile
+      const int last = (int)(Nk - 1 - key0);  // last real row of the tile
 #pragma unroll
       for (int n = 0; n < LPW; ++n) {
         const int q = n * NW + wave;
@@ -637,26 +638,28 @@ extern "C" __attribute__((visibility("default"))) size_t bbm_attn_fwd_workspace_
   return queue_bytes(1, nbr, B * H) + partial_bytes(1, nbr, B * H, d, Br);
 }
 
-extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H,
-                            int64_t N, int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask,
-                            const bbm_index* idx, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t N, int64_t Nk,
+                  int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask, const bbm_index* idx, int mode,
+                  void* workspace, size_t workspace_bytes, void* stream) {
   using namespace bbm;
   clear_error();
-  if (!q || !k || !v || !o) return fail(BBM_EINVAL, "bbm_attn_fwd: q, k, v, o must not be NULL");
+  if (!q || !k || !v || !o) return fail(BBM_EINVAL, "%s: q, k, v, o must not be NULL", fn);
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16))
-    return fail(BBM_EINVAL, "bbm_attn_fwd: q, k, v, o must be 16-byte aligned");
-  if (lse && !aligned(lse, 4)) return fail(BBM_EINVAL, "bbm_attn_fwd: lse must be 4-byte aligned");
-  if (B < 1 || H < 1 || N < 1) return fail(BBM_EINVAL, "bbm_attn_fwd: B=%lld, H=%lld, N=%lld must be >= 1", (long long)B, (long long)H, (long long)N);
-  if (!(softmax_scale > 0.0f) || !(softmax_scale < INFINITY)) return fail(BBM_EINVAL, "bbm_attn_fwd: softmax_scale must be finite and > 0");
-  if (Mb != 1 && Mb != B) return fail(BBM_EINVAL, "bbm_attn_fwd: Mb=%lld must be 1 or B=%lld", (long long)Mb, (long long)B);
-  if (!idx) return fail(BBM_EINVAL, "bbm_attn_fwd: idx must not be NULL");
-  if (!packed_mask || !aligned(packed_mask, 8)) return fail(BBM_EINVAL, "bbm_attn_fwd: packed_mask must be a non-NULL 8-byte aligned pointer");
-  if (d != 64 && d != 128) return fail(BBM_EUNSUPPORTED, "bbm_attn_fwd: d=%d has no kernel instance (64, 128)", d);
+    return fail(BBM_EINVAL, "%s: q, k, v, o must be 16-byte aligned", fn);
+  if (lse && !aligned(lse, 4)) return fail(BBM_EINVAL, "%s: lse must be 4-byte aligned", fn);
+  if (B < 1 || H < 1 || N < 1 || Nk < 1)
+    return fail(BBM_EINVAL, "%s: B=%lld, H=%lld, N=%lld (queries), %lld (keys) must be >= 1", fn, (long long)B, (long long)H, (long long)N, (long long)Nk);
+  if (!(softmax_scale > 0.0f) || !(softmax_scale < INFINITY)) return fail(BBM_EINVAL, "%s: softmax_scale must be finite and > 0", fn);
+  if (Mb != 1 && Mb != B) return fail(BBM_EINVAL, "%s: Mb=%lld must be 1 or B=%lld", fn, (long long)Mb, (long long)B);
+  if (!idx) return fail(BBM_EINVAL, "%s: idx must not be NULL", fn);
+  if (!packed_mask || !aligned(packed_mask, 8)) return fail(BBM_EINVAL, "%s: packed_mask must be a non-NULL 8-byte aligned pointer", fn);
+  if (d != 64 && d != 128) return fail(BBM_EUNSUPPORTED, "%s: d=%d has no kernel instance (64, 128)", fn, d);
   if (idx->Bc != kBc || (idx->Br != 64 && idx->Br != 128 && idx->Br != 256))
-    return fail(BBM_EUNSUPPORTED, "bbm_attn_fwd: tile (Br=%d, Bc=%d) has no kernel instance (Br in {64,128,256}, Bc = 64)", idx->Br, idx->Bc);
-  const int64_t nbr = ceil_div(N, idx->Br), nbc = ceil_div(N, idx->Bc);
+    return fail(BBM_EUNSUPPORTED, "%s: tile (Br=%d, Bc=%d) has no kernel instance (Br in {64,128,256}, Bc = 64)", fn, idx->Br, idx->Bc);
+  const int64_t nbr = ceil_div(N, idx->Br), nbc = ceil_div(Nk, idx->Bc);
   if (idx->Mb != Mb || idx->nbr != nbr || idx->nbc != nbc)
-    return fail(BBM_EINVAL, "bbm_attn_fwd: index (Mb=%lld, nbr=%lld, nbc=%lld) does not match the problem (Mb=%lld, nbr=%lld, nbc=%lld)",
+    return fail(BBM_EINVAL, "%s: index (Mb=%lld, nbr=%lld, nbc=%lld) does not match the problem (Mb=%lld, nbr=%lld, nbc=%lld)", fn,
                 (long long)idx->Mb, (long long)idx->nbr, (long long)idx->nbc, (long long)Mb, (long long)nbr, (long long)nbc);
   if (mode == BBM_MODE_AUTO)
     mode = (idx->row_ptr && idx->col_idx && idx->sched) ? BBM_MODE_LIST
@@ -664,27 +667,27 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
                                                                                               : BBM_MODE_BITMAP;
   switch (mode) {
     case BBM_MODE_BITMAP:
-      if (!idx->bin_blk_mat) return fail(BBM_EINVAL, "bbm_attn_fwd: BITMAP mode needs idx->bin_blk_mat");
+      if (!idx->bin_blk_mat) return fail(BBM_EINVAL, "%s: BITMAP mode needs idx->bin_blk_mat", fn);
       break;
     case BBM_MODE_RUNS:
       if (!idx->bin_blk_mat || !idx->offset || !idx->total_ones || !idx->nz_lo || !idx->nz_hi)
-        return fail(BBM_EINVAL, "bbm_attn_fwd: RUNS mode needs bin_blk_mat, offset, total_ones, nz_lo, nz_hi");
+        return fail(BBM_EINVAL, "%s: RUNS mode needs bin_blk_mat, offset, total_ones, nz_lo, nz_hi", fn);
       break;
     case BBM_MODE_LIST:
       if (!idx->row_ptr || !idx->col_idx || !idx->sched)
-        return fail(BBM_EINVAL, "bbm_attn_fwd: LIST mode needs row_ptr, col_idx and sched");
+        return fail(BBM_EINVAL, "%s: LIST mode needs row_ptr, col_idx and sched", fn);
       break;
     case BBM_MODE_DENSE_BASELINE:
       break;
     default:
-      return fail(BBM_EINVAL, "bbm_attn_fwd: unknown mode %d", mode);
+      return fail(BBM_EINVAL, "%s: unknown mode %d", fn, mode);
   }
-  if (nbr * nbc >= (1ll << 31) || B * H * nbr >= (1ll << 31) || N >= (1ll << 31))
-    return fail(BBM_EUNSUPPORTED, "bbm_attn_fwd: problem too large for 32-bit tile counters");
+  if (nbr * nbc >= (1ll << 31) || B * H * nbr >= (1ll << 31) || N >= (1ll << 31) || Nk >= (1ll << 31))
+    return fail(BBM_EUNSUPPORTED, "%s: problem too large for 32-bit tile counters", fn);
   const size_t need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx->Br, idx->Bc, mode);
   if (need > 0 && (!workspace || workspace_bytes < need))
-    return fail(BBM_EWORKSPACE, "bbm_attn_fwd: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
-  if (need > 0 && !aligned(workspace, 16)) return fail(BBM_EINVAL, "bbm_attn_fwd: workspace must be 16-byte aligned");
+    return fail(BBM_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
+  if (need > 0 && !aligned(workspace, 16)) return fail(BBM_EINVAL, "%s: workspace must be 16-byte aligned", fn);
 
   AttnParams P;
   P.q = static_cast<const __bf16*>(q);
@@ -701,11 +704,12 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
   P.row_ptr = idx->row_ptr;
   P.col_idx = idx->col_idx;
   P.N = N;
+  P.Nk = Nk;
   P.H = (int32_t)H;
   P.Mb = (int32_t)Mb;
   P.nbr = (int32_t)nbr;
   P.nbc = (int32_t)nbc;
-  P.W = (int32_t)ceil_div(N, 64);
+  P.W = (int32_t)ceil_div(Nk, 64);
   P.total_wgs = (int32_t)(B * H * nbr);
   P.mode = mode;
   P.scale = softmax_scale;
@@ -725,4 +729,19 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q
   if (idx->Br == 64) return launch<128, 2>(P, Mb, workspace, s);
   if (idx->Br == 128) return launch<128, 4>(P, Mb, workspace, s);
   return launch<128, 8>(P, Mb, workspace, s);
+}
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H,
+                            int64_t N, int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask,
+                            const bbm_index* idx, int mode, void* workspace, size_t workspace_bytes, void* stream) {
+  return attn_fwd_impl("bbm_attn_fwd", q, k, v, o, lse, B, H, N, N, d, softmax_scale, Mb, packed_mask, idx, mode, workspace, workspace_bytes, stream);
+}
+
+extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd_rect(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B,
+                                 int64_t H, int64_t Nq, int64_t Nk, int d, float softmax_scale, int64_t Mb,
+                                 const uint64_t* packed_mask, const bbm_index* idx, int mode, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  return attn_fwd_impl("bbm_attn_fwd_rect", q, k, v, o, lse, B, H, Nq, Nk, d, softmax_scale, Mb, packed_mask, idx, mode, workspace, workspace_bytes,
+                       stream);
 }

@@ -36,7 +36,7 @@ __device__ __forceinline__ uint32_t load_bits16(const uint8_t* row, int64_t col,
 }
 
 template <bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* __restrict__ mask, int64_t N,
+__global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* __restrict__ mask, int64_t Nr, int64_t N,
                                                                 int64_t row_stride, int Br, int Bc, int64_t nbr,
                                                                 int64_t nbc, uint8_t* __restrict__ blk_class,
                                                                 uint8_t* __restrict__ bin_blk_mat,
@@ -48,9 +48,9 @@ __global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* _
   const int64_t c0 = (int64_t)blockIdx.x * kColsPerWG;
   const int64_t i = blockIdx.y, m = blockIdx.z;
   const int64_t r0 = i * Br;
-  const int rows = (int)((r0 + Br <= N) ? Br : (N - r0));  // real (unpadded) rows of this block row
+  const int rows = (int)((r0 + Br <= Nr) ? Br : (Nr - r0));  // real (unpadded) rows of this block row (Nr mask rows, N columns)
   const int64_t col = c0 + 16 * lane;
-  const uint8_t* base = mask + (m * N + r0) * row_stride;
+  const uint8_t* base = mask + (m * Nr + r0) * row_stride;
   const int BrP = Br + 1;  // padded row count: consecutive words land in different LDS banks
 
   uint32_t any16 = 0, all16 = 0xffffu;
@@ -115,33 +115,46 @@ __global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* _
     const uint64_t* stage64 = reinterpret_cast<const uint64_t*>(stage);
     for (int t = threadIdx.x; t < kWordsPerWG * rows; t += kThreads) {
       const int wl = t / rows, rl = t - wl * rows;
-      if (w0 + wl < W) packed[(m * W + w0 + wl) * N + r0 + rl] = stage64[wl * BrP + rl];
+      if (w0 + wl < W) packed[(m * W + w0 + wl) * Nr + r0 + rl] = stage64[wl * BrP + rl];
     }
   }
 }
 
 }  // namespace
 
-extern "C" __attribute__((visibility("default"))) int bbm_build_block_mask(const uint8_t* mask, int64_t Mb, int64_t N, int64_t row_stride_bytes, int Br,
-                                    int Bc, uint8_t* blk_class, uint8_t* bin_blk_mat, uint64_t* packed_mask,
-                                    void* stream) {
+namespace {
+int build_block_mask_impl(const char* fn, const uint8_t* mask, int64_t Mb, int64_t Nq, int64_t Nk, int64_t row_stride_bytes, int Br, int Bc,
+                          uint8_t* blk_class, uint8_t* bin_blk_mat, uint64_t* packed_mask, void* stream) {
   using namespace bbm;
   clear_error();
-  if (!mask || !blk_class) return fail(BBM_EINVAL, "bbm_build_block_mask: mask and blk_class must not be NULL");
-  if (Mb < 1 || N < 1) return fail(BBM_EINVAL, "bbm_build_block_mask: Mb=%lld, N=%lld must be >= 1", (long long)Mb, (long long)N);
-  if (row_stride_bytes < N) return fail(BBM_EINVAL, "bbm_build_block_mask: row_stride_bytes=%lld < N=%lld", (long long)row_stride_bytes, (long long)N);
-  if (Br < 1 || Br > kMaxBr) return fail(BBM_EUNSUPPORTED, "bbm_build_block_mask: Br=%d outside [1, %d]", Br, kMaxBr);
-  if (Bc != 16 && Bc != 32 && Bc != 64 && Bc != 128 && Bc != 256)
-    return fail(BBM_EUNSUPPORTED, "bbm_build_block_mask: Bc=%d not in {16,32,64,128,256}", Bc);
-  if (packed_mask && !aligned(packed_mask, 8)) return fail(BBM_EINVAL, "bbm_build_block_mask: packed_mask must be 8-byte aligned");
-  const int64_t nbr = ceil_div(N, Br), nbc = ceil_div(N, Bc);
-  if (nbr > 65535 || Mb > 65535) return fail(BBM_EUNSUPPORTED, "bbm_build_block_mask: nbr=%lld or Mb=%lld exceeds 65535", (long long)nbr, (long long)Mb);
-  dim3 grid((unsigned)ceil_div(N, kColsPerWG), (unsigned)nbr, (unsigned)Mb);
+  if (!mask || !blk_class) return fail(BBM_EINVAL, "%s: mask and blk_class must not be NULL", fn);
+  if (Mb < 1 || Nq < 1 || Nk < 1)
+    return fail(BBM_EINVAL, "%s: Mb=%lld, rows=%lld, columns=%lld must be >= 1", fn, (long long)Mb, (long long)Nq, (long long)Nk);
+  if (row_stride_bytes < Nk) return fail(BBM_EINVAL, "%s: row_stride_bytes=%lld < columns=%lld", fn, (long long)row_stride_bytes, (long long)Nk);
+  if (Br < 1 || Br > kMaxBr) return fail(BBM_EUNSUPPORTED, "%s: Br=%d outside [1, %d]", fn, Br, kMaxBr);
+  if (Bc != 16 && Bc != 32 && Bc != 64 && Bc != 128 && Bc != 256) return fail(BBM_EUNSUPPORTED, "%s: Bc=%d not in {16,32,64,128,256}", fn, Bc);
+  if (packed_mask && !aligned(packed_mask, 8)) return fail(BBM_EINVAL, "%s: packed_mask must be 8-byte aligned", fn);
+  const int64_t nbr = ceil_div(Nq, Br), nbc = ceil_div(Nk, Bc);
+  if (nbr > 65535 || Mb > 65535) return fail(BBM_EUNSUPPORTED, "%s: nbr=%lld or Mb=%lld exceeds 65535", fn, (long long)nbr, (long long)Mb);
+  dim3 grid((unsigned)ceil_div(Nk, kColsPerWG), (unsigned)nbr, (unsigned)Mb);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool fast = aligned(mask, 16) && (row_stride_bytes % 16 == 0);
   if (fast)
-    block_reduce_kernel<true><<<grid, kThreads, 0, s>>>(mask, N, row_stride_bytes, Br, Bc, nbr, nbc, blk_class, bin_blk_mat, packed_mask);
+    block_reduce_kernel<true><<<grid, kThreads, 0, s>>>(mask, Nq, Nk, row_stride_bytes, Br, Bc, nbr, nbc, blk_class, bin_blk_mat, packed_mask);
   else
-    block_reduce_kernel<false><<<grid, kThreads, 0, s>>>(mask, N, row_stride_bytes, Br, Bc, nbr, nbc, blk_class, bin_blk_mat, packed_mask);
-  return launch_status("bbm_build_block_mask");
+    block_reduce_kernel<false><<<grid, kThreads, 0, s>>>(mask, Nq, Nk, row_stride_bytes, Br, Bc, nbr, nbc, blk_class, bin_blk_mat, packed_mask);
+  return launch_status(fn);
+}
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) int bbm_build_block_mask(const uint8_t* mask, int64_t Mb, int64_t N, int64_t row_stride_bytes, int Br,
+                                    int Bc, uint8_t* blk_class, uint8_t* bin_blk_mat, uint64_t* packed_mask,
+                                    void* stream) {
+  return build_block_mask_impl("bbm_build_block_mask", mask, Mb, N, N, row_stride_bytes, Br, Bc, blk_class, bin_blk_mat, packed_mask, stream);
+}
+
+extern "C" __attribute__((visibility("default"))) int bbm_build_block_mask_rect(const uint8_t* mask, int64_t Mb, int64_t Nq, int64_t Nk,
+                                         int64_t row_stride_bytes, int Br, int Bc, uint8_t* blk_class,
+                                         uint8_t* bin_blk_mat, uint64_t* packed_mask, void* stream) {
+  return build_block_mask_impl("bbm_build_block_mask_rect", mask, Mb, Nq, Nk, row_stride_bytes, Br, Bc, blk_class, bin_blk_mat, packed_mask, stream);
 }

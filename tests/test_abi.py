@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported(bbm):
     assert names == {"bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs",
                      "bbm_build_sparse_index", "bbm_build_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes",
                      "bbm_attn_fwd", "bbm_build_col_index", "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes",
-                     "bbm_attn_bwd"}
+                     "bbm_attn_bwd", "bbm_build_block_mask_rect", "bbm_attn_fwd_rect"}
     raw = C.CDLL(bbm.library_path())
     for n in names:
         assert getattr(raw, n) is not None
@@ -33,7 +33,8 @@ def test_binding_has_the_same_names(bbm):
     for n in ("bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs", "bbm_build_sparse_index",
               "bbm_build_index",
               "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd", "bbm_build_col_index",
-              "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd"):
+              "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd", "bbm_build_block_mask_rect",
+              "bbm_attn_fwd_rect"):
         assert callable(getattr(bbm, n))
 
 
@@ -150,3 +151,18 @@ def test_attn_bwd_and_col_index_reject_bad_arguments(bbm):
     assert _bwd(bbm, full, ws=None) == bbm.BBM_EWORKSPACE
     assert _bwd(bbm, full, ws_bytes=16) == bbm.BBM_EWORKSPACE
     assert _bwd(bbm, full, ws=C.c_void_p(0x1008)) == bbm.BBM_EINVAL
+
+
+def test_rectangular_entry_points_reject_bad_arguments(bbm):
+    L = bbm.lib
+    assert L.bbm_build_block_mask_rect(None, 1, 64, 128, 128, 64, 64, FAKE, None, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_block_mask_rect(FAKE, 1, 64, 0, 128, 64, 64, FAKE, None, None, None) == bbm.BBM_EINVAL
+    assert L.bbm_build_block_mask_rect(FAKE, 1, 64, 128, 127, 64, 64, FAKE, None, None, None) == bbm.BBM_EINVAL   # stride < columns
+    assert "bbm_build_block_mask_rect" in bbm.bbm_last_error()
+    idx = _idx(bbm, N=256)                                     # nbr = 2, nbc = 4: fits Nq = 256, Nk = 256 only
+    rect = lambda Nq, Nk, **kw: L.bbm_attn_fwd_rect(kw.get("q", FAKE), FAKE, FAKE, FAKE, None, 1, 1, Nq, Nk, 64, 0.125, 1, FAKE,
+                                                    C.byref(idx), bbm.BBM_MODE_DENSE_BASELINE, None, 0, None)
+    assert rect(256, 0) == bbm.BBM_EINVAL
+    assert rect(256, 512) == bbm.BBM_EINVAL and "does not match" in bbm.bbm_last_error()
+    assert rect(512, 256) == bbm.BBM_EINVAL
+    assert rect(256, 256, q=None) == bbm.BBM_EINVAL and "bbm_attn_fwd_rect" in bbm.bbm_last_error()

@@ -221,3 +221,49 @@ def test_cut_rows_with_a_mask_shared_by_the_batch(Br):
     o1, l1 = _gpu_attn(cfg, Br, "LIST")              # merging in part order: the same bits on every run
     o2, l2 = _gpu_attn(cfg, Br, "LIST")
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(l1, l2)
+
+
+def _gpu_attn_rect(q, k, v, mask, Br, mode, check_index=False):
+    bbm = _bbm()
+    idx = bbm.build_index(torch.from_numpy(np.ascontiguousarray(mask)).cuda(), Br, 64)
+    if check_index:
+        from gpu_util import assert_index_equal, index_to_numpy
+        assert_index_equal(index_to_numpy(idx), mask, Br, 64)
+    o, lse = bbm.bbm_attn_fwd_rect(bf16_tensor(q), bf16_tensor(k), bf16_tensor(v), idx, mode=_mode(bbm, mode))
+    torch.cuda.synchronize()
+    return o, lse
+
+
+@pytest.mark.parametrize("Br", [64, 128, 256])
+def test_tree_verification_at_decode_time_new_queries_against_the_cache(Br):
+    """Nq != Nk: the 200 candidate-tree tokens are the only queries; keys are the 1024-token prefix plus the tree
+    (the rows of the square tree-verification mask that belong to the tree)."""
+    B, H, d, prefix, tree = 2, 2, 128, 1024, 200
+    full = masks.tree_verification(prefix, masks.random_subtree([10, 5, 3, 2], tree, 77))      # [1, 1224, 1224]
+    mask = np.ascontiguousarray(full[:, prefix:])                                              # [1, 200, 1224]
+    q = make_qkv(B, H, tree, d, seed=5)[0]
+    _, k, v = make_qkv(B, H, prefix + tree, d, seed=6)
+    O_ref, lse_ref = oracle.masked_attention(q, k, v, mask)
+    for mode in MODES:
+        print(f"decode-time tree Br={Br} mode={mode}", flush=True)
+        o, lse = _gpu_attn_rect(q, k, v, mask, Br, mode, check_index=(mode == "LIST"))
+        assert o.shape == (B, H, tree, d) and lse.shape == (B, H, tree)
+        assert_attention_close(o, lse, O_ref, lse_ref)
+
+
+@pytest.mark.parametrize("Nq,Nk", [(1, 65), (77, 1000), (300, 130), (129, 64), (64, 4097)])
+@pytest.mark.parametrize("d", [64, 128])
+def test_rectangular_ragged_sizes_with_empty_rows(Nq, Nk, d):
+    B, H = 2, 2
+    q = make_qkv(B, H, Nq, d, seed=Nq + d)[0]
+    _, k, v = make_qkv(B, H, Nk, d, seed=Nk + d)
+    side = 64 * (-(-max(Nq, Nk) // 64))
+    m = masks.random_blocks(side, Nq + Nk, blk=32, p_empty=0.4, p_full=0.3)[0][:Nq, :Nk].copy()
+    m[np.random.default_rng(Nq).integers(0, Nq, size=max(1, Nq // 10))] = 0
+    mask = np.stack([m, np.roll(m, 5, axis=1)])
+    O_ref, lse_ref = oracle.masked_attention(q, k, v, mask)
+    for Br in (64, 128, 256):
+        for mode in MODES:
+            print(f"rect Nq={Nq} Nk={Nk} d={d} Br={Br} mode={mode}", flush=True)
+            o, lse = _gpu_attn_rect(q, k, v, mask, Br, mode, check_index=(mode == "BITMAP"))
+            assert_attention_close(o, lse, O_ref, lse_ref)

@@ -24,6 +24,9 @@ CONFIGS = {
     "C2b": dict(B=4, H=16, N=4096, d=64, Mb=4, family="packed_bidir"),
     "C4w": dict(B=1, H=16, N=16384, d=64, Mb=1, family="window"),
     "C4d": dict(B=1, H=16, N=16384, d=64, Mb=1, family="dilated"),
+    # tree verification at decode time: only the 256 candidate-tree tokens are queries (Nq), the keys are the 1024-token
+    # prefix plus the tree (N): the last Nq rows of the mask of C3
+    "C3q": dict(B=8, H=32, N=1280, d=128, Mb=1, family="tree", Nq=256),
 }
 _IDS = {k: i for i, k in enumerate(CONFIGS)}
 
@@ -72,6 +75,10 @@ def make_config(name: str, with_qkv: bool = True, **override):
     cfg["mask"] = make_mask(cfg["family"], cfg["N"], cfg["Mb"], seed)
     if with_qkv:
         cfg["q"], cfg["k"], cfg["v"] = make_qkv(cfg["B"], cfg["H"], cfg["N"], cfg["d"], seed + 100)
+    if "Nq" in cfg:   # the last Nq tokens are the queries: mask [Mb, Nq, N], q [B, H, Nq, d]
+        cfg["mask"] = np.ascontiguousarray(cfg["mask"][:, cfg["N"] - cfg["Nq"]:])
+        if with_qkv:
+            cfg["q"] = np.ascontiguousarray(cfg["q"][:, :, cfg["N"] - cfg["Nq"]:])
     return cfg
 
 
