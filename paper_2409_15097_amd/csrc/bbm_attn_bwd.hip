@@ -190,7 +190,7 @@ __device__ __forceinline__ int logical_wg(int wg, int total) {
 // row's last part adds the parts up in part order and writes the row, and the row's own work-group only writes the
 // statistics.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P) {
+__global__ __launch_bounds__(NW * 64, D == 128 ? 2 : 1) void attn_bwd_dq_kernel(const BwdParams P) {
   using L = TL<D>;
   constexpr int NT = NW * 64;
   constexpr int BR = NW * 32;
@@ -220,6 +220,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P)
   const uint64_t* __restrict__ mrow;
   bf16x8 qf[KS], dof[KS];
   f32x16 s_init, dp_init, dq[DB];
+  float nl_lane = 0.0f, nd_lane = 0.0f;
 
   // this lane's query: Q * scale * log2(e) and dO as B operands, D = <dO, O>, the negated statistics
   auto begin_item = [&](bool write_stats) {
@@ -253,9 +254,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P)
       P.nl2[(int64_t)bh * N + qrow] = nl;
       P.ndelta[(int64_t)bh * N + qrow] = -delta;
     }
-    for (int e = 0; e < 16; ++e) {
-      s_init[e] = nl;
-      dp_init[e] = -delta;
+    nl_lane = nl;
+    nd_lane = -delta;
+    if constexpr (D == 64) {
+      for (int e = 0; e < 16; ++e) {
+        s_init[e] = nl;
+        dp_init[e] = -delta;
+      }
     }
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -286,43 +291,41 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdParams P)
     if (e1 != kNoTile) request(e1, k_oth, v_oth);
     // a partial tile in which none of this wave's 32 queries sees a key contributes exact zeros: skip it
     if ((e0 >> 31) != 0 || __ballot(mw != 0ull) != 0ull) {
-      f32x16 s[2], dp[2];
+      // the two 32-key halves of the tile one after the other (at D = 128 their accumulators do not fit side by side)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) s[kb] = s_init;
+      for (int kb = 0; kb < 2; ++kb) {
+        f32x16 s, dp;
+        if constexpr (D == 64) {
+          s = s_init;
+          dp = dp_init;
+        } else {  // D = 128: registers are short, the start values are kept as two scalars per lane
+          for (int e = 0; e < 16; ++e) {
+            s[e] = nl_lane;
+            dp[e] = nd_lane;
+          }
+        }
 #pragma unroll
-      for (int t = 0; t < KS; ++t)
+        for (int t = 0; t < KS; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(k_cur, kb, t), qf[t], s, 0, 0, 0);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(k_cur, kb, t), qf[t], s[kb], 0, 0, 0);
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) dp[kb] = dp_init;
-#pragma unroll
-      for (int t = 0; t < KS; ++t)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) dp[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(v_cur, kb, t), dof[t], dp[kb], 0, 0, 0);
-
-      // element mask where the list cannot rule out zeros: masked scores become -inf, i.e. probability 0
-      if ((e0 >> 31) == 0) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int t = 0; t < KS; ++t) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(v_cur, kb, t), dof[t], dp, 0, 0, 0);
+        // element mask where the list cannot rule out zeros: masked scores become -inf, i.e. probability 0
+        if ((e0 >> 31) == 0) {
           const uint32_t w = (uint32_t)(mw >> (32 * kb)) >> (4 * hh);
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int bit = 8 * (e / 4) + (e % 4);
             const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);
-            s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
+            s[e] = __uint_as_float((__float_as_uint(s[e]) & keep) | (0xff800000u & ~keep));
           }
         }
-      }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        bf16x8 dsf;
+        for (int u2 = 0; u2 < 2; ++u2) {
+          bf16x8 dsf;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float p = __builtin_amdgcn_exp2f(s[u / 2][8 * (u % 2) + e]);
-          dsf[e] = (__bf16)(p * dp[u / 2][8 * (u % 2) + e]);
+          for (int e = 0; e < 8; ++e) dsf[e] = (__bf16)(__builtin_amdgcn_exp2f(s[8 * u2 + e]) * dp[8 * u2 + e]);
+#pragma unroll
+          for (int db = 0; db < DB; ++db) dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(k_cur, 2 * kb + u2, db), dsf, dq[db], 0, 0, 0);
         }
-#pragma unroll
-        for (int db = 0; db < DB; ++db) dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(k_cur, u, db), dsf, dq[db], 0, 0, 0);
       }
     }
     e0 = e1;
