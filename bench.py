@@ -80,6 +80,9 @@ def visited_tiles(idx, B, H):
 
 def measure_mask(bbm, name, Br, warmup, steps, torch, backward=False):
     from workloads import make_config
+    if ":" in name:                      # "C0d128:256": this mask at another tile height than --Br
+        name, br = name.split(":")
+        Br = int(br)
     cfg = make_config(name)
     B, H, N, d, Mb = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["Mb"]
     Nq = cfg.get("Nq", N)                 # queries per head (N keys): differs only for the decode-time configuration
@@ -225,7 +228,7 @@ def main():
 
     main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch, not a.no_backward)
     rows = [main_res]
-    extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128,C2b,C4w,C4d,C3q" if a.masks == "all" else a.masks
+    extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128,C2b,C4w,C4d,C3q,C0d128:256,C0c128:256" if a.masks == "all" else a.masks
     for name in [m for m in extra.split(",") if m and m != a.workload]:
         r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch, not a.no_backward)
         rows.append(r)
