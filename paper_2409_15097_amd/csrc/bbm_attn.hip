@@ -326,8 +326,11 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     __bf16* const k_oth = PB ? k_s0 : k_s1;
     __bf16* const v_cur = PB ? v_s1 : v_s0;
     __bf16* const v_oth = PB ? v_s0 : v_s1;
+    // a partial tile in which none of this wave's 32 queries sees a key adds exact zeros: such a wave only takes part
+    // in the copies and barriers of the step
+    const bool live = (e0 >> 31) != 0 || __ballot(mw != 0ull) != 0ull;
     f32x16 s[2];
-    qk(k_cur, s);
+    if (live) qk(k_cur, s);
     // the next tile's copies are requested behind the first product: their address arithmetic runs while the matrix
     // pipe works (about 1 % on dense masks)
     if (e1 != kNoTile) {
@@ -336,61 +339,63 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       if ((e1 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e1) * N];
     }
 
-    // ---- element mask (only where the schedule cannot rule out zeros): keep s where the bit is set, else -inf
-    if ((e0 >> 31) == 0) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const uint32_t w = (uint32_t)(mw >> (32 * kb)) >> (4 * hh);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int bit = 8 * (e / 4) + (e % 4);
-          const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);  // all ones iff the bit is set
-          s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
+    if (live) {
+      // ---- element mask (only where the schedule cannot rule out zeros): keep s where the bit is set, else -inf
+      if ((e0 >> 31) == 0) {
+  #pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          const uint32_t w = (uint32_t)(mw >> (32 * kb)) >> (4 * hh);
+  #pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int bit = 8 * (e / 4) + (e % 4);
+            const uint32_t keep = (uint32_t)((int32_t)(w << (31 - bit)) >> 31);  // all ones iff the bit is set
+            s[kb][e] = __uint_as_float((__float_as_uint(s[kb][e]) & keep) | (0xff800000u & ~keep));
+          }
         }
       }
-    }
 
-    // ---- row maximum of this lane's query row
-    float mx = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
-    mx = partner_max(mx);
-    // The scores arrive relative to the reference (s = exponent - m_run).  The reference only moves when some row's
-    // maximum exceeds it by more than kLazy: softmax is invariant to the reference, probabilities stay <= 2^kLazy, and
-    // the rescale of O -- and here also the per-element subtraction -- is skipped on almost every tile.
-    if (__any(((m_run == -INFINITY) ? (mx > -INFINITY) : (mx > kLazy)) ? 1 : 0)) {
-      const float m_old = (m_run == -INFINITY) ? 0.0f : m_run;       // what the accumulators started from
-      const float m_new = fmaxf(m_run, m_old + mx);
-      const float m_fin = (m_new == -INFINITY) ? 0.0f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);
-      const float shift = m_fin - m_old;
-      l_run *= alpha;
-      m_run = m_new;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) s_init[e] = -m_fin;
-#pragma unroll
+      // ---- row maximum of this lane's query row
+      float mx = s[0][0];
+  #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
-        for (int e = 0; e < 16; ++e) s[kb][e] -= shift;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-        for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-    }
-
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      bf16x8 pf;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pf[e] = (__bf16)__builtin_amdgcn_exp2f(s[u / 2][8 * (u % 2) + e]);
-      // row sum of the ROUNDED probabilities (the same numbers the second product consumes), two per instruction
-#pragma unroll
-      for (int e = 0; e < 8; e += 2) {
-        const bf16x2 pair = {pf[e], pf[e + 1]};
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(pair, ones2, l_run, false);
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
+      mx = partner_max(mx);
+      // The scores arrive relative to the reference (s = exponent - m_run).  The reference only moves when some row's
+      // maximum exceeds it by more than kLazy: softmax is invariant to the reference, probabilities stay <= 2^kLazy, and
+      // the rescale of O -- and here also the per-element subtraction -- is skipped on almost every tile.
+      if (__any(((m_run == -INFINITY) ? (mx > -INFINITY) : (mx > kLazy)) ? 1 : 0)) {
+        const float m_old = (m_run == -INFINITY) ? 0.0f : m_run;       // what the accumulators started from
+        const float m_new = fmaxf(m_run, m_old + mx);
+        const float m_fin = (m_new == -INFINITY) ? 0.0f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);
+        const float shift = m_fin - m_old;
+        l_run *= alpha;
+        m_run = m_new;
+  #pragma unroll
+        for (int e = 0; e < 16; ++e) s_init[e] = -m_fin;
+  #pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+          for (int e = 0; e < 16; ++e) s[kb][e] -= shift;
+  #pragma unroll
+        for (int db = 0; db < DB; ++db)
+          for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
       }
-      // ---- O^T += V^T P^T
-#pragma unroll
-      for (int db = 0; db < DB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(v_cur, u, db), pf, oacc[db], 0, 0, 0);
+
+  #pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        bf16x8 pf;
+  #pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)__builtin_amdgcn_exp2f(s[u / 2][8 * (u % 2) + e]);
+        // row sum of the ROUNDED probabilities (the same numbers the second product consumes), two per instruction
+  #pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const bf16x2 pair = {pf[e], pf[e + 1]};
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(pair, ones2, l_run, false);
+        }
+        // ---- O^T += V^T P^T
+  #pragma unroll
+        for (int db = 0; db < DB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(v_cur, u, db), pf, oacc[db], 0, 0, 0);
+      }
     }
     e0 = e1;
     e1 = tiles_s[it + 2];
