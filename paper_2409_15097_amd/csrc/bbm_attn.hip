@@ -327,8 +327,9 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     __bf16* const v_cur = PB ? v_s1 : v_s0;
     __bf16* const v_oth = PB ? v_s0 : v_s1;
     // a partial tile in which none of this wave's 32 queries sees a key adds exact zeros: such a wave only takes part
-    // in the copies and barriers of the step
-    const bool live = (e0 >> 31) != 0 || __ballot(mw != 0ull) != 0ull;
+    // in the copies and barriers of the step (not in the dense-tile baseline, which stands for a kernel that knows
+    // nothing about the mask's structure)
+    const bool live = (e0 >> 31) != 0 || (!SCHED && P.mode == BBM_MODE_DENSE_BASELINE) || __ballot(mw != 0ull) != 0ull;
     f32x16 s[2];
     if (live) qk(k_cur, s);
     // the next tile's copies are requested behind the first product: their address arithmetic runs while the matrix
