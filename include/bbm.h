@@ -290,6 +290,44 @@ int bbm_attn_bwd(const void* q, const void* k, const void* v, const void* o, con
                  const uint64_t* packed_mask, const bbm_index* idx, void* workspace, size_t workspace_bytes,
                  void* stream);
 
+/*
+ * Reverse Cuthill-McKee reordering of a sparse mask (paper Sec. 4 "Binary Block Masking with Reverse Cuthill-McKee
+ * (RCM)": the mask is treated as the adjacency matrix of a graph and reordered so that fewer blocks are non-zero).
+ * The published algorithm with every choice fixed: the neighbours of node i are the non-zero entries of mask row i
+ * (the mask is read row-wise; the method assumes a symmetric mask), its degree their number; each connected component
+ * starts at its unvisited node of minimum degree (ties: smallest index); breadth-first, each level ordered by (position
+ * of the node's earliest parent in the ordering, degree, index); the ordering is reversed at the end.
+ *
+ *   mask             device in, uint8 [N][row_stride_bytes], one plane, row_stride_bytes >= N (16-byte aligned pointer
+ *                    and stride take the fast path).
+ *   perm             device out, int32 [N]: perm[k] = old index of the node placed at position k; the reordered mask is
+ *                    mask[perm][:, perm] (bbm_permute_mask), reordered Q/K/V rows are row perm[k] at position k
+ *                    (bbm_gather_rows), and O comes back with the inverse (bbm_gather_rows with inverse = 1).
+ *   workspace        device scratch of at least bbm_rcm_workspace_bytes(N) bytes (N*ceil(N/64)*8 for the packed rows
+ *                    plus 24*N), 16-byte aligned; needs no initialisation.
+ * N <= 65536.  The level walk runs in one work-group with no host round trip: time grows with the number of
+ * breadth-first levels and of connected components (each costs a scan over the N nodes).
+ * Errors: BBM_EINVAL, BBM_EUNSUPPORTED (N > 65536), BBM_EWORKSPACE, BBM_EHIP.
+ */
+size_t bbm_rcm_workspace_bytes(int64_t N);
+int bbm_rcm_order(const uint8_t* mask, int64_t N, int64_t row_stride_bytes, int32_t* perm, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+/*
+ * out[m][i][j] = mask[m][perm[i]][perm[j]] for Mb planes (uint8, out contiguous [Mb][N][N], out != mask).  N <= 65536.
+ * Entries of perm outside [0, N) are clamped.  Errors: BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EHIP.
+ */
+int bbm_permute_mask(const uint8_t* mask, int64_t Mb, int64_t N, int64_t row_stride_bytes, const int32_t* perm,
+                     uint8_t* out, void* stream);
+
+/*
+ * Rows of a bf16 tensor [BH][N][d] (d a multiple of 8, 16-byte aligned, out != in): inverse = 0 gathers,
+ * out[bh][k] = in[bh][perm[k]] (Q, K, V into the reordered problem); inverse = 1 scatters, out[bh][perm[k]] = in[bh][k]
+ * (O back to the original order).  Errors: BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EHIP.
+ */
+int bbm_gather_rows(const void* in, const int32_t* perm, void* out, int64_t BH, int64_t N, int d, int inverse,
+                    void* stream);
+
 #ifdef __cplusplus
 }
 #endif

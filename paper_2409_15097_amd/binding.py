@@ -69,6 +69,14 @@ def _load():
     L.bbm_attn_bwd.restype = ci
     L.bbm_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, C.c_float, i64, vp,
                                C.POINTER(_CIndex), vp, C.c_size_t, vp]
+    L.bbm_rcm_workspace_bytes.restype = C.c_size_t
+    L.bbm_rcm_workspace_bytes.argtypes = [i64]
+    L.bbm_rcm_order.restype = ci
+    L.bbm_rcm_order.argtypes = [vp, i64, i64, vp, vp, C.c_size_t, vp]
+    L.bbm_permute_mask.restype = ci
+    L.bbm_permute_mask.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    L.bbm_gather_rows.restype = ci
+    L.bbm_gather_rows.argtypes = [vp, vp, vp, i64, i64, ci, ci, vp]
     return L
 
 
@@ -320,3 +328,47 @@ def bbm_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Ten
                             B, H, N, d, softmax_scale, idx.Mb, _ptr(idx.packed_mask), C.byref(cs), _ptr(workspace),
                             workspace.numel(), _stream(stream)))
     return dq, dk, dv
+
+
+def bbm_rcm_workspace_bytes(N: int) -> int:
+    return int(lib.bbm_rcm_workspace_bytes(N))
+
+
+def bbm_rcm_order(mask2d: torch.Tensor, perm: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                  stream=None) -> torch.Tensor:
+    """mask2d: uint8 CUDA tensor [N,N] (row stride may exceed N).  Returns perm int32 [N]: old index of the node at
+    each new position (reverse Cuthill-McKee)."""
+    assert mask2d.is_cuda and mask2d.dtype == torch.uint8 and mask2d.dim() == 2 and mask2d.stride(1) == 1
+    N = mask2d.shape[0]
+    assert mask2d.shape[1] == N
+    if perm is None:
+        perm = torch.empty(N, dtype=torch.int32, device=mask2d.device)
+    if workspace is None:
+        workspace = torch.empty(max(16, bbm_rcm_workspace_bytes(N)), dtype=torch.uint8, device=mask2d.device)
+    _check(lib.bbm_rcm_order(_ptr(mask2d), N, mask2d.stride(0), _ptr(perm), _ptr(workspace), workspace.numel(),
+                             _stream(stream)))
+    return perm
+
+
+def bbm_permute_mask(mask: torch.Tensor, perm: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None):
+    """mask: uint8 CUDA tensor [Mb,N,N]; returns mask[:, perm][:, :, perm] as a new contiguous tensor."""
+    assert mask.is_cuda and mask.dtype == torch.uint8 and mask.dim() == 3 and mask.stride(2) == 1
+    Mb, N, _ = mask.shape
+    assert mask.shape[2] == N and (Mb == 1 or mask.stride(0) == N * mask.stride(1))
+    assert perm.dtype == torch.int32 and perm.is_contiguous() and perm.numel() == N
+    if out is None:
+        out = torch.empty((Mb, N, N), dtype=torch.uint8, device=mask.device)
+    _check(lib.bbm_permute_mask(_ptr(mask), Mb, N, mask.stride(1), _ptr(perm), _ptr(out), _stream(stream)))
+    return out
+
+
+def bbm_gather_rows(x: torch.Tensor, perm: torch.Tensor, inverse: bool = False, out: Optional[torch.Tensor] = None,
+                    stream=None) -> torch.Tensor:
+    """x: bf16 CUDA tensor [B,H,N,d] contiguous.  inverse=False: out[.., k, :] = x[.., perm[k], :]; True: the scatter."""
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous() and x.dim() == 4
+    B, H, N, d = x.shape
+    assert perm.dtype == torch.int32 and perm.is_contiguous() and perm.numel() == N
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib.bbm_gather_rows(_ptr(x), _ptr(perm), _ptr(out), B * H, N, d, 1 if inverse else 0, _stream(stream)))
+    return out

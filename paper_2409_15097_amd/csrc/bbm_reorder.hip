@@ -1,0 +1,282 @@
+// Reverse Cuthill-McKee reordering of a sparse attention mask on the GPU (paper Sec. 4 "Binary Block Masking with
+// Reverse Cuthill-McKee (RCM)": the mask is treated as a graph and reordered so that fewer blocks are non-zero), and the
+// gathers that apply the permutation to the mask and to Q/K/V/O rows.
+//
+// The ordering is the published algorithm with every choice fixed (the library header states them): neighbours of node
+// i are the non-zero entries of mask row i, a component starts at its unvisited node of minimum degree (ties: smallest
+// index), each breadth-first level is ordered by (position of the earliest parent, degree, index), the result is
+// reversed.  Two kernels: a parallel one packs the mask rows to bits and counts degrees; a single work-group then
+// walks the levels -- every node's row is scanned exactly once, when the node is in the frontier -- with no host
+// round trip and no grid-wide barrier: its loops end when every node has been placed.
+#include "bbm_internal.h"
+
+#include <climits>
+
+namespace {
+
+constexpr int kMaxNodes = 65536;            // visited set and one mask row must fit in LDS
+constexpr int kOrderThreads = 1024;
+constexpr int kPackThreads = 256;
+
+// 4 mask bytes -> 4 bits (bit t = byte t non-zero).
+__device__ __forceinline__ uint32_t nz_nibble(uint32_t x) {
+  uint32_t y = (((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u;
+  return (((y >> 7) * 0x00204081u) >> 21) & 0xfu;
+}
+
+// One work-group per mask row: bits[row][w] (row-major, bits past N zero), degree[row], parent_pos[row] = "none".
+__global__ __launch_bounds__(kPackThreads) void rcm_pack_kernel(const uint8_t* __restrict__ mask, int N, int64_t row_stride, int W,
+                                                                uint64_t* __restrict__ bits, int32_t* __restrict__ degree,
+                                                                int32_t* __restrict__ parent_pos) {
+  __shared__ int red_s[kPackThreads / 64];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const uint8_t* __restrict__ src = mask + (int64_t)row * row_stride;
+  const bool vec = ((reinterpret_cast<uintptr_t>(mask) | (uintptr_t)row_stride) & 15) == 0;
+  int count = 0;
+  for (int w = tid; w < W; w += kPackThreads) {
+    uint64_t word = 0;
+    const int c0 = 64 * w;
+    if (vec && c0 + 64 <= N) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint4 x = *reinterpret_cast<const uint4*>(src + c0 + 16 * t);
+        const uint64_t b16 = nz_nibble(x.x) | (nz_nibble(x.y) << 4) | (nz_nibble(x.z) << 8) | (nz_nibble(x.w) << 12);
+        word |= b16 << (16 * t);
+      }
+    } else {
+      for (int t = 0; t < 64; ++t)
+        if (c0 + t < N && src[c0 + t] != 0) word |= 1ull << t;
+    }
+    bits[(int64_t)row * W + w] = word;
+    count += __popcll(word);
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) count += __shfl_xor(count, d);
+  if (lane == 0) red_s[tid >> 6] = count;
+  __syncthreads();
+  if (tid == 0) {
+    int total = 0;
+    for (int w = 0; w < kPackThreads / 64; ++w) total += red_s[w];
+    degree[row] = total;
+    parent_pos[row] = INT_MAX;
+  }
+}
+
+// The level walk, one work-group.  Global arrays written by some threads and read by others are separated by an
+// agent-scope fence and a barrier.
+__global__ __launch_bounds__(kOrderThreads) void rcm_order_kernel(const uint64_t* __restrict__ bits, const int32_t* __restrict__ degree,
+                                                                  int32_t* parent_pos, int32_t* order, int32_t* cand, uint64_t* keys,
+                                                                  int N, int W, int32_t* __restrict__ perm) {
+  __shared__ uint64_t visited[kMaxNodes / 64];
+  __shared__ unsigned long long min_s[kOrderThreads / 64];
+  __shared__ int count_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  auto sync_global = [&]() {
+    __threadfence();
+    __syncthreads();
+  };
+  for (int w = tid; w < kMaxNodes / 64; w += kOrderThreads) {
+    uint64_t v = 0;                                       // nodes past N count as visited
+    if (w >= W) v = ~0ull;
+    else if (w == W - 1 && (N & 63)) v = ~0ull << (N & 63);
+    visited[w] = v;
+  }
+  __syncthreads();
+  int n_done = 0;
+  while (n_done < N) {
+    // ---- start of a component: the unvisited node of minimum (degree, index)
+    unsigned long long best = ~0ull;
+    for (int i = tid; i < N; i += kOrderThreads)
+      if (!((visited[i >> 6] >> (i & 63)) & 1ull)) best = min(best, ((unsigned long long)(uint32_t)degree[i] << 32) | (uint32_t)i);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) best = min(best, (unsigned long long)__shfl_xor(best, d));
+    if (lane == 0) min_s[wave] = best;
+    __syncthreads();
+    best = min_s[0];
+    for (int w = 1; w < kOrderThreads / 64; ++w) best = min(best, min_s[w]);
+    const int start = (int)(best & 0xffffffffull);
+    if (tid == 0) {
+      order[n_done] = start;
+      visited[start >> 6] |= 1ull << (start & 63);
+      count_s = 0;
+    }
+    int lvl_lo = n_done, lvl_hi = n_done + 1;
+    n_done += 1;
+    sync_global();
+    // ---- breadth-first levels of this component
+    while (lvl_lo < lvl_hi) {
+      // expand: every frontier node scans its row once; an unvisited neighbour is claimed by its earliest parent
+      const int64_t total = (int64_t)(lvl_hi - lvl_lo) * W;
+      for (int64_t x0 = tid; x0 < total; x0 += 4 * kOrderThreads) {
+        uint64_t word[4];
+        int f[4], w[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int64_t x = x0 + (int64_t)t * kOrderThreads;
+          word[t] = 0;
+          f[t] = w[t] = 0;
+          if (x < total) {
+            f[t] = lvl_lo + (int)(x / W);
+            w[t] = (int)(x % W);
+            word[t] = bits[(int64_t)order[f[t]] * W + w[t]] & ~visited[w[t]];
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          uint64_t b = word[t];
+          while (b) {
+            const int v = 64 * w[t] + __builtin_ctzll(b);
+            b &= b - 1;
+            if (atomicMin(&parent_pos[v], f[t]) == INT_MAX) cand[atomicAdd(&count_s, 1)] = v;
+          }
+        }
+      }
+      sync_global();
+      const int L = count_s;
+      // sort keys: (position of the earliest parent, degree, index)
+      for (int c = tid; c < L; c += kOrderThreads) {
+        const int v = cand[c];
+        keys[c] = ((uint64_t)(uint32_t)parent_pos[v] << 40) | ((uint64_t)(uint32_t)degree[v] << 20) | (uint64_t)(uint32_t)v;
+      }
+      sync_global();
+      // rank by counting (keys are distinct), place, mark visited
+      for (int c = tid; c < L; c += kOrderThreads) {
+        const uint64_t k = keys[c];
+        int r = 0;
+        for (int j = 0; j < L; ++j) r += keys[j] < k ? 1 : 0;
+        const int v = (int)(k & 0xfffffull);
+        order[n_done + r] = v;
+        atomicOr(reinterpret_cast<unsigned long long*>(&visited[v >> 6]), 1ull << (v & 63));
+      }
+      if (tid == 0) count_s = 0;
+      lvl_lo = lvl_hi;
+      lvl_hi = n_done + L;
+      n_done += L;
+      sync_global();
+    }
+  }
+  // the ordering reversed
+  for (int k = tid; k < N; k += kOrderThreads) perm[k] = order[N - 1 - k];
+}
+
+// out[m][i][j] = mask[m][perm[i]][perm[j]]: one work-group per output row stages the source row in LDS.
+__global__ __launch_bounds__(256) void permute_mask_kernel(const uint8_t* __restrict__ mask, int N, int64_t row_stride,
+                                                           const int32_t* __restrict__ perm, uint8_t* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) uint8_t row_s[kMaxNodes];
+  const int i = blockIdx.x, tid = threadIdx.x;
+  const int64_t m = blockIdx.y;
+  // entries of perm outside [0, N) are clamped: a wrong permutation gives a wrong mask, never a wild access
+  const uint8_t* __restrict__ src = mask + (m * N + min(max(perm[i], 0), N - 1)) * row_stride;
+  const bool vec = ((reinterpret_cast<uintptr_t>(mask) | (uintptr_t)row_stride) & 15) == 0;
+  if (vec) {
+    for (int c = 16 * tid; c < N; c += 16 * 256) {
+      if (c + 16 <= N) *reinterpret_cast<uint4*>(row_s + c) = *reinterpret_cast<const uint4*>(src + c);
+      else
+        for (int t = 0; c + t < N; ++t) row_s[c + t] = src[c + t];
+    }
+  } else {
+    for (int c = tid; c < N; c += 256) row_s[c] = src[c];
+  }
+  __syncthreads();
+  uint8_t* __restrict__ dst = out + (m * N + i) * (int64_t)N;
+  for (int j = tid; j < N; j += 256) dst[j] = row_s[min(max(perm[j], 0), N - 1)];
+}
+
+// Rows of a [BH][N][d] bf16 tensor: gather (out[k] = in[perm[k]]) or scatter (out[perm[k]] = in[k]); 16 bytes per lane.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ in, const int32_t* __restrict__ perm, uint4* __restrict__ out,
+                                                          int64_t N, int chunks, int64_t total, int inverse) {
+  const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (bh, k, chunk)
+  if (x >= total) return;
+  const int ch = (int)(x % chunks);
+  const int64_t k = (x / chunks) % N, bh = x / chunks / N;
+  const int64_t p = min<int64_t>(max(perm[k], 0), N - 1);  // clamped: never a wild access
+  const int64_t from = inverse ? k : p, to = inverse ? p : k;
+  out[(bh * N + to) * chunks + ch] = in[(bh * N + from) * chunks + ch];
+}
+
+inline size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+struct RcmLayout {
+  size_t bits, degree, parent, order, cand, keys, total;
+  explicit RcmLayout(int64_t N) {
+    const size_t W = (size_t)((N + 63) / 64);
+    size_t o = 0;
+    bits = o;
+    o += round256((size_t)N * W * 8);
+    degree = o;
+    o += round256((size_t)N * 4);
+    parent = o;
+    o += round256((size_t)N * 4);
+    order = o;
+    o += round256((size_t)N * 4);
+    cand = o;
+    o += round256((size_t)N * 4);
+    keys = o;
+    o += round256((size_t)N * 8);
+    total = o;
+  }
+};
+
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) size_t bbm_rcm_workspace_bytes(int64_t N) {
+  if (N < 1 || N > kMaxNodes) return 0;
+  return RcmLayout(N).total;
+}
+
+extern "C" __attribute__((visibility("default"))) int bbm_rcm_order(const uint8_t* mask, int64_t N, int64_t row_stride_bytes, int32_t* perm,
+                                                                   void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace bbm;
+  clear_error();
+  if (!mask || !perm) return fail(BBM_EINVAL, "bbm_rcm_order: mask and perm must not be NULL");
+  if (N < 1) return fail(BBM_EINVAL, "bbm_rcm_order: N=%lld must be >= 1", (long long)N);
+  if (N > kMaxNodes) return fail(BBM_EUNSUPPORTED, "bbm_rcm_order: N=%lld exceeds %d", (long long)N, kMaxNodes);
+  if (row_stride_bytes < N) return fail(BBM_EINVAL, "bbm_rcm_order: row_stride_bytes=%lld < N=%lld", (long long)row_stride_bytes, (long long)N);
+  if (!aligned(perm, 4)) return fail(BBM_EINVAL, "bbm_rcm_order: perm must be 4-byte aligned");
+  const RcmLayout lay(N);
+  if (!workspace || workspace_bytes < lay.total)
+    return fail(BBM_EWORKSPACE, "bbm_rcm_order: workspace of %zu bytes needed, %zu given", lay.total, workspace ? workspace_bytes : (size_t)0);
+  if (!aligned(workspace, 16)) return fail(BBM_EINVAL, "bbm_rcm_order: workspace must be 16-byte aligned");
+  char* ws = static_cast<char*>(workspace);
+  uint64_t* bits = reinterpret_cast<uint64_t*>(ws + lay.bits);
+  int32_t* degree = reinterpret_cast<int32_t*>(ws + lay.degree);
+  int32_t* parent = reinterpret_cast<int32_t*>(ws + lay.parent);
+  int32_t* order = reinterpret_cast<int32_t*>(ws + lay.order);
+  int32_t* cand = reinterpret_cast<int32_t*>(ws + lay.cand);
+  uint64_t* keys = reinterpret_cast<uint64_t*>(ws + lay.keys);
+  const int W = (int)ceil_div(N, 64);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rcm_pack_kernel<<<(unsigned)N, kPackThreads, 0, s>>>(mask, (int)N, row_stride_bytes, W, bits, degree, parent);
+  int rc = launch_status("bbm_rcm_order (pack)");
+  if (rc != BBM_OK) return rc;
+  rcm_order_kernel<<<1, kOrderThreads, 0, s>>>(bits, degree, parent, order, cand, keys, (int)N, W, perm);
+  return launch_status("bbm_rcm_order");
+}
+
+extern "C" __attribute__((visibility("default"))) int bbm_permute_mask(const uint8_t* mask, int64_t Mb, int64_t N, int64_t row_stride_bytes,
+                                                                      const int32_t* perm, uint8_t* out, void* stream) {
+  using namespace bbm;
+  clear_error();
+  if (!mask || !perm || !out) return fail(BBM_EINVAL, "bbm_permute_mask: mask, perm, out must not be NULL");
+  if (mask == out) return fail(BBM_EINVAL, "bbm_permute_mask: out must not be the input");
+  if (Mb < 1 || N < 1) return fail(BBM_EINVAL, "bbm_permute_mask: Mb=%lld, N=%lld must be >= 1", (long long)Mb, (long long)N);
+  if (N > kMaxNodes || Mb > 65535) return fail(BBM_EUNSUPPORTED, "bbm_permute_mask: N=%lld exceeds %d or Mb=%lld exceeds 65535", (long long)N, kMaxNodes, (long long)Mb);
+  if (row_stride_bytes < N) return fail(BBM_EINVAL, "bbm_permute_mask: row_stride_bytes=%lld < N=%lld", (long long)row_stride_bytes, (long long)N);
+  permute_mask_kernel<<<dim3((unsigned)N, (unsigned)Mb), 256, 0, static_cast<hipStream_t>(stream)>>>(mask, (int)N, row_stride_bytes, perm, out);
+  return launch_status("bbm_permute_mask");
+}
+
+extern "C" __attribute__((visibility("default"))) int bbm_gather_rows(const void* in, const int32_t* perm, void* out, int64_t BH, int64_t N, int d,
+                                                                     int inverse, void* stream) {
+  using namespace bbm;
+  clear_error();
+  if (!in || !perm || !out) return fail(BBM_EINVAL, "bbm_gather_rows: in, perm, out must not be NULL");
+  if (in == out) return fail(BBM_EINVAL, "bbm_gather_rows: out must not be the input");
+  if (!aligned(in, 16) || !aligned(out, 16)) return fail(BBM_EINVAL, "bbm_gather_rows: in and out must be 16-byte aligned");
+  if (BH < 1 || N < 1 || d < 8 || d % 8 != 0) return fail(BBM_EINVAL, "bbm_gather_rows: BH=%lld, N=%lld >= 1 and d=%d a multiple of 8 required", (long long)BH, (long long)N, d);
+  const int chunks = d / 8;
+  const int64_t total = BH * N * chunks;
+  if (ceil_div(total, 256) >= (1ll << 31)) return fail(BBM_EUNSUPPORTED, "bbm_gather_rows: tensor too large");
+  gather_rows_kernel<<<(unsigned)ceil_div(total, 256), 256, 0, static_cast<hipStream_t>(stream)>>>(
+      static_cast<const uint4*>(in), perm, static_cast<uint4*>(out), N, chunks, total, inverse ? 1 : 0);
+  return launch_status("bbm_gather_rows");
+}

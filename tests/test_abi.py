@@ -22,7 +22,8 @@ def test_every_declared_symbol_is_exported(bbm):
     assert names == {"bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs",
                      "bbm_build_sparse_index", "bbm_build_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes",
                      "bbm_attn_fwd", "bbm_build_col_index", "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes",
-                     "bbm_attn_bwd", "bbm_build_block_mask_rect", "bbm_attn_fwd_rect"}
+                     "bbm_attn_bwd", "bbm_build_block_mask_rect", "bbm_attn_fwd_rect", "bbm_rcm_workspace_bytes",
+                     "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows"}
     raw = C.CDLL(bbm.library_path())
     for n in names:
         assert getattr(raw, n) is not None
@@ -34,7 +35,7 @@ def test_binding_has_the_same_names(bbm):
               "bbm_build_index",
               "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd", "bbm_build_col_index",
               "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd", "bbm_build_block_mask_rect",
-              "bbm_attn_fwd_rect"):
+              "bbm_attn_fwd_rect", "bbm_rcm_workspace_bytes", "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows"):
         assert callable(getattr(bbm, n))
 
 
@@ -166,3 +167,20 @@ def test_rectangular_entry_points_reject_bad_arguments(bbm):
     assert rect(256, 512) == bbm.BBM_EINVAL and "does not match" in bbm.bbm_last_error()
     assert rect(512, 256) == bbm.BBM_EINVAL
     assert rect(256, 256, q=None) == bbm.BBM_EINVAL and "bbm_attn_fwd_rect" in bbm.bbm_last_error()
+
+
+def test_reorder_entry_points_reject_bad_arguments(bbm):
+    L = bbm.lib
+    need = bbm.bbm_rcm_workspace_bytes(1000)
+    assert need >= 1000 * 16 * 8 + 24 * 1000 and bbm.bbm_rcm_workspace_bytes(0) == 0 and bbm.bbm_rcm_workspace_bytes(70000) == 0
+    assert L.bbm_rcm_order(None, 64, 64, FAKE, FAKE, 1 << 30, None) == bbm.BBM_EINVAL
+    assert L.bbm_rcm_order(FAKE, 64, 63, FAKE, FAKE, 1 << 30, None) == bbm.BBM_EINVAL
+    assert L.bbm_rcm_order(FAKE, 70000, 70000, FAKE, FAKE, 1 << 40, None) == bbm.BBM_EUNSUPPORTED
+    assert L.bbm_rcm_order(FAKE, 64, 64, FAKE, FAKE, 16, None) == bbm.BBM_EWORKSPACE
+    assert L.bbm_rcm_order(FAKE, 64, 64, FAKE, None, 0, None) == bbm.BBM_EWORKSPACE
+    assert L.bbm_permute_mask(FAKE, 1, 64, 64, None, C.c_void_p(0x2000), None) == bbm.BBM_EINVAL
+    assert L.bbm_permute_mask(FAKE, 1, 64, 64, FAKE, FAKE, None) == bbm.BBM_EINVAL and "input" in bbm.bbm_last_error()
+    assert L.bbm_permute_mask(FAKE, 1, 70000, 70000, FAKE, C.c_void_p(0x2000), None) == bbm.BBM_EUNSUPPORTED
+    assert L.bbm_gather_rows(FAKE, FAKE, C.c_void_p(0x2000), 2, 64, 60, 0, None) == bbm.BBM_EINVAL
+    assert L.bbm_gather_rows(FAKE, FAKE, C.c_void_p(0x2008), 2, 64, 64, 0, None) == bbm.BBM_EINVAL
+    assert L.bbm_gather_rows(FAKE, FAKE, FAKE, 2, 64, 64, 0, None) == bbm.BBM_EINVAL
