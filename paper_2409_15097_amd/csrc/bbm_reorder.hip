@@ -17,6 +17,9 @@ namespace {
 constexpr int kMaxNodes = 65536;            // visited set and one mask row must fit in LDS
 constexpr int kOrderThreads = 1024;
 constexpr int kPackThreads = 256;
+constexpr int kRankChunk = 2048;            // keys of a level staged in LDS at a time
+constexpr int kRankPerThread = 4;           // keys a thread ranks per sweep
+constexpr int kBatch = 8;                   // row words a thread of the level walk has in flight
 
 // 4 mask bytes -> 4 bits (bit t = byte t non-zero).
 __device__ __forceinline__ uint32_t nz_nibble(uint32_t x) {
@@ -68,6 +71,8 @@ __global__ __launch_bounds__(kOrderThreads) void rcm_order_kernel(const uint64_t
                                                                   int32_t* parent_pos, int32_t* order, int32_t* cand, uint64_t* keys,
                                                                   int N, int W, int32_t* __restrict__ perm) {
   __shared__ uint64_t visited[kMaxNodes / 64];
+  __shared__ uint64_t claimed[kMaxNodes / 64];  // nodes some frontier node has reached (they become visited within the level)
+  __shared__ uint64_t chunk_s[kRankChunk];
   __shared__ unsigned long long min_s[kOrderThreads / 64];
   __shared__ int count_s;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -80,6 +85,7 @@ __global__ __launch_bounds__(kOrderThreads) void rcm_order_kernel(const uint64_t
     if (w >= W) v = ~0ull;
     else if (w == W - 1 && (N & 63)) v = ~0ull << (N & 63);
     visited[w] = v;
+    claimed[w] = 0;
   }
   __syncthreads();
   int n_done = 0;
@@ -107,11 +113,11 @@ __global__ __launch_bounds__(kOrderThreads) void rcm_order_kernel(const uint64_t
     while (lvl_lo < lvl_hi) {
       // expand: every frontier node scans its row once; an unvisited neighbour is claimed by its earliest parent
       const int64_t total = (int64_t)(lvl_hi - lvl_lo) * W;
-      for (int64_t x0 = tid; x0 < total; x0 += 4 * kOrderThreads) {
-        uint64_t word[4];
-        int f[4], w[4];
+      for (int64_t x0 = tid; x0 < total; x0 += kBatch * kOrderThreads) {
+        uint64_t word[kBatch];
+        int f[kBatch], w[kBatch];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < kBatch; ++t) {
           const int64_t x = x0 + (int64_t)t * kOrderThreads;
           word[t] = 0;
           f[t] = w[t] = 0;
@@ -122,12 +128,14 @@ __global__ __launch_bounds__(kOrderThreads) void rcm_order_kernel(const uint64_t
           }
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < kBatch; ++t) {
           uint64_t b = word[t];
           while (b) {
             const int v = 64 * w[t] + __builtin_ctzll(b);
             b &= b - 1;
-            if (atomicMin(&parent_pos[v], f[t]) == INT_MAX) cand[atomicAdd(&count_s, 1)] = v;
+            atomicMin(&parent_pos[v], f[t]);  // result unused: the atomics of a thread pipeline instead of each waiting for its return
+            const unsigned long long bit = 1ull << (v & 63);
+            if (!(atomicOr(reinterpret_cast<unsigned long long*>(&claimed[v >> 6]), bit) & bit)) cand[atomicAdd(&count_s, 1)] = v;
           }
         }
       }
@@ -139,14 +147,36 @@ __global__ __launch_bounds__(kOrderThreads) void rcm_order_kernel(const uint64_t
         keys[c] = ((uint64_t)(uint32_t)parent_pos[v] << 40) | ((uint64_t)(uint32_t)degree[v] << 20) | (uint64_t)(uint32_t)v;
       }
       sync_global();
-      // rank by counting (keys are distinct), place, mark visited
-      for (int c = tid; c < L; c += kOrderThreads) {
-        const uint64_t k = keys[c];
-        int r = 0;
-        for (int j = 0; j < L; ++j) r += keys[j] < k ? 1 : 0;
-        const int v = (int)(k & 0xfffffull);
-        order[n_done + r] = v;
-        atomicOr(reinterpret_cast<unsigned long long*>(&visited[v >> 6]), 1ull << (v & 63));
+      // rank by counting (keys are distinct), place, mark visited.  The keys pass through LDS in chunks; a thread
+      // ranks up to kRankPerThread keys per sweep over the level.
+      for (int c0 = 0; c0 < L; c0 += kRankPerThread * kOrderThreads) {
+        uint64_t mine[kRankPerThread];
+        int r[kRankPerThread];
+#pragma unroll
+        for (int t = 0; t < kRankPerThread; ++t) {
+          const int c = c0 + t * kOrderThreads + tid;
+          mine[t] = c < L ? keys[c] : 0;
+          r[t] = 0;
+        }
+        for (int j0 = 0; j0 < L; j0 += kRankChunk) {
+          const int n = min(kRankChunk, L - j0);
+          __syncthreads();  // the previous chunk has been read
+          for (int j = tid; j < n; j += kOrderThreads) chunk_s[j] = keys[j0 + j];
+          __syncthreads();
+          for (int j = 0; j < n; ++j) {
+            const uint64_t kj = chunk_s[j];
+#pragma unroll
+            for (int t = 0; t < kRankPerThread; ++t) r[t] += kj < mine[t] ? 1 : 0;
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < kRankPerThread; ++t) {
+          if (c0 + t * kOrderThreads + tid < L) {
+            const int v = (int)(mine[t] & 0xfffffull);
+            order[n_done + r[t]] = v;
+            atomicOr(reinterpret_cast<unsigned long long*>(&visited[v >> 6]), 1ull << (v & 63));
+          }
+        }
       }
       if (tid == 0) count_s = 0;
       lvl_lo = lvl_hi;

@@ -37,6 +37,12 @@ def _cases():
     star[17, :] = 1
     star[:, 17] = 1
     yield "star", star                                               # one level of 199 nodes
+    big = np.eye(5000, dtype=np.uint8)
+    big[4321, :] = 1
+    big[:, 4321] = 1
+    big[np.arange(0, 4999, 2), np.arange(1, 5000, 2)] = 1                # unequal degrees among the 4999 nodes of the level
+    big[np.arange(1, 5000, 2), np.arange(0, 4999, 2)] = 1
+    yield "big star", big                                            # a level larger than one ranking sweep (4096 keys)
     yield "graph workload", masks.graph_mask(1024, 5, reorder="none", xm=8.0, cap=60)[0]
     yield "single node", np.ones((1, 1), dtype=np.uint8)
     yield "no self loops", (_sym(64, 4, 0.05) * (1 - np.eye(64, dtype=np.uint8))).astype(np.uint8)
@@ -107,3 +113,24 @@ def test_reordered_pipeline_equals_attention_on_the_original_problem():
     assert after < before // 2, (before, after)
     want = oracle.reverse_cuthill_mckee(A[0])
     assert np.array_equal(perm.cpu().numpy().astype(np.int64), want)
+
+
+def test_full_size_graph_workload_ordering_and_block_reduction():
+    """The scrambled graph of the largest configuration (N = 32768, about 10 million edges): the ordering equals the
+    oracle's, and it cuts the non-zero 128 x 64 blocks as the host-side reordering of the workload generator does."""
+    bbm = _bbm()
+    from workloads import make_config
+    cfg = make_config("C5", with_qkv=False)
+    A = masks.graph_mask(cfg["N"], cfg["seed"], reorder="none")
+    mt = torch.from_numpy(A).cuda()
+    print("rcm full size: gpu", flush=True)
+    perm = bbm.bbm_rcm_order(mt[0])
+    pm = bbm.bbm_permute_mask(mt, perm)
+    torch.cuda.synchronize()
+    print("rcm full size: oracle", flush=True)
+    want = oracle.reverse_cuthill_mckee(A[0])
+    assert np.array_equal(perm.cpu().numpy().astype(np.int64), want)
+    after = int((bbm.build_index(pm, 128, 64).blk_class != 0).sum())
+    host = int((bbm.build_index(torch.from_numpy(cfg["mask"]).cuda(), 128, 64).blk_class != 0).sum())
+    before = int((bbm.build_index(mt, 128, 64).blk_class != 0).sum())
+    assert before == 256 * 512 and after <= host * 1.05 and after < before // 5, (before, after, host)

@@ -27,6 +27,8 @@ CONFIGS = {
     # tree verification at decode time: only the 256 candidate-tree tokens are queries (Nq), the keys are the 1024-token
     # prefix plus the tree (N): the last Nq rows of the mask of C3
     "C3q": dict(B=8, H=32, N=1280, d=128, Mb=1, family="tree", Nq=256),
+    # the graph of C5 as it arrives, with scrambled node labels: the reordering is part of the measured pipeline
+    "C5g": dict(B=1, H=8, N=32768, d=64, Mb=1, family="graph_scrambled", gpu_reorder=True),
 }
 _IDS = {k: i for i, k in enumerate(CONFIGS)}
 
@@ -58,6 +60,11 @@ def make_mask(family: str, N: int, Mb: int, seed: int) -> np.ndarray:
             return masks.graph_mask(N, seed)
         f = N / 32768.0
         return masks.graph_mask(N, seed, xm=max(2.0, 84.0 * f * 4), cap=max(16, int(2000 * f * 4)))
+    if family == "graph_scrambled":
+        if N >= 32768:
+            return masks.graph_mask(N, seed, reorder="none")
+        f = N / 32768.0
+        return masks.graph_mask(N, seed, reorder="none", xm=max(2.0, 84.0 * f * 4), cap=max(16, int(2000 * f * 4)))
     if family == "all_ones":
         return masks.all_ones(N)
     if family == "causal":
