@@ -251,7 +251,7 @@ def main():
 
     main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch, not a.no_backward)
     rows = [main_res]
-    extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128,C2b,C4w,C4d,C3q,C5g,C0d128:256,C0c128:256" if a.masks == "all" else a.masks
+    extra = "C3,C4,C5,C0d,C0c,C0d128,C0c128,C2b,C4w,C4d,C3q,C3qL,C5g,C0d128:256,C0c128:256" if a.masks == "all" else a.masks
     for name in [m for m in extra.split(",") if m and m != a.workload]:
         r, _ = measure_mask(bbm, name, a.Br, a.warmup, a.steps, torch, not a.no_backward)
         rows.append(r)

@@ -57,6 +57,7 @@ struct AttnParams {
   int32_t hbp;        // (batch, head) pairs per mask plane: B*H if Mb == 1, else H
   int32_t n_extra;    // leading work-groups that serve the queue of cut-row parts (LIST mode)
   int32_t G;          // (batch, head) planes whose block rows are interleaved in launch order
+  int32_t split;      // parts per block row when the launch is too small to fill the chip (LIST mode), else 1
 };
 
 __device__ __forceinline__ float partner_max(float x) {
@@ -147,11 +148,13 @@ struct IntC {
   static constexpr int value = V;
 };
 
-// One work-group per (block row, batch, head), tiles from build_window.  With SCHED = true (LIST mode) the first
+// One work-group per (block row, batch, head), tiles from build_window.  SCHED = 2 (LIST mode on a launch too small to
+// fill the chip): every block row is computed in P.split equal parts by as many work-groups, merged like cut rows.
+// With SCHED = 1 (LIST mode) the first
 // P.n_extra work-groups, before turning to their own block row, take the parts of the block rows which the split
 // schedule cut from a queue; the work-group that completes a row's last part merges the parts in part order and
 // writes the row, and the row's own work-group skips it.
-template <int D, int NW, bool SCHED>
+template <int D, int NW, int SCHED>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NT = NW * 64;
   constexpr int BR = NW * 32;
@@ -329,7 +332,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     // a partial tile in which none of this wave's 32 queries sees a key adds exact zeros: such a wave only takes part
     // in the copies and barriers of the step (not in the dense-tile baseline, which stands for a kernel that knows
     // nothing about the mask's structure)
-    const bool live = (e0 >> 31) != 0 || (!SCHED && P.mode == BBM_MODE_DENSE_BASELINE) || __ballot(mw != 0ull) != 0ull;
+    const bool live = (e0 >> 31) != 0 || (SCHED == 0 && P.mode == BBM_MODE_DENSE_BASELINE) || __ballot(mw != 0ull) != 0ull;
     f32x16 s[2];
     if (live) qk(k_cur, s);
     // the next tile's copies are requested behind the first product: their address arithmetic runs while the matrix
@@ -483,6 +486,65 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * (1.0f / kLog2e) + __logf(l_tot) : -INFINITY;
   };
 
+  // ---- LIST mode on a small launch: work-group = (block row, part); the parts of a row run side by side and the last
+  // one to finish merges them in part order (same arithmetic as the parts of a cut row)
+  if constexpr (SCHED == 2) {
+    const int S = P.split;
+    const int part = (int)blockIdx.x % S, rest = (int)blockIdx.x / S;
+    bh = rest / P.nbr;
+    i = P.nbr - 1 - (rest - bh * P.nbr);
+    m = (P.Mb == 1) ? 0 : bh / P.H;
+    const int hb = (P.Mb == 1) ? bh : bh - m * P.H;
+    const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
+    const int p_row = rp[0], n_row = rp[1] - rp[0];
+    const int chunk = (n_row + S - 1) / S;
+    const int p0 = p_row + part * chunk, nt = max(0, min(chunk, n_row - part * chunk));
+    const uint32_t* __restrict__ list = P.col_idx + (int64_t)m * P.nbr * P.nbc + p0;
+    begin_item();
+    if (nt > 0) {
+      run_list(list, nt, list[0]);
+    } else if (Q_VIA_LDS && q_pending) {  // nothing to compute: let the Q copies land before anyone reuses the slabs
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      q_pending = false;
+    }
+    const int row = m * P.nbr + i;
+    float* rec = P.partials + (((int64_t)row * S + part) * P.hbp + hb) * ((REGS + 2) * NT) + tid;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      for (int e = 0; e < 16; ++e) rec[(db * 16 + e) * NT] = oacc[db][e];
+    rec[REGS * NT] = m_run;
+    rec[(REGS + 1) * NT] = l_run;
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) item_s[1] = atomicAdd(P.queue + 8 + row * P.hbp + hb, 1);
+    __syncthreads();
+    if (item_s[1] == S - 1) {
+      __threadfence();
+      const float* r0 = P.partials + ((int64_t)row * S * P.hbp + hb) * ((REGS + 2) * NT) + tid;
+      const int64_t pstride = (int64_t)P.hbp * ((REGS + 2) * NT);
+      float m_all = -INFINITY;
+      for (int k = 0; k < S; ++k) m_all = fmaxf(m_all, r0[k * pstride + REGS * NT]);
+      const float m_fin = (m_all == -INFINITY) ? 0.0f : m_all;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
+      l_run = 0.0f;
+      for (int k = 0; k < S; ++k) {
+        const float* rk = r0 + k * pstride;
+        const float wgt = __builtin_amdgcn_exp2f(rk[REGS * NT] - m_fin);
+        l_run += wgt * rk[(REGS + 1) * NT];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          for (int e = 0; e < 16; ++e) oacc[db][e] += wgt * rk[(db * 16 + e) * NT];
+      }
+      m_run = m_all;
+      write_output();
+      if (tid == 0) P.queue[8 + row * P.hbp + hb] = 0;  // last user of this counter: leave it zero for the next call
+    }
+    return;
+  }
+
   // ---- which block row is this work-group's own?  Work-groups are handed to the 8 XCDs round-robin; give each XCD a
   // contiguous range of logical ids so the row blocks of one head (which share K and V) meet in one XCD's L2.
   // Launch order inside a group of G consecutive (batch, head) planes: rank-major, i.e. rank 0 of every plane of the
@@ -505,7 +567,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   // its rank, where its list lies and how it starts -- are requested together: one round trip, not three
   int4 own_rec = make_int4(0, 0, 0, -1);
   int nparts_all = 0, split_T = 0;
-  if (SCHED) {
+  if (SCHED == 1) {
     static_assert(bbm::kSchedNParts == 0 && bbm::kSchedSplitT == 1, "the header is read as one 8-byte pair");
     const int2 hdr = *reinterpret_cast<const int2*>(P.sched);
     own_rec = *reinterpret_cast<const int4*>(P.sched + bbm::sched_order_base(P.Mb, P.nbr) +
@@ -515,7 +577,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   }
   // ---- LIST mode, the first n_extra work-groups: before their own block row they serve the queue of cut-row parts
   // (nothing to do, and no cost, when the schedule cut no row)
-  if (SCHED && (int)blockIdx.x < P.n_extra) {
+  if (SCHED == 1 && (int)blockIdx.x < P.n_extra) {
     const int32_t* __restrict__ S = P.sched;
   const int n_items = nparts_all * P.hbp;
   // The first item of a work-group is its own index; later ones come from the queue counter, which therefore stands
@@ -586,7 +648,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   {
     bh = own_bh;
     m = own_m;
-    if (SCHED) {
+    if (SCHED == 1) {
       i = own_rec.x;
       const int n_list = own_rec.z;
       begin_item();
@@ -621,15 +683,32 @@ inline size_t partial_bytes(int64_t Mb, int64_t nbr, int64_t hbp, int d, int Br)
   return (size_t)(Mb * nbr * hbp) * (size_t)((d / 32 * 16 + 2) * (Br * 2)) * sizeof(float);
 }
 
+// A LIST-mode launch of fewer than kSplitBelow work-groups leaves most of the 256 CUs idle (a few block rows of new
+// tokens against a long key/value cache): every block row is then computed in split_parts() equal parts -- as many as
+// give every CU one work-group, but no more than leave a part kSplitMinTiles block columns.  A part costs a prologue,
+// a parked partial result, two device-wide fences and a share of the merge: with 20 tiles per row, 8 parts were 3.5
+// times slower than none; with 260 tiles per row and 64 rows, 2 / 4 / 8 parts took 0.193 / 0.146 / 0.205 ms against
+// 0.32 ms unsplit (the fences of 512 work-groups cost more than the second work-group per CU gains).
+constexpr int kSplitBelow = 128, kSplitTarget = 256, kSplitMax = 8, kSplitMinTiles = 32;
+inline int split_parts(int64_t total_wgs, int64_t nbc) {
+  if (total_wgs >= kSplitBelow) return 1;
+  const int64_t s = std::min<int64_t>(std::min<int64_t>(kSplitMax, kSplitTarget / total_wgs), nbc / kSplitMinTiles);
+  return s < 2 ? 1 : (int)s;
+}
+
 template <int D, int NW>
 int launch(AttnParams& P, int64_t Mb, void* workspace, hipStream_t s) {
   if (P.mode == BBM_MODE_LIST) {
     P.queue = static_cast<int32_t*>(workspace);
     P.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + queue_bytes(Mb, P.nbr, P.hbp));
     P.n_extra = P.total_wgs < kExtraWGs ? P.total_wgs : kExtraWGs;
-    attn_fwd_kernel<D, NW, true><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+    P.split = split_parts(P.total_wgs, P.nbc);
+    if (P.split > 1)
+      attn_fwd_kernel<D, NW, 2><<<(unsigned)(P.total_wgs * P.split), NW * 64, 0, s>>>(P);
+    else
+      attn_fwd_kernel<D, NW, 1><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   } else {
-    attn_fwd_kernel<D, NW, false><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+    attn_fwd_kernel<D, NW, 0><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   }
   return bbm::launch_status("bbm_attn_fwd");
 }
@@ -640,8 +719,9 @@ extern "C" __attribute__((visibility("default"))) size_t bbm_attn_fwd_workspace_
   if (B < 1 || H < 1 || N < 1 || Br < 1 || Bc < 1 || (d != 64 && d != 128)) return 0;
   if (mode != BBM_MODE_LIST && mode != BBM_MODE_AUTO) return 0;
   // sized for the larger of the two plane counts a caller may use (Mb = 1 or Mb = B): both give Mb*hbp = B*H
+  // (N counts the queries; the number of keys is not known here, so the largest split of a small launch is assumed)
   const int64_t nbr = (N + Br - 1) / Br;
-  return queue_bytes(1, nbr, B * H) + partial_bytes(1, nbr, B * H, d, Br);
+  return queue_bytes(1, nbr, B * H) + partial_bytes(1, nbr, B * H, d, Br) * (size_t)split_parts(B * H * nbr, 1 << 30);
 }
 
 namespace {
@@ -724,6 +804,7 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   P.partials = nullptr;
   P.hbp = (int32_t)(Mb == 1 ? B * H : H);
   P.n_extra = 0;
+  P.split = 1;
   // interleave the planes that one XCD's share of the launch spans (at most 8: their K and V should stay in its L2)
   P.G = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, (B * H * nbr / 8) / nbr));
   hipStream_t s = static_cast<hipStream_t>(stream);

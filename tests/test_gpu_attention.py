@@ -267,3 +267,37 @@ def test_rectangular_ragged_sizes_with_empty_rows(Nq, Nk, d):
             print(f"rect Nq={Nq} Nk={Nk} d={d} Br={Br} mode={mode}", flush=True)
             o, lse = _gpu_attn_rect(q, k, v, mask, Br, mode, check_index=(mode == "BITMAP"))
             assert_attention_close(o, lse, O_ref, lse_ref)
+
+
+def test_small_launch_computes_every_block_row_in_parts():
+    """Fewer than 256 work-groups (one sequence, a few block rows of new tokens against a long cache): LIST mode
+    computes every block row in parts.  Rows with fewer tiles than parts, empty rows, a workspace reused by two calls
+    (bit-identical results, counters back to zero), and agreement with the one-work-group-per-row schedules."""
+    bbm = _bbm()
+    B, H, d, Nq, Nk = 1, 3, 64, 300, 16400          # 257 block columns: 8 parts per block row
+    q = make_qkv(B, H, Nq, d, seed=41)[0]
+    _, k, v = make_qkv(B, H, Nk, d, seed=42)
+    rng = np.random.default_rng(43)
+    mask = (rng.random((1, Nq, Nk)) < 0.3).astype(np.uint8)
+    mask[0, :, 3000:9000] = 1                      # full tiles, too
+    mask[0, :70, 200:] = 0                         # a block row with 4 tiles only (fewer than the 8 parts)
+    mask[0, 128:192] = 0                           # an empty block row at Br = 64
+    mask[0, 250:260, :] = 1
+    O_ref, lse_ref = oracle.masked_attention(q, k, v, mask)
+    for Br in (64, 128, 256):
+        idx = bbm.build_index(torch.from_numpy(mask).cuda(), Br, 64)
+        need = bbm.bbm_attn_fwd_workspace_bytes(B, H, Nq, d, Br, 64, bbm.BBM_MODE_LIST)
+        ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+        qt, kt, vt = (bf16_tensor(x) for x in (q, k, v))
+        o1, l1 = bbm.bbm_attn_fwd_rect(qt, kt, vt, idx, mode=bbm.BBM_MODE_LIST, workspace=ws)
+        o1, l1 = o1.clone(), l1.clone()
+        o2, l2 = bbm.bbm_attn_fwd_rect(qt, kt, vt, idx, mode=bbm.BBM_MODE_LIST, workspace=ws)
+        torch.cuda.synchronize()
+        assert_attention_close(o1, l1, O_ref, lse_ref)
+        assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(l1, l2)
+        nbr = idx.nbr
+        assert int(ws[:4 * (8 + B * H * nbr)].view(torch.int32).abs().sum()) == 0
+        ob, lb = bbm.bbm_attn_fwd_rect(qt, kt, vt, idx, mode=bbm.BBM_MODE_BITMAP)
+        torch.cuda.synchronize()
+        assert np.abs(bf16_result_to_f64(o1) - bf16_result_to_f64(ob)).max() <= O_MAX_ABS
+        assert torch.all(o1[0, :, 128:192] == 0)

@@ -27,6 +27,9 @@ CONFIGS = {
     # tree verification at decode time: only the 256 candidate-tree tokens are queries (Nq), the keys are the 1024-token
     # prefix plus the tree (N): the last Nq rows of the mask of C3
     "C3q": dict(B=8, H=32, N=1280, d=128, Mb=1, family="tree", Nq=256),
+    # the same for a single sequence against a 16384-token cache: 64 work-groups of 128 queries, far fewer than the
+    # chip has CUs, each with 260 tiles to walk
+    "C3qL": dict(B=1, H=32, N=16640, d=128, Mb=1, family="tree", Nq=256),
     # the graph of C5 as it arrives, with scrambled node labels: the reordering is part of the measured pipeline
     "C5g": dict(B=1, H=8, N=32768, d=64, Mb=1, family="graph_scrambled", gpu_reorder=True),
 }
