@@ -209,7 +209,23 @@ __global__ __launch_bounds__(256) void permute_mask_kernel(const uint8_t* __rest
   }
   __syncthreads();
   uint8_t* __restrict__ dst = out + (m * N + i) * (int64_t)N;
-  for (int j = tid; j < N; j += 256) dst[j] = row_s[min(max(perm[j], 0), N - 1)];
+  if ((N & 15) == 0 && ((reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(perm)) & 15) == 0) {
+    // 16 output bytes per lane: four 16-byte reads of perm, sixteen LDS byte reads, one 16-byte store
+    for (int j0 = 16 * tid; j0 < N; j0 += 16 * 256) {
+      uint32_t w[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int4 p = *reinterpret_cast<const int4*>(perm + j0 + 4 * g);
+        const int pp[4] = {p.x, p.y, p.z, p.w};
+        w[g] = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) w[g] |= (uint32_t)row_s[min(max(pp[t], 0), N - 1)] << (8 * t);
+      }
+      *reinterpret_cast<uint4*>(dst + j0) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  } else {
+    for (int j = tid; j < N; j += 256) dst[j] = row_s[min(max(perm[j], 0), N - 1)];
+  }
 }
 
 // Rows of a [BH][N][d] bf16 tensor: gather (out[k] = in[perm[k]]) or scatter (out[perm[k]] = in[k]); 16 bytes per lane.
