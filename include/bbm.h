@@ -306,9 +306,10 @@ int bbm_attn_bwd(const void* q, const void* k, const void* v, const void* o, con
  *                    mask[perm][:, perm] (bbm_permute_mask), reordered Q/K/V rows are row perm[k] at position k
  *                    (bbm_gather_rows), and O comes back with the inverse (bbm_gather_rows with inverse = 1).
  *   workspace        device scratch of at least bbm_rcm_workspace_bytes(N) bytes (N*ceil(N/64)*8 for the packed rows
- *                    plus 24*N), 16-byte aligned; needs no initialisation.
- * N <= 65536.  The level walk runs in one work-group with no host round trip: time grows with the number of
- * breadth-first levels and of connected components (each costs a scan over the N nodes).
+ *                    plus about 26*N), 16-byte aligned; needs no initialisation.
+ * N <= 65536.  No host round trip: a fixed number of rounds (one breadth-first level or one component start each) use
+ * the whole GPU, a one-work-group finisher walks whatever is left; so time grows with the number of levels and of
+ * connected components beyond 48 (each costs one work-group a scan over the N nodes).
  * Errors: BBM_EINVAL, BBM_EUNSUPPORTED (N > 65536), BBM_EWORKSPACE, BBM_EHIP.
  */
 size_t bbm_rcm_workspace_bytes(int64_t N);

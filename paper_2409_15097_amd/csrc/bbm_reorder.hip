@@ -27,12 +27,22 @@ __device__ __forceinline__ uint32_t nz_nibble(uint32_t x) {
   return (((y >> 7) * 0x00204081u) >> 21) & 0xfu;
 }
 
+enum { kStDone = 0, kStLvlLo = 1, kStLvlHi = 2, kStCand = 3, kStInts = 8 };  // state of the level walk (int32)
+
 // One work-group per mask row: bits[row][w] (row-major, bits past N zero), degree[row], parent_pos[row] = "none".
 __global__ __launch_bounds__(kPackThreads) void rcm_pack_kernel(const uint8_t* __restrict__ mask, int N, int64_t row_stride, int W,
                                                                 uint64_t* __restrict__ bits, int32_t* __restrict__ degree,
-                                                                int32_t* __restrict__ parent_pos) {
+                                                                int32_t* __restrict__ parent_pos, uint64_t* __restrict__ visited,
+                                                                uint64_t* __restrict__ claimed, int32_t* __restrict__ state) {
   __shared__ int red_s[kPackThreads / 64];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  if (row == 0) {  // the walk's sets (nodes past N count as visited) and state
+    for (int w = tid; w < W; w += kPackThreads) {
+      visited[w] = (w == W - 1 && (N & 63)) ? ~0ull << (N & 63) : 0ull;
+      claimed[w] = 0;
+    }
+    if (tid < kStInts) state[tid] = 0;
+  }
   const uint8_t* __restrict__ src = mask + (int64_t)row * row_stride;
   const bool vec = ((reinterpret_cast<uintptr_t>(mask) | (uintptr_t)row_stride) & 15) == 0;
   int count = 0;
@@ -65,126 +75,232 @@ __global__ __launch_bounds__(kPackThreads) void rcm_pack_kernel(const uint8_t* _
   }
 }
 
-// The level walk, one work-group.  Global arrays written by some threads and read by others are separated by an
-// agent-scope fence and a barrier.
-__global__ __launch_bounds__(kOrderThreads) void rcm_order_kernel(const uint64_t* __restrict__ bits, const int32_t* __restrict__ degree,
-                                                                  int32_t* parent_pos, int32_t* order, int32_t* cand, uint64_t* keys,
-                                                                  int N, int W, int32_t* __restrict__ perm) {
+// State of the level walk in the workspace (int32): the walk is cut into kernels -- a fixed number of rounds of a
+// parallel expansion (many work-groups) and a one-work-group advance, then a one-work-group finisher that does both
+// itself for whatever is left (graphs with more levels or components than rounds).  No kernel waits for another.
+constexpr int kRounds = 48;                 // parallel rounds (one breadth-first level, or one component start, each)
+constexpr int kExpandWGs = 1024, kExpandThreads = 256;
+
+__device__ __forceinline__ uint64_t level_key(int parent, int degree, int v) {
+  return ((uint64_t)(uint32_t)parent << 40) | ((uint64_t)(uint32_t)degree << 20) | (uint64_t)(uint32_t)v;
+}
+
+// Ranks the L distinct keys by counting and calls place(rank, node) for each; the keys pass through LDS in chunks and
+// a thread ranks up to kRankPerThread keys per sweep.  All kOrderThreads threads of the work-group must call it.
+template <typename Place>
+__device__ __forceinline__ void rank_level(const uint64_t* keys, int L, uint64_t* chunk_s, int tid, Place place) {
+  for (int c0 = 0; c0 < L; c0 += kRankPerThread * kOrderThreads) {
+    uint64_t mine[kRankPerThread];
+    int r[kRankPerThread];
+#pragma unroll
+    for (int t = 0; t < kRankPerThread; ++t) {
+      const int c = c0 + t * kOrderThreads + tid;
+      mine[t] = c < L ? keys[c] : 0;
+      r[t] = 0;
+    }
+    for (int j0 = 0; j0 < L; j0 += kRankChunk) {
+      const int n = min(kRankChunk, L - j0);
+      __syncthreads();  // the previous chunk has been read
+      for (int j = tid; j < n; j += kOrderThreads) chunk_s[j] = keys[j0 + j];
+      __syncthreads();
+      for (int j = 0; j < n; ++j) {
+        const uint64_t kj = chunk_s[j];
+#pragma unroll
+        for (int t = 0; t < kRankPerThread; ++t) r[t] += kj < mine[t] ? 1 : 0;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < kRankPerThread; ++t)
+      if (c0 + t * kOrderThreads + tid < L) place(r[t], (int)(mine[t] & 0xfffffull));
+  }
+}
+
+// The unvisited node of minimum (degree, index), or -1: every thread of the work-group gets the result.
+template <typename Visited>
+__device__ __forceinline__ int min_degree_unvisited(const int32_t* __restrict__ degree, int N, Visited visited_word,
+                                                    unsigned long long* min_s, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  unsigned long long best = ~0ull;
+  for (int i = tid; i < N; i += kOrderThreads)
+    if (!((visited_word(i >> 6) >> (i & 63)) & 1ull)) best = min(best, ((unsigned long long)(uint32_t)degree[i] << 32) | (uint32_t)i);
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) best = min(best, (unsigned long long)__shfl_xor(best, d));
+  __syncthreads();  // min_s may still be read from an earlier call
+  if (lane == 0) min_s[wave] = best;
+  __syncthreads();
+  best = min_s[0];
+  for (int w = 1; w < kOrderThreads / 64; ++w) best = min(best, min_s[w]);
+  return best == ~0ull ? -1 : (int)(best & 0xffffffffull);
+}
+
+// Parallel expansion of the current level: every frontier node's bit row is scanned once; an unvisited neighbour is
+// claimed by its earliest parent (atomic minimum of the parent's position) and entered in the candidate list by
+// whoever sets its bit in the `claimed` set first.  Returns at once when there is no frontier.
+__global__ __launch_bounds__(kExpandThreads) void rcm_expand_kernel(const uint64_t* __restrict__ bits, const int32_t* __restrict__ order,
+                                                                    const uint64_t* __restrict__ visited, uint64_t* claimed,
+                                                                    int32_t* parent_pos, int32_t* cand, int32_t* state, int W) {
+  const int lvl_lo = state[kStLvlLo], lvl_hi = state[kStLvlHi];
+  if (state[kStDone] || lvl_lo >= lvl_hi) return;
+  const int64_t total = (int64_t)(lvl_hi - lvl_lo) * W;
+  const int64_t stride = (int64_t)gridDim.x * kExpandThreads;
+  for (int64_t x0 = (int64_t)blockIdx.x * kExpandThreads + threadIdx.x; x0 < total; x0 += kBatch * stride) {
+    uint64_t word[kBatch];
+    int f[kBatch], w[kBatch];
+#pragma unroll
+    for (int t = 0; t < kBatch; ++t) {
+      const int64_t x = x0 + t * stride;
+      word[t] = 0;
+      f[t] = w[t] = 0;
+      if (x < total) {
+        f[t] = lvl_lo + (int)(x / W);
+        w[t] = (int)(x % W);
+        word[t] = bits[(int64_t)order[f[t]] * W + w[t]] & ~visited[w[t]];
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < kBatch; ++t) {
+      uint64_t b = word[t];
+      while (b) {
+        const int v = 64 * w[t] + __builtin_ctzll(b);
+        b &= b - 1;
+        atomicMin(&parent_pos[v], f[t]);
+        const unsigned long long bit = 1ull << (v & 63);
+        if (!(atomicOr(reinterpret_cast<unsigned long long*>(&claimed[v >> 6]), bit) & bit)) cand[atomicAdd(&state[kStCand], 1)] = v;
+      }
+    }
+  }
+}
+
+// One advance, one work-group: order the candidates the expansion found and make them the next level -- or, when it
+// found none (a component is finished, or nothing has started yet), start the next component.
+__global__ __launch_bounds__(kOrderThreads) void rcm_advance_kernel(const int32_t* __restrict__ degree, const int32_t* __restrict__ parent_pos,
+                                                                   const int32_t* __restrict__ cand, uint64_t* keys, int32_t* order,
+                                                                   uint64_t* visited, int32_t* state, int N) {
+  __shared__ uint64_t chunk_s[kRankChunk];
+  __shared__ unsigned long long min_s[kOrderThreads / 64];
+  const int tid = threadIdx.x;
+  if (state[kStDone]) return;
+  const int n_done = state[kStLvlHi], L = state[kStCand];  // every placed node lies below the end of the current level
+  __syncthreads();                                         // everyone has read the state before thread 0 rewrites it
+  if (L > 0) {
+    for (int c = tid; c < L; c += kOrderThreads) {
+      const int v = cand[c];
+      keys[c] = level_key(parent_pos[v], degree[v], v);
+    }
+    __threadfence();
+    __syncthreads();
+    rank_level(keys, L, chunk_s, tid, [&](int r, int v) {
+      order[n_done + r] = v;
+      atomicOr(reinterpret_cast<unsigned long long*>(&visited[v >> 6]), 1ull << (v & 63));
+    });
+    if (tid == 0) {
+      state[kStLvlLo] = n_done;
+      state[kStLvlHi] = n_done + L;
+      state[kStCand] = 0;
+    }
+  } else {
+    const int start = min_degree_unvisited(degree, N, [&](int w) { return visited[w]; }, min_s, tid);
+    if (tid == 0) {
+      if (start < 0) {
+        state[kStDone] = 1;
+      } else {
+        order[n_done] = start;
+        visited[start >> 6] |= 1ull << (start & 63);
+        state[kStLvlLo] = n_done;
+        state[kStLvlHi] = n_done + 1;
+      }
+    }
+  }
+}
+
+// The finisher, one work-group: whatever the rounds left (nothing, for graphs of few levels and components) is walked
+// here with the expansion done by the same work-group; then the ordering is reversed into perm.  Global arrays written
+// by some threads and read by others are separated by an agent-scope fence and a barrier.
+__global__ __launch_bounds__(kOrderThreads) void rcm_finish_kernel(const uint64_t* __restrict__ bits, const int32_t* __restrict__ degree,
+                                                                   int32_t* parent_pos, int32_t* order, int32_t* cand, uint64_t* keys,
+                                                                   const uint64_t* __restrict__ visited_g, const int32_t* __restrict__ state,
+                                                                   int N, int W, int32_t* __restrict__ perm) {
   __shared__ uint64_t visited[kMaxNodes / 64];
   __shared__ uint64_t claimed[kMaxNodes / 64];  // nodes some frontier node has reached (they become visited within the level)
   __shared__ uint64_t chunk_s[kRankChunk];
   __shared__ unsigned long long min_s[kOrderThreads / 64];
   __shared__ int count_s;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   auto sync_global = [&]() {
     __threadfence();
     __syncthreads();
   };
-  for (int w = tid; w < kMaxNodes / 64; w += kOrderThreads) {
-    uint64_t v = 0;                                       // nodes past N count as visited
-    if (w >= W) v = ~0ull;
-    else if (w == W - 1 && (N & 63)) v = ~0ull << (N & 63);
-    visited[w] = v;
-    claimed[w] = 0;
-  }
-  __syncthreads();
-  int n_done = 0;
-  while (n_done < N) {
-    // ---- start of a component: the unvisited node of minimum (degree, index)
-    unsigned long long best = ~0ull;
-    for (int i = tid; i < N; i += kOrderThreads)
-      if (!((visited[i >> 6] >> (i & 63)) & 1ull)) best = min(best, ((unsigned long long)(uint32_t)degree[i] << 32) | (uint32_t)i);
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) best = min(best, (unsigned long long)__shfl_xor(best, d));
-    if (lane == 0) min_s[wave] = best;
+  const bool done = state[kStDone] != 0;
+  int lvl_lo = state[kStLvlLo], lvl_hi = state[kStLvlHi];
+  int n_done = lvl_hi;
+  if (!done) {
+    for (int w = tid; w < kMaxNodes / 64; w += kOrderThreads) {
+      visited[w] = w < W ? visited_g[w] : ~0ull;  // nodes past N were marked visited when the set was initialised
+      claimed[w] = 0;
+    }
+    if (tid == 0) count_s = 0;
     __syncthreads();
-    best = min_s[0];
-    for (int w = 1; w < kOrderThreads / 64; ++w) best = min(best, min_s[w]);
-    const int start = (int)(best & 0xffffffffull);
-    if (tid == 0) {
-      order[n_done] = start;
-      visited[start >> 6] |= 1ull << (start & 63);
-      count_s = 0;
-    }
-    int lvl_lo = n_done, lvl_hi = n_done + 1;
-    n_done += 1;
-    sync_global();
-    // ---- breadth-first levels of this component
-    while (lvl_lo < lvl_hi) {
-      // expand: every frontier node scans its row once; an unvisited neighbour is claimed by its earliest parent
-      const int64_t total = (int64_t)(lvl_hi - lvl_lo) * W;
-      for (int64_t x0 = tid; x0 < total; x0 += kBatch * kOrderThreads) {
-        uint64_t word[kBatch];
-        int f[kBatch], w[kBatch];
+    while (true) {
+      // ---- breadth-first levels of the current component
+      while (lvl_lo < lvl_hi) {
+        const int64_t total = (int64_t)(lvl_hi - lvl_lo) * W;
+        for (int64_t x0 = tid; x0 < total; x0 += kBatch * kOrderThreads) {
+          uint64_t word[kBatch];
+          int f[kBatch], w[kBatch];
 #pragma unroll
-        for (int t = 0; t < kBatch; ++t) {
-          const int64_t x = x0 + (int64_t)t * kOrderThreads;
-          word[t] = 0;
-          f[t] = w[t] = 0;
-          if (x < total) {
-            f[t] = lvl_lo + (int)(x / W);
-            w[t] = (int)(x % W);
-            word[t] = bits[(int64_t)order[f[t]] * W + w[t]] & ~visited[w[t]];
+          for (int t = 0; t < kBatch; ++t) {
+            const int64_t x = x0 + (int64_t)t * kOrderThreads;
+            word[t] = 0;
+            f[t] = w[t] = 0;
+            if (x < total) {
+              f[t] = lvl_lo + (int)(x / W);
+              w[t] = (int)(x % W);
+              word[t] = bits[(int64_t)order[f[t]] * W + w[t]] & ~visited[w[t]];
+            }
+          }
+#pragma unroll
+          for (int t = 0; t < kBatch; ++t) {
+            uint64_t b = word[t];
+            while (b) {
+              const int v = 64 * w[t] + __builtin_ctzll(b);
+              b &= b - 1;
+              atomicMin(&parent_pos[v], f[t]);  // result unused: a thread's atomics pipeline instead of each waiting for its return
+              const unsigned long long bit = 1ull << (v & 63);
+              if (!(atomicOr(reinterpret_cast<unsigned long long*>(&claimed[v >> 6]), bit) & bit)) cand[atomicAdd(&count_s, 1)] = v;
+            }
           }
         }
-#pragma unroll
-        for (int t = 0; t < kBatch; ++t) {
-          uint64_t b = word[t];
-          while (b) {
-            const int v = 64 * w[t] + __builtin_ctzll(b);
-            b &= b - 1;
-            atomicMin(&parent_pos[v], f[t]);  // result unused: the atomics of a thread pipeline instead of each waiting for its return
-            const unsigned long long bit = 1ull << (v & 63);
-            if (!(atomicOr(reinterpret_cast<unsigned long long*>(&claimed[v >> 6]), bit) & bit)) cand[atomicAdd(&count_s, 1)] = v;
-          }
+        sync_global();
+        const int L = count_s;
+        for (int c = tid; c < L; c += kOrderThreads) {
+          const int v = cand[c];
+          keys[c] = level_key(parent_pos[v], degree[v], v);
         }
+        sync_global();
+        rank_level(keys, L, chunk_s, tid, [&](int r, int v) {
+          order[n_done + r] = v;
+          atomicOr(reinterpret_cast<unsigned long long*>(&visited[v >> 6]), 1ull << (v & 63));
+        });
+        if (tid == 0) count_s = 0;
+        lvl_lo = lvl_hi;
+        lvl_hi = n_done + L;
+        n_done += L;
+        sync_global();
       }
-      sync_global();
-      const int L = count_s;
-      // sort keys: (position of the earliest parent, degree, index)
-      for (int c = tid; c < L; c += kOrderThreads) {
-        const int v = cand[c];
-        keys[c] = ((uint64_t)(uint32_t)parent_pos[v] << 40) | ((uint64_t)(uint32_t)degree[v] << 20) | (uint64_t)(uint32_t)v;
+      // ---- next component
+      const int start = min_degree_unvisited(degree, N, [&](int w) { return visited[w]; }, min_s, tid);
+      if (start < 0) break;
+      if (tid == 0) {
+        order[n_done] = start;
+        visited[start >> 6] |= 1ull << (start & 63);
       }
-      sync_global();
-      // rank by counting (keys are distinct), place, mark visited.  The keys pass through LDS in chunks; a thread
-      // ranks up to kRankPerThread keys per sweep over the level.
-      for (int c0 = 0; c0 < L; c0 += kRankPerThread * kOrderThreads) {
-        uint64_t mine[kRankPerThread];
-        int r[kRankPerThread];
-#pragma unroll
-        for (int t = 0; t < kRankPerThread; ++t) {
-          const int c = c0 + t * kOrderThreads + tid;
-          mine[t] = c < L ? keys[c] : 0;
-          r[t] = 0;
-        }
-        for (int j0 = 0; j0 < L; j0 += kRankChunk) {
-          const int n = min(kRankChunk, L - j0);
-          __syncthreads();  // the previous chunk has been read
-          for (int j = tid; j < n; j += kOrderThreads) chunk_s[j] = keys[j0 + j];
-          __syncthreads();
-          for (int j = 0; j < n; ++j) {
-            const uint64_t kj = chunk_s[j];
-#pragma unroll
-            for (int t = 0; t < kRankPerThread; ++t) r[t] += kj < mine[t] ? 1 : 0;
-          }
-        }
-#pragma unroll
-        for (int t = 0; t < kRankPerThread; ++t) {
-          if (c0 + t * kOrderThreads + tid < L) {
-            const int v = (int)(mine[t] & 0xfffffull);
-            order[n_done + r[t]] = v;
-            atomicOr(reinterpret_cast<unsigned long long*>(&visited[v >> 6]), 1ull << (v & 63));
-          }
-        }
-      }
-      if (tid == 0) count_s = 0;
-      lvl_lo = lvl_hi;
-      lvl_hi = n_done + L;
-      n_done += L;
+      lvl_lo = n_done;
+      lvl_hi = n_done + 1;
+      n_done += 1;
       sync_global();
     }
   }
+  sync_global();
   // the ordering reversed
   for (int k = tid; k < N; k += kOrderThreads) perm[k] = order[N - 1 - k];
 }
@@ -242,7 +358,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restric
 
 inline size_t round256(size_t n) { return (n + 255) / 256 * 256; }
 struct RcmLayout {
-  size_t bits, degree, parent, order, cand, keys, total;
+  size_t bits, degree, parent, order, cand, keys, visited, claimed, state, total;
   explicit RcmLayout(int64_t N) {
     const size_t W = (size_t)((N + 63) / 64);
     size_t o = 0;
@@ -258,6 +374,12 @@ struct RcmLayout {
     o += round256((size_t)N * 4);
     keys = o;
     o += round256((size_t)N * 8);
+    visited = o;
+    o += round256(W * 8);
+    claimed = o;
+    o += round256(W * 8);
+    state = o;
+    o += round256(kStInts * 4);
     total = o;
   }
 };
@@ -291,10 +413,22 @@ extern "C" __attribute__((visibility("default"))) int bbm_rcm_order(const uint8_
   uint64_t* keys = reinterpret_cast<uint64_t*>(ws + lay.keys);
   const int W = (int)ceil_div(N, 64);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rcm_pack_kernel<<<(unsigned)N, kPackThreads, 0, s>>>(mask, (int)N, row_stride_bytes, W, bits, degree, parent);
+  uint64_t* visited = reinterpret_cast<uint64_t*>(ws + lay.visited);
+  uint64_t* claimed = reinterpret_cast<uint64_t*>(ws + lay.claimed);
+  int32_t* state = reinterpret_cast<int32_t*>(ws + lay.state);
+  rcm_pack_kernel<<<(unsigned)N, kPackThreads, 0, s>>>(mask, (int)N, row_stride_bytes, W, bits, degree, parent, visited, claimed, state);
   int rc = launch_status("bbm_rcm_order (pack)");
   if (rc != BBM_OK) return rc;
-  rcm_order_kernel<<<1, kOrderThreads, 0, s>>>(bits, degree, parent, order, cand, keys, (int)N, W, perm);
+  // the first advance starts the first component; then kRounds rounds of (parallel expansion, advance); the finisher
+  // walks whatever is left and writes perm.  Kernels that find the walk finished return at once.
+  rcm_advance_kernel<<<1, kOrderThreads, 0, s>>>(degree, parent, cand, keys, order, visited, state, (int)N);
+  for (int r = 0; r < kRounds; ++r) {
+    rcm_expand_kernel<<<kExpandWGs, kExpandThreads, 0, s>>>(bits, order, visited, claimed, parent, cand, state, W);
+    rcm_advance_kernel<<<1, kOrderThreads, 0, s>>>(degree, parent, cand, keys, order, visited, state, (int)N);
+  }
+  rc = launch_status("bbm_rcm_order (rounds)");
+  if (rc != BBM_OK) return rc;
+  rcm_finish_kernel<<<1, kOrderThreads, 0, s>>>(bits, degree, parent, order, cand, keys, visited, state, (int)N, W, perm);
   return launch_status("bbm_rcm_order");
 }
 
