@@ -103,3 +103,20 @@ def test_joint_permutation_commutes_with_attention():
     Op, lp = oracle.masked_attention(q[:, :, perm], k[:, :, perm], v[:, :, perm], oracle.permute_mask(A, perm))
     inv = np.argsort(perm)
     assert np.abs(Op[:, :, inv] - O).max() < 1e-12 and np.abs(lp[:, :, inv] - lse).max() < 1e-12
+
+
+def test_hand_worked_example():
+    """Edges 0-1, 0-2, 1-3, 2-3, 3-4 and self loops: degrees 3, 3, 3, 4, 2.  The walk starts at node 4 (minimum
+    degree), reaches 3, then 1 and 2 (same parent, same degree: by index), then 0 (claimed by 1, the earlier parent)."""
+    A = np.eye(5, dtype=np.uint8)
+    for i, j in ((0, 1), (0, 2), (1, 3), (2, 3), (3, 4)):
+        A[i, j] = A[j, i] = 1
+    assert oracle.cuthill_mckee_order(A).tolist() == [4, 3, 1, 2, 0]
+    assert oracle.reverse_cuthill_mckee(A).tolist() == [0, 2, 1, 3, 4]
+    # a lower degree wins over a lower index inside a level: give node 2 a pendant neighbour 5
+    B = np.eye(6, dtype=np.uint8)
+    for i, j in ((0, 1), (0, 2), (1, 3), (2, 3), (3, 4), (2, 5)):
+        B[i, j] = B[j, i] = 1
+    # degrees 3, 3, 4, 4, 2, 2: start 4 (degree 2, lower index than 5); 3; then 1 (degree 3) before 2 (degree 4);
+    # then 0 (parent 1), then 5 (parent 2)
+    assert oracle.cuthill_mckee_order(B).tolist() == [4, 3, 1, 2, 0, 5]
