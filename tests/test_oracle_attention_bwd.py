@@ -155,3 +155,19 @@ def test_bf16_bit_inputs_are_widened_exactly():
     b = oracle.masked_attention_bwd(*(oracle.bf16_bits_to_f64(x) for x in (qb, kb, vb)), mask, oracle.bf16_bits_to_f64(dob))
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+def test_hand_worked_two_by_two():
+    """N = 2, d = 1, scale = 1, q = 0 (uniform p = 1/2), k = (2, 5), v = (1, 3), dO = (1, 1), all pairs allowed:
+    O = 2; dV_j = 1/2 + 1/2 = 1; dP_i = (1, 3), D_i = 2, dS_i = (-1/2, +1/2); dQ_i = -1/2*2 + 1/2*5 = 3/2; dK = 0."""
+    q = np.zeros((1, 1, 2, 1))
+    k = np.array([2.0, 5.0]).reshape(1, 1, 2, 1)
+    v = np.array([1.0, 3.0]).reshape(1, 1, 2, 1)
+    do = np.ones((1, 1, 2, 1))
+    dQ, dK, dV = oracle.masked_attention_bwd(q, k, v, np.ones((1, 2, 2), dtype=np.uint8), do, scale=1.0)
+    assert np.allclose(dQ.ravel(), [1.5, 1.5], atol=1e-15) and np.allclose(dK.ravel(), [0, 0], atol=1e-15)
+    assert np.allclose(dV.ravel(), [1.0, 1.0], atol=1e-15)
+    # mask out key 1 for query 0: its row sees one key only (p = 1, dS = 0, dQ_0 = 0); dV_0 = 1 + 1/2, dV_1 = 1/2
+    m = np.array([[[1, 0], [1, 1]]], dtype=np.uint8)
+    dQ, dK, dV = oracle.masked_attention_bwd(q, k, v, m, do, scale=1.0)
+    assert np.allclose(dQ.ravel(), [0.0, 1.5], atol=1e-15) and np.allclose(dV.ravel(), [1.5, 0.5], atol=1e-15)
