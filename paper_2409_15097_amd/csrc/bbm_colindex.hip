@@ -55,6 +55,61 @@ __global__ __launch_bounds__(kColThreads) void col_index_kernel(const uint8_t* _
   if (tid == 0) cp[nbc] = base;
 }
 
+// The same list in three small launches for larger class matrices (a plane of more than kColOneKernelRows block rows):
+// one WAVE per block column, its lanes over 64 block rows at a time (count; scan over the columns of a plane; fill).
+constexpr int kColOneKernelRows = 64;
+constexpr int kColWaves = 4;
+
+__global__ __launch_bounds__(kColWaves * 64) void col_count_kernel(const uint8_t* __restrict__ cls, int64_t Mb, int nbr, int nbc,
+                                                                   int32_t* __restrict__ col_ptr) {
+  const int lane = threadIdx.x & 63;
+  const int64_t col = (int64_t)blockIdx.x * kColWaves + (threadIdx.x >> 6);
+  if (col >= Mb * nbc) return;
+  const int64_t m = col / nbc, j = col - m * nbc;
+  const uint8_t* __restrict__ c = cls + m * nbr * nbc + j;
+  int cnt = 0;
+  for (int base = 0; base < nbr; base += 64) {
+    const uint8_t v = (base + lane < nbr) ? c[(int64_t)(base + lane) * nbc] : (uint8_t)0;
+    cnt += __popcll(__ballot(v != BBM_BLOCK_EMPTY));
+  }
+  if (lane == 0) col_ptr[m * (nbc + 1) + j + 1] = cnt;
+}
+
+// In-place inclusive scan of col_ptr[m][1..nbc], one wave per plane.
+__global__ __launch_bounds__(64) void col_scan_kernel(int nbc, int32_t* __restrict__ col_ptr) {
+  const int lane = threadIdx.x;
+  int32_t* p = col_ptr + (int64_t)blockIdx.x * (nbc + 1);
+  int carry = 0;
+  for (int base = 0; base < nbc; base += 64) {
+    int x = (base + lane < nbc) ? p[base + lane + 1] : 0;
+    for (int s = 1; s < 64; s <<= 1) {
+      const int y = __shfl_up(x, s);
+      if (lane >= s) x += y;
+    }
+    x += carry;
+    if (base + lane < nbc) p[base + lane + 1] = x;
+    carry = __shfl(x, 63);
+  }
+  if (lane == 0) p[0] = 0;
+}
+
+__global__ __launch_bounds__(kColWaves * 64) void col_fill_kernel(const uint8_t* __restrict__ cls, int64_t Mb, int nbr, int nbc,
+                                                                  const int32_t* __restrict__ col_ptr, uint32_t* __restrict__ row_idx) {
+  const int lane = threadIdx.x & 63;
+  const int64_t col = (int64_t)blockIdx.x * kColWaves + (threadIdx.x >> 6);
+  if (col >= Mb * nbc) return;
+  const int64_t m = col / nbc, j = col - m * nbc;
+  const uint8_t* __restrict__ c = cls + m * nbr * nbc + j;
+  uint32_t* __restrict__ out = row_idx + m * nbr * nbc + col_ptr[m * (nbc + 1) + j];
+  int written = 0;
+  for (int base = 0; base < nbr; base += 64) {
+    const uint8_t v = (base + lane < nbr) ? c[(int64_t)(base + lane) * nbc] : (uint8_t)0;
+    const uint64_t nz = __ballot(v != BBM_BLOCK_EMPTY);
+    if (v != BBM_BLOCK_EMPTY) out[written + __popcll(nz & ((1ull << lane) - 1ull))] = (uint32_t)(base + lane) | (v == BBM_BLOCK_FULL ? 0x80000000u : 0u);
+    written += __popcll(nz);
+  }
+}
+
 // Split schedule of the column walk: columns with more than T = max(kColSchedMinSplit, 2 * mean entries per non-empty
 // column) list entries are cut into ceil(n/T) near-equal parts; work-group 0 scans all Mb*nbc columns for that.
 // Work-group 1 + m writes the launch-order records of plane m: columns by list length, longest first (ties: the
@@ -202,7 +257,16 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_col_index(const 
   if (col_sched && !aligned(col_sched, 32)) return fail(BBM_EINVAL, "bbm_build_col_index: col_sched must be 32-byte aligned");
   if (col_sched && Mb * nbc >= (1ll << 24)) return fail(BBM_EINVAL, "bbm_build_col_index: Mb*nbc must be below 2^24 for a schedule");
   if (nbr * nbc >= (1ll << 31) || Mb >= (1ll << 31)) return fail(BBM_EINVAL, "bbm_build_col_index: nbr*nbc and Mb must be below 2^31");
-  col_index_kernel<<<(unsigned)Mb, kColThreads, 0, static_cast<hipStream_t>(stream)>>>(blk_class, (int)nbr, (int)nbc, col_ptr, row_idx);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (nbr <= kColOneKernelRows) {
+    col_index_kernel<<<(unsigned)Mb, kColThreads, 0, st>>>(blk_class, (int)nbr, (int)nbc, col_ptr, row_idx);
+  } else {
+    if (ceil_div(Mb * nbc, kColWaves) >= (1ll << 31)) return fail(BBM_EINVAL, "bbm_build_col_index: Mb*nbc too large");
+    const unsigned grid = (unsigned)ceil_div(Mb * nbc, kColWaves);
+    col_count_kernel<<<grid, kColWaves * 64, 0, st>>>(blk_class, Mb, (int)nbr, (int)nbc, col_ptr);
+    col_scan_kernel<<<(unsigned)Mb, 64, 0, st>>>((int)nbc, col_ptr);
+    col_fill_kernel<<<grid, kColWaves * 64, 0, st>>>(blk_class, Mb, (int)nbr, (int)nbc, col_ptr, row_idx);
+  }
   int rc = launch_status("bbm_build_col_index");
   if (rc != BBM_OK || !col_sched) return rc;
   col_sched_kernel<<<(unsigned)(1 + Mb), kColSchedThreads, 0, static_cast<hipStream_t>(stream)>>>(col_ptr, row_idx, (int)Mb, (int)nbr, (int)nbc, col_sched);
