@@ -815,8 +815,7 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   P.hbp = (int32_t)(Mb == 1 ? B * H : H);
   P.n_extra = 0;
   P.split = 1;
-  // interleave the planes that one XCD's share of the launch spans (at most 8: their K and V should stay in its L2)
-  P.G = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, (B * H * nbr / 8) / nbr));
+  P.G = interleaved_planes(B * H, 2 * Nk * d * (int64_t)sizeof(__bf16));
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (d == 64) {
     if (idx->Br == 64) return launch<64, 2>(P, Mb, workspace, s);

@@ -450,12 +450,19 @@ __global__ __launch_bounds__(NW * 64, (D == 128 && NW >= 4) ? 2 : 1) void attn_b
 // ------------------------------------------------------------------------------------------------------------------
 // dK, dV
 // ------------------------------------------------------------------------------------------------------------------
-// One work-group (2 waves) per (block column, batch, head); the first P.n_extra work-groups first serve the queue of
+// One work-group per (block column, batch, head); the first P.n_extra work-groups first serve the queue of
 // the parts of cut block columns, as the dQ kernel does for cut block rows.
-template <int D>
-__global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
+// RS = false: two waves, one per key half (32 keys); each computes all four products for its keys.
+// RS = true: four waves, (key half) x (role).  Role 0 computes S, P and dV, role 1 computes dP, dS and dK; P (rounded to
+// bf16, as the dV product consumes it) crosses from role 0 to role 1 through LDS at a barrier in the middle of a step.
+// Each wave then holds one operand (K or V) and one accumulator set, about half the registers: at D = 128, where the
+// tile buffers let two work-groups share a CU, that puts two waves on every SIMD instead of one, and one wave's
+// exponentials and LDS reads run under the other's matrix products.
+template <int D, bool RS>
+__global__ __launch_bounds__(RS ? 256 : 128, RS ? 2 : 1) void attn_bwd_dkv_kernel(const BwdParams P) {
   using L = TL<D>;
-  constexpr int NW = 2, NT = 128;
+  constexpr int NW = RS ? 4 : 2, NT = 64 * NW;
+  constexpr int NTP = 128;  // lanes per role: stride of the parked records
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
   constexpr int REGS = DB * 16;
@@ -473,9 +480,12 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
   __shared__ __attribute__((aligned(16))) uint32_t mk_s1[2][64];
   __shared__ uint32_t tiles_s[kWin];
   __shared__ int item_s[2];
+  __shared__ __attribute__((aligned(16))) bf16x8 p_s[RS ? 2 : 1][4][64];  // RS: P of [key half][16-query step][lane]
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // = key half of the column block
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kh = wave & 1;              // key half of the column block
+  const int role = RS ? wave >> 1 : 0;  // RS: 0 = S, P, dV; 1 = dP, dS, dK
   const int lq = lane & 31, hh = lane >> 5;
   const int64_t N = P.N;
   const float c = P.scale * kLog2e;
@@ -488,8 +498,8 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
   const float* __restrict__ nlg;
   const float* __restrict__ ndg;
   const uint32_t* __restrict__ mcol;
-  bf16x8 kf[KS], vf[KS];
-  f32x16 dk[DB], dv[DB];
+  bf16x8 kf[KS], vf[KS];  // RS: kf is the wave's one operand (role 0: K scaled, role 1: V), vf unused
+  f32x16 dk[DB], dv[DB];  // RS: dk is the wave's one accumulator set (role 0: dV, role 1: dK), dv unused
 
   // this lane's key: K * scale * log2(e) and V as B operands (keys past N: zeros, never stored)
   auto begin_item = [&]() {
@@ -499,23 +509,39 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
     nlg = P.nl2 + (int64_t)bh * N;
     ndg = P.ndelta + (int64_t)bh * N;
     // this wave's 32-bit half of the packed mask words of block column j (one word per query row)
-    mcol = reinterpret_cast<const uint32_t*>(P.packed + ((int64_t)m * P.W + j) * N) + wave;
-    const int64_t krow = (int64_t)j * 64 + wave * 32 + lq;
+    mcol = reinterpret_cast<const uint32_t*>(P.packed + ((int64_t)m * P.W + j) * N) + kh;
+    const int64_t krow = (int64_t)j * 64 + kh * 32 + lq;
     const bool k_ok = krow < N;
+    if constexpr (RS) {
+      const __bf16* __restrict__ src = role == 0 ? P.k : P.v;
+      const float mult = role == 0 ? c : 1.0f;  // exact for V
 #pragma unroll
-    for (int t = 0; t < KS; ++t) {
-      if (k_ok) {
-        const int64_t at = head_off + krow * D + 16 * t + 8 * hh;
-        kf[t] = *reinterpret_cast<const bf16x8*>(P.k + at);
-        vf[t] = *reinterpret_cast<const bf16x8*>(P.v + at);
-      } else {
-        for (int e = 0; e < 8; ++e) kf[t][e] = vf[t][e] = (__bf16)0.0f;
+      for (int t = 0; t < KS; ++t) {
+        if (k_ok)
+          kf[t] = *reinterpret_cast<const bf16x8*>(src + head_off + krow * D + 16 * t + 8 * hh);
+        else
+          for (int e = 0; e < 8; ++e) kf[t][e] = (__bf16)0.0f;
+        for (int e = 0; e < 8; ++e) kf[t][e] = (__bf16)((float)kf[t][e] * mult);
       }
-      for (int e = 0; e < 8; ++e) kf[t][e] = (__bf16)((float)kf[t][e] * c);
-    }
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-      for (int e = 0; e < 16; ++e) dk[db][e] = dv[db][e] = 0.0f;
+      for (int db = 0; db < DB; ++db)
+        for (int e = 0; e < 16; ++e) dk[db][e] = 0.0f;
+    } else {
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        if (k_ok) {
+          const int64_t at = head_off + krow * D + 16 * t + 8 * hh;
+          kf[t] = *reinterpret_cast<const bf16x8*>(P.k + at);
+          vf[t] = *reinterpret_cast<const bf16x8*>(P.v + at);
+        } else {
+          for (int e = 0; e < 8; ++e) kf[t][e] = vf[t][e] = (__bf16)0.0f;
+        }
+        for (int e = 0; e < 8; ++e) kf[t][e] = (__bf16)((float)kf[t][e] * c);
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        for (int e = 0; e < 16; ++e) dk[db][e] = dv[db][e] = 0.0f;
+    }
   };
 
   TileAddr<D> A;
@@ -523,24 +549,28 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
 
   const int qs_shift = P.br == 64 ? 0 : P.br == 128 ? 1 : 2;  // 64-query sub-tiles per block row: 1, 2, 4
   // Requests sub-tile `sub` of list entry e into the buffers of one parity: Q and dO tiles, the negated statistics of
-  // its 64 queries (wave 0: -lse*log2 e, wave 1: -D), and this wave's half of the mask words if the block is partial.
-  // Query rows past N get -inf / 0 so that their probabilities are exactly 0.
+  // its 64 queries (-lse*log2 e and -D: one wave each), and the two 32-bit halves of the mask words if the block is
+  // partial (the waves of role 0, each its own half).  Query rows past N get -inf / 0 so that their probabilities are
+  // exactly 0.
   auto request = [&](uint32_t e, int sub, __bf16* qd, __bf16* gd, float* nld, float* ndd, uint32_t (*mkd)[64]) {
     const int64_t row0 = ((int64_t)(e & 0x7fffffffu) << qs_shift) * 64 + (int64_t)sub * 64;
     tile_copy_async<D, NW>(Qg, row0, N, qd, wave, lane);
     tile_copy_async<D, NW>(Gg, row0, N, gd, wave, lane);
     const int64_t r = row0 + lane;
-    float* const sd = wave == 0 ? nld : ndd;
-    const float* const sg = wave == 0 ? nlg : ndg;
-    if (r < N)
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sg + r),
-                                       (void __attribute__((address_space(3)))*)sd, 4, 0, 0);
-    else
-      sd[lane] = wave == 0 ? -INFINITY : 0.0f;
-    if ((e >> 31) == 0) {
+    const bool lse_wave = RS ? wave == 0 : wave == 0, delta_wave = RS ? wave == 2 : wave == 1;
+    if (lse_wave || delta_wave) {
+      float* const sd = lse_wave ? nld : ndd;
+      const float* const sg = lse_wave ? nlg : ndg;
+      if (r < N)
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sg + r),
+                                         (void __attribute__((address_space(3)))*)sd, 4, 0, 0);
+      else
+        sd[lane] = lse_wave ? -INFINITY : 0.0f;
+    }
+    if (role == 0 && (e >> 31) == 0) {
       const int64_t rc = min(r, N - 1);
       __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(mcol + 2 * rc),
-                                       (void __attribute__((address_space(3)))*)mkd[wave], 4, 0, 0);
+                                       (void __attribute__((address_space(3)))*)mkd[kh], 4, 0, 0);
     }
   };
 
@@ -566,7 +596,69 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
     }
     const bool partial = (e0 >> 31) == 0;
     // a partial sub-tile in which none of the 64 queries sees one of this wave's 32 keys contributes exact zeros
-    if (partial && __ballot(mk_cur[wave][lane] != 0u) == 0ull) return;
+    if constexpr (RS) {
+      const bool live = !partial || __ballot(mk_cur[kh][lane] != 0u) != 0ull;  // the same for both roles of a key half
+      f32x16 acc2[2];  // role 0: S^T, then P; role 1: dP^T
+      bf16x8 pf[4];
+      if (live) {
+        const float* const init = role == 0 ? nl_cur : nd_cur;
+        const __bf16* const rows = role == 0 ? q_cur : g_cur;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float4 a = *reinterpret_cast<const float4*>(init + 32 * qb + 8 * g + 4 * hh);
+            acc2[qb][4 * g + 0] = a.x, acc2[qb][4 * g + 1] = a.y, acc2[qb][4 * g + 2] = a.z, acc2[qb][4 * g + 3] = a.w;
+          }
+#pragma unroll
+          for (int t = 0; t < KS; ++t) acc2[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(rows, qb, t), kf[t], acc2[qb], 0, 0, 0);
+        }
+        if (role == 0) {
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb) {
+            float p[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) p[e] = __builtin_amdgcn_exp2f(acc2[qb][e]);
+            if (partial) {
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                const uint4 w = *reinterpret_cast<const uint4*>(&mk_cur[kh][32 * qb + 8 * g + 4 * hh]);
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)ww[e], lq, 1);  // all ones iff bit lq is set
+                  p[4 * g + e] = __uint_as_float(__float_as_uint(p[4 * g + e]) & keep);
+                }
+              }
+            }
+#pragma unroll
+            for (int u2 = 0; u2 < 2; ++u2) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) pf[2 * qb + u2][e] = (__bf16)p[8 * u2 + e];
+              p_s[kh][2 * qb + u2][lane] = pf[2 * qb + u2];
+            }
+          }
+        }
+      }
+      __syncthreads();  // P of this step is in LDS (the next step's first barrier comes after its last reader)
+      if (live) {
+        const __bf16* const cols = role == 0 ? g_cur : q_cur;
+        if (role != 0) {  // dS = P o dP, rounded to bf16, in place of P
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const bf16x8 pu = p_s[kh][u][lane];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[u][e] = (__bf16)((float)pu[e] * acc2[u >> 1][8 * (u & 1) + e]);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int db = 0; db < DB; ++db) dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(cols, u, db), pf[u], dk[db], 0, 0, 0);
+      }
+      return;
+    }
+    if (partial && __ballot(mk_cur[kh][lane] != 0u) == 0ull) return;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       f32x16 sc, dp;
@@ -587,7 +679,7 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
       if (partial) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const uint4 w = *reinterpret_cast<const uint4*>(&mk_cur[wave][32 * qb + 8 * g + 4 * hh]);
+          const uint4 w = *reinterpret_cast<const uint4*>(&mk_cur[kh][32 * qb + 8 * g + 4 * hh]);
           const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
@@ -631,10 +723,19 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
   };
 
   auto write_dkv = [&]() {
-    const int64_t row0 = (int64_t)j * 64 + wave * 32;
-    store_slab<D>(dk, P.scale, q_s0 + wave * 32 * D, P.dk + head_off, row0, N, lane);
-    store_slab<D>(dv, 1.0f, g_s0 + wave * 32 * D, P.dv + head_off, row0, N, lane);
+    const int64_t row0 = (int64_t)j * 64 + kh * 32;
+    if constexpr (RS) {
+      if (role == 0)
+        store_slab<D>(dk, 1.0f, g_s0 + kh * 32 * D, P.dv + head_off, row0, N, lane);
+      else
+        store_slab<D>(dk, P.scale, q_s0 + kh * 32 * D, P.dk + head_off, row0, N, lane);
+    } else {
+      store_slab<D>(dk, P.scale, q_s0 + kh * 32 * D, P.dk + head_off, row0, N, lane);
+      store_slab<D>(dv, 1.0f, g_s0 + kh * 32 * D, P.dv + head_off, row0, N, lane);
+    }
   };
+  // where this thread's sums sit in a parked record: [dK registers | dV registers][NTP lanes]
+  const int rec_lane = kh * 64 + lane, rec_reg0 = (RS && role == 0) ? REGS : 0;
 
   int nparts_all = 0, split_T = 0x7fffffff;
   if (P.csched) {
@@ -658,12 +759,12 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
       bh = (P.Mb == 1) ? hb : m * P.H + hb;
       begin_item();
       run_list(P.row_idx + (int64_t)m * P.nbr * P.nbc + p0, nt);
-      float* rec = P.col_partials + ((int64_t)(q_first + part) * P.hbp + hb) * (2 * REGS * NT) + tid;
+      float* rec = P.col_partials + ((int64_t)(q_first + part) * P.hbp + hb) * (2 * REGS * NTP) + rec_lane;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
         for (int e = 0; e < 16; ++e) {
-          rec[(db * 16 + e) * NT] = dk[db][e];
-          rec[(REGS + db * 16 + e) * NT] = dv[db][e];
+          rec[(rec_reg0 + db * 16 + e) * NTP] = dk[db][e];
+          if constexpr (!RS) rec[(REGS + db * 16 + e) * NTP] = dv[db][e];
         }
       // one thread publishes for the work-group: the barrier orders everyone's stores before its device-wide release,
       // and its acquire before everyone's reads after the second barrier (four times fewer fences than one per wave)
@@ -676,8 +777,8 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
       }
       __syncthreads();
       if (item_s[1] == nparts - 1) {
-        const float* r0 = P.col_partials + ((int64_t)q_first * P.hbp + hb) * (2 * REGS * NT) + tid;
-        const int64_t pstride = (int64_t)P.hbp * (2 * REGS * NT);
+        const float* r0 = P.col_partials + ((int64_t)q_first * P.hbp + hb) * (2 * REGS * NTP) + rec_lane;
+        const int64_t pstride = (int64_t)P.hbp * (2 * REGS * NTP);
 #pragma unroll
         for (int db = 0; db < DB; ++db)
           for (int e = 0; e < 16; ++e) dk[db][e] = dv[db][e] = 0.0f;
@@ -685,8 +786,8 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(const BwdParams P) {
 #pragma unroll
           for (int db = 0; db < DB; ++db)
             for (int e = 0; e < 16; ++e) {
-              dk[db][e] += r0[k * pstride + (db * 16 + e) * NT];
-              dv[db][e] += r0[k * pstride + (REGS + db * 16 + e) * NT];
+              dk[db][e] += r0[k * pstride + (rec_reg0 + db * 16 + e) * NTP];
+              if constexpr (!RS) dv[db][e] += r0[k * pstride + (REGS + db * 16 + e) * NTP];
             }
         }
         write_dkv();
@@ -750,7 +851,7 @@ template <int D>
 int launch_bwd(BwdParams& P, int64_t B, int64_t H, hipStream_t s) {
   P.total_wgs = (int32_t)(B * H * P.nbr);
   P.n_extra = std::min<int32_t>(P.total_wgs, kExtraWGs);
-  P.G = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, (B * H * P.nbr / 8) / P.nbr));
+  P.G = bbm::interleaved_planes(B * H, 2 * P.N * D * (int64_t)sizeof(__bf16));
   if (P.br == 64)
     attn_bwd_dq_kernel<D, 2><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
   else if (P.br == 128)
@@ -761,8 +862,9 @@ int launch_bwd(BwdParams& P, int64_t B, int64_t H, hipStream_t s) {
   if (rc != BBM_OK) return rc;
   P.total_wgs = (int32_t)(B * H * P.nbc);
   P.n_extra = std::min<int32_t>(P.total_wgs, kExtraWGs);
-  P.Gc = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, (B * H * P.nbc / 8) / P.nbc));
-  attn_bwd_dkv_kernel<D><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
+  P.Gc = P.G;
+  constexpr bool RS = D == 128;
+  attn_bwd_dkv_kernel<D, RS><<<(unsigned)P.total_wgs, RS ? 256 : 128, 0, s>>>(P);
   return bbm::launch_status("bbm_attn_bwd (dk, dv)");
 }
 
