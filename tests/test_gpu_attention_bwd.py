@@ -68,6 +68,30 @@ def test_column_index_of_a_plane_with_more_than_4096_block_columns():
     assert got[-4 * 4100:].reshape(4100, 4)[:, 0].tolist() == list(range(4099, -1, -1))
 
 
+def test_column_index_of_planes_with_more_than_64_block_rows():
+    """Class matrices of more than 64 block rows take the three-launch path (one wave per block column, 64 block rows
+    per ballot step): 130 rows = two full steps and a ragged one, 71 columns = a ragged last work-group, an empty and a
+    completely full column, two planes."""
+    bbm = _bbm()
+    from paper_2409_15097_amd.binding import BlockIndex
+    rng = np.random.default_rng(43)
+    Mb, nbr, nbc = 2, 130, 71
+    cls = rng.choice(np.array([0, 0, 1, 2], dtype=np.uint8), size=(Mb, nbr, nbc))
+    cls[:, :, 5] = 0
+    cls[1, :, 9] = 2
+    idx = BlockIndex(128, 64, Mb, nbr, nbc, nbc * 64, blk_class=torch.from_numpy(cls).cuda())
+    bbm.bbm_build_col_index(idx)
+    torch.cuda.synchronize()
+    cp, ri = oracle.column_index(cls)
+    cs = oracle.column_schedule(cp, ri)
+    assert np.array_equal(idx.col_ptr.cpu().numpy(), cp)
+    got_ri = idx.row_idx.cpu().numpy().view(np.uint32)
+    cap = nbr * nbc
+    for m in range(Mb):
+        assert np.array_equal(got_ri[m * cap: m * cap + cp[m, -1]], ri[m * cap: m * cap + cp[m, -1]])
+    assert np.array_equal(idx.col_sched.cpu().numpy(), cs)
+
+
 SMALL = [("C1", 256, 1, 2), ("C2", 1024, 2, 2), ("C3", 640, 1, 2), ("C4", 2048, 1, 2), ("C5", 2048, 1, 2),
          ("C0d", 512, 1, 2), ("C0c", 512, 1, 2), ("C2b", 1024, 2, 2), ("C4w", 1024, 1, 2), ("C4d", 1024, 1, 2)]
 
