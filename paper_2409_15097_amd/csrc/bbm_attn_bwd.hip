@@ -557,7 +557,7 @@ __global__ __launch_bounds__(RS ? 256 : 128, RS ? 2 : 1) void attn_bwd_dkv_kerne
     tile_copy_async<D, NW>(Qg, row0, N, qd, wave, lane);
     tile_copy_async<D, NW>(Gg, row0, N, gd, wave, lane);
     const int64_t r = row0 + lane;
-    const bool lse_wave = RS ? wave == 0 : wave == 0, delta_wave = RS ? wave == 2 : wave == 1;
+    const bool lse_wave = wave == 0, delta_wave = wave == (RS ? 2 : 1);  // one wave of each role when the roles are split
     if (lse_wave || delta_wave) {
       float* const sd = lse_wave ? nld : ndd;
       const float* const sg = lse_wave ? nlg : ndg;
