@@ -190,7 +190,7 @@ __device__ __forceinline__ int logical_wg(int wg, int total) {
 // row's last part adds the parts up in part order and writes the row, and the row's own work-group only writes the
 // statistics.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, (D == 128 && NW >= 4) ? 2 : 1) void attn_bwd_dq_kernel(const BwdParams P) {
+__global__ __launch_bounds__(NW * 64, (D == 128 && NW >= 4) ? 2 : (D == 64 && NW == 4) ? 3 : 1) void attn_bwd_dq_kernel(const BwdParams P) {
   using L = TL<D>;
   constexpr int NT = NW * 64;
   constexpr int BR = NW * 32;
