@@ -174,6 +174,24 @@ def test_single_allowed_key_routes_dO_to_dV():
     assert np.abs(bf16_result_to_f64(dq)).max() <= 2e-2 and np.abs(bf16_result_to_f64(dk)).max() <= 2e-2
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_key_permutation_permutes_dk_dv_and_leaves_dq(d):
+    """Permuting keys/values together with the mask columns scrambles the block matrix (and with it every list,
+    schedule and skipped tile); dQ must not move and dK, dV must move with their keys."""
+    cfg = small_variant("C2", N=1024, B=1, H=2)
+    if d == 128:
+        q, k, v = make_qkv(1, 2, 1024, 128, seed=77)
+        cfg = dict(cfg, q=q, k=k, v=v)
+    do = _d_o(*cfg["q"].shape)
+    pi = np.random.default_rng(5).permutation(1024)
+    cfg2 = dict(q=cfg["q"], k=cfg["k"][:, :, pi].copy(), v=cfg["v"][:, :, pi].copy(), mask=cfg["mask"][:, :, pi].copy())
+    dq2, dk2, dv2 = (bf16_result_to_f64(g) for g in _gpu_grads(cfg2, do, 128))
+    ref = oracle.masked_attention_bwd(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], do)
+    assert_grad_close("dQ", dq2, ref[0])
+    assert_grad_close("dK", dk2, ref[1][:, :, pi])
+    assert_grad_close("dV", dv2, ref[2][:, :, pi])
+
+
 def test_deterministic():
     cfg = small_variant("C4", N=2048, B=1, H=2)
     do = _d_o(*cfg["q"].shape)
