@@ -304,10 +304,6 @@ __device__ __forceinline__ int wave_excl_scan(int x, int lane) {  // exclusive p
   }
   return incl - x;
 }
-__device__ __forceinline__ int wave_sum(int x) {
-  for (int d = 32; d > 0; d >>= 1) x += __shfl_xor(x, d);
-  return x;
-}
 
 __global__ __launch_bounds__(kTinyMaxPlanes * 64) void tiny_index_kernel(const uint8_t* __restrict__ cls, int Mb, int nbr,
                                                                         int nbc, int32_t* __restrict__ row_ptr,
@@ -352,8 +348,12 @@ __global__ __launch_bounds__(kTinyMaxPlanes * 64) void tiny_index_kernel(const u
 #pragma unroll
   for (int ch = 0; ch < kTinyMaxChunks; ++ch) c += __popcll(nz[ch]);
 
-  // ---- list: position by a scan over the rows of the plane, entries written row by row
-  const int start = wave_excl_scan(c, lane);
+  // ---- list: position by a scan over the rows of the plane, entries written row by row.  A cross-lane step costs
+  // an LDS round trip, so two quantities share each scan (counts stay below 2^16: at most 64 rows of at most 256
+  // entries) and totals are read from lane 63 of the scan instead of being reduced again.
+  const int packed_c = c | ((c > 0 ? 1 : 0) << 16);
+  const int scan_c = wave_excl_scan(packed_c, lane);
+  const int start = scan_c & 0xffff;
   if (live) {
     row_ptr[(int64_t)m * (nbr + 1) + i] = start;
     if (i == nbr - 1) row_ptr[(int64_t)m * (nbr + 1) + nbr] = start + c;
@@ -381,7 +381,8 @@ __global__ __launch_bounds__(kTinyMaxPlanes * 64) void tiny_index_kernel(const u
   if (!sched) return;
 
   // ---- schedule (same definition as sched_kernel)
-  const int plane_total = wave_sum(c), plane_nonempty = wave_sum(c > 0 ? 1 : 0);
+  const int last_c = __builtin_amdgcn_readlane(scan_c + packed_c, 63);
+  const int plane_total = last_c & 0xffff, plane_nonempty = last_c >> 16;
   if (lane == 0) {
     tot_s[m][0] = plane_total;
     tot_s[m][1] = plane_nonempty;
@@ -396,8 +397,11 @@ __global__ __launch_bounds__(kTinyMaxPlanes * 64) void tiny_index_kernel(const u
   const int mean = nonempty > 0 ? (total + nonempty - 1) / nonempty : 0;
   const int T = max(kSchedMinSplit, 2 * mean);
   const int np = c > T ? (c + T - 1) / T : 0;
-  const int q_in_plane = wave_excl_scan(np, lane), rho_in_plane = wave_excl_scan(np > 0 ? 1 : 0, lane);
-  const int plane_parts = wave_sum(np), plane_cut = wave_sum(np > 0 ? 1 : 0);
+  const int packed_np = np | ((np > 0 ? 1 : 0) << 16);
+  const int scan_np = wave_excl_scan(packed_np, lane);
+  const int q_in_plane = scan_np & 0xffff, rho_in_plane = scan_np >> 16;
+  const int last_np = __builtin_amdgcn_readlane(scan_np + packed_np, 63);
+  const int plane_parts = last_np & 0xffff, plane_cut = last_np >> 16;
   if (lane == 0) {
     part_s[m][0] = plane_parts;
     part_s[m][1] = plane_cut;
