@@ -296,12 +296,17 @@ __device__ __forceinline__ uint32_t class_bits16(uint4 x) {
   return nz | ((~ne & 0xffffu) << 16);
 }
 
-__device__ __forceinline__ int wave_excl_scan(int x, int lane) {  // exclusive prefix sum over the 64 lanes
+// Exclusive prefix sum over the 64 lanes with data-parallel-primitive moves (register to register; a shuffle goes
+// through LDS): shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane without a source adds 0), then lane 15 of a
+// row added to the next row (rows 1 and 3), then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int wave_excl_scan(int x, int /*lane*/) {
   int incl = x;
-  for (int d = 1; d < 64; d <<= 1) {
-    const int y = __shfl_up(incl, d);
-    if (lane >= d) incl += y;
-  }
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xf, 0xf, false);  // row_shr:1
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xf, 0xf, false);  // row_shr:2
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xf, 0xf, false);  // row_shr:4
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, false);  // row_shr:8
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
   return incl - x;
 }
 
