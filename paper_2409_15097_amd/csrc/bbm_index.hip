@@ -46,12 +46,14 @@ struct RunScan {
   }
 };
 
-// One wave per block row.
+// One wave per block row.  With `row_ptr` (rows per plane: nbr) the row's count of non-zero blocks is also left at
+// row_ptr[m][i+1], which is pass 1 of the list: the index stage in one call then needs no list_count_kernel.
 __global__ __launch_bounds__(kWavesPerWG * 64) void runs_kernel(const uint8_t* __restrict__ cls, int64_t rows_total,
                                                                 int64_t nbc, int32_t* __restrict__ offset,
                                                                 int32_t* __restrict__ total_ones,
                                                                 int32_t* __restrict__ nz_lo, int32_t* __restrict__ nz_hi,
-                                                                int32_t* __restrict__ nz_cnt) {
+                                                                int32_t* __restrict__ nz_cnt, int32_t* __restrict__ row_ptr,
+                                                                int64_t nbr) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * kWavesPerWG + (threadIdx.x >> 6);
   if (row >= rows_total) return;
@@ -68,6 +70,10 @@ __global__ __launch_bounds__(kWavesPerWG * 64) void runs_kernel(const uint8_t* _
     nz_lo[row] = rs.lo;
     nz_hi[row] = rs.hi;
     nz_cnt[row] = rs.cnt;
+    if (row_ptr) {
+      const int64_t m = row / nbr, i = row - m * nbr;
+      row_ptr[m * (nbr + 1) + i + 1] = rs.cnt;
+    }
   }
 }
 
@@ -681,10 +687,10 @@ int check_list_args(const char* fn, const uint8_t* blk_class, int64_t Mb, int64_
 }
 
 int launch_runs(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset, int32_t* total_ones,
-                int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt, hipStream_t s) {
+                int32_t* nz_lo, int32_t* nz_hi, int32_t* nz_cnt, int32_t* row_ptr_counts, hipStream_t s) {
   const int64_t rows = Mb * nbr;
   runs_kernel<<<(unsigned)bbm::ceil_div(rows, kWavesPerWG), kWavesPerWG * 64, 0, s>>>(blk_class, rows, nbc, offset, total_ones,
-                                                                                    nz_lo, nz_hi, nz_cnt);
+                                                                                    nz_lo, nz_hi, nz_cnt, row_ptr_counts, nbr);
   return bbm::launch_status("bbm_build_runs");
 }
 
@@ -710,15 +716,19 @@ bool launch_one_kernel(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_
   return false;
 }
 
+// `counted`: the per-row counts are already at row_ptr[m][i+1] (left there by runs_kernel on the same stream).
 int launch_list(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* row_ptr, uint32_t* col_idx,
-                int32_t* sched, hipStream_t s) {
+                int32_t* sched, bool counted, hipStream_t s) {
   using namespace bbm;
-  if (launch_one_kernel(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, nullptr, nullptr, nullptr, nullptr, nullptr, s))
+  if (!counted && launch_one_kernel(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, nullptr, nullptr, nullptr, nullptr, nullptr, s))
     return launch_status("bbm_build_sparse_index(one launch)");
   const unsigned grid = (unsigned)ceil_div(Mb * nbr, kWavesPerWG);
-  list_count_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr);
-  int rc = launch_status("bbm_build_sparse_index(count)");
-  if (rc) return rc;
+  int rc = BBM_OK;
+  if (!counted) {
+    list_count_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr);
+    rc = launch_status("bbm_build_sparse_index(count)");
+    if (rc) return rc;
+  }
   list_scan_kernel<<<(unsigned)Mb, 64, 0, s>>>(nbr, row_ptr);
   rc = launch_status("bbm_build_sparse_index(scan)");
   if (rc) return rc;
@@ -736,7 +746,7 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_runs(const uint8
   bbm::clear_error();
   const int rc = check_runs_args("bbm_build_runs", blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt);
   if (rc) return rc;
-  return launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, static_cast<hipStream_t>(stream));
+  return launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" __attribute__((visibility("default"))) size_t bbm_sched_bytes(int64_t Mb, int64_t nbr) {
@@ -749,7 +759,7 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_sparse_index(con
   bbm::clear_error();
   const int rc = check_list_args("bbm_build_sparse_index", blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched);
   if (rc) return rc;
-  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, static_cast<hipStream_t>(stream));
+  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, false, static_cast<hipStream_t>(stream));
 }
 
 extern "C" __attribute__((visibility("default"))) int bbm_build_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset,
@@ -764,7 +774,7 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_index(const uint
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (launch_one_kernel(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, offset, total_ones, nz_lo, nz_hi, nz_cnt, s))
     return launch_status("bbm_build_index(one launch)");
-  rc = launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, s);
+  rc = launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, row_ptr, s);  // also pass 1 of the list
   if (rc) return rc;
-  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, s);
+  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, true, s);
 }
