@@ -46,6 +46,20 @@ struct RunScan {
   }
 };
 
+// Exclusive prefix sum over the 64 lanes with data-parallel-primitive moves (register to register; a shuffle goes
+// through LDS): shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane without a source adds 0), then lane 15 of a
+// row added to the next row (rows 1 and 3), then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int wave_excl_scan(int x, int /*lane*/) {
+  int incl = x;
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xf, 0xf, false);  // row_shr:1
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xf, 0xf, false);  // row_shr:2
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xf, 0xf, false);  // row_shr:4
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, false);  // row_shr:8
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+  incl += __builtin_amdgcn_update_dpp(0, incl, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
+  return incl - x;
+}
+
 // One wave per block row.  With `row_ptr` (rows per plane: nbr) the row's count of non-zero blocks is also left at
 // row_ptr[m][i+1], which is pass 1 of the list: the index stage in one call then needs no list_count_kernel.
 __global__ __launch_bounds__(kWavesPerWG * 64) void runs_kernel(const uint8_t* __restrict__ cls, int64_t rows_total,
@@ -101,10 +115,7 @@ __global__ __launch_bounds__(64) void list_scan_kernel(int64_t nbr, int32_t* __r
   int carry = 0;
   for (int64_t base = 0; base < nbr; base += 64) {
     int x = (base + lane < nbr) ? p[base + lane + 1] : 0;
-    for (int s = 1; s < 64; s <<= 1) {
-      const int y = __shfl_up(x, s);
-      if (lane >= s) x += y;
-    }
+    x += wave_excl_scan(x, lane);
     x += carry;
     if (base + lane < nbr) p[base + lane + 1] = x;
     carry = __shfl(x, 63);
@@ -112,17 +123,33 @@ __global__ __launch_bounds__(64) void list_scan_kernel(int64_t nbr, int32_t* __r
   if (lane == 0) p[0] = 0;
 }
 
-// Pass 3: write the ascending list of each row at row_ptr[m][i] (one wave per row).
+// Pass 3: write the ascending list of each row at row_ptr[m][i] (one wave per row).  With `counts` ([Mb][nbr] list
+// lengths, as the runs kernel leaves them in nz_cnt) pass 2 is done here as well: the wave adds up the counts of the
+// rows above its own -- a few hundred integers -- and writes its entry of row_ptr itself.
 __global__ __launch_bounds__(kWavesPerWG * 64) void list_fill_kernel(const uint8_t* __restrict__ cls, int64_t Mb,
                                                                      int64_t nbr, int64_t nbc,
-                                                                     const int32_t* __restrict__ row_ptr,
+                                                                     int32_t* __restrict__ row_ptr,
+                                                                     const int32_t* __restrict__ counts,
                                                                      uint32_t* __restrict__ col_idx) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * kWavesPerWG + (threadIdx.x >> 6);
   if (row >= Mb * nbr) return;
   const int64_t m = row / nbr, i = row - m * nbr;
   const uint8_t* c = cls + row * nbc;
-  uint32_t* out = col_idx + m * nbr * nbc + row_ptr[m * (nbr + 1) + i];
+  int start;
+  if (counts) {
+    const int32_t* cp = counts + m * nbr;
+    int part = 0;
+    for (int64_t b = lane; b < i; b += 64) part += cp[b];
+    start = __builtin_amdgcn_readlane(wave_excl_scan(part, lane) + part, 63);
+    if (lane == 0) {
+      row_ptr[m * (nbr + 1) + i] = start;
+      if (i == nbr - 1) row_ptr[m * (nbr + 1) + nbr] = start + cp[i];
+    }
+  } else {
+    start = row_ptr[m * (nbr + 1) + i];
+  }
+  uint32_t* out = col_idx + m * nbr * nbc + start;
   int written = 0;
   for (int64_t base = 0; base < nbc; base += 64) {
     const uint8_t v = (base + lane < nbc) ? c[base + lane] : (uint8_t)0;
@@ -302,19 +329,6 @@ __device__ __forceinline__ uint32_t class_bits16(uint4 x) {
   return nz | ((~ne & 0xffffu) << 16);
 }
 
-// Exclusive prefix sum over the 64 lanes with data-parallel-primitive moves (register to register; a shuffle goes
-// through LDS): shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane without a source adds 0), then lane 15 of a
-// row added to the next row (rows 1 and 3), then lane 31 to rows 2 and 3.
-__device__ __forceinline__ int wave_excl_scan(int x, int /*lane*/) {
-  int incl = x;
-  incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xf, 0xf, false);  // row_shr:1
-  incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xf, 0xf, false);  // row_shr:2
-  incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xf, 0xf, false);  // row_shr:4
-  incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, false);  // row_shr:8
-  incl += __builtin_amdgcn_update_dpp(0, incl, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
-  incl += __builtin_amdgcn_update_dpp(0, incl, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
-  return incl - x;
-}
 
 __global__ __launch_bounds__(kTinyMaxPlanes * 64) void tiny_index_kernel(const uint8_t* __restrict__ cls, int Mb, int nbr,
                                                                         int nbc, int32_t* __restrict__ row_ptr,
@@ -716,23 +730,28 @@ bool launch_one_kernel(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_
   return false;
 }
 
-// `counted`: the per-row counts are already at row_ptr[m][i+1] (left there by runs_kernel on the same stream).
+// `counts`: per-row list lengths [Mb][nbr] already on the stream (the runs kernel's nz_cnt), or NULL.  With them the
+// count launch is not needed, nor -- up to kScanInFillRows block rows per plane -- the scan launch.
+constexpr int64_t kScanInFillRows = 1024;
 int launch_list(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* row_ptr, uint32_t* col_idx,
-                int32_t* sched, bool counted, hipStream_t s) {
+                int32_t* sched, const int32_t* counts, bool counts_in_row_ptr, hipStream_t s) {
   using namespace bbm;
-  if (!counted && launch_one_kernel(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, nullptr, nullptr, nullptr, nullptr, nullptr, s))
+  if (!counts && launch_one_kernel(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, nullptr, nullptr, nullptr, nullptr, nullptr, s))
     return launch_status("bbm_build_sparse_index(one launch)");
   const unsigned grid = (unsigned)ceil_div(Mb * nbr, kWavesPerWG);
   int rc = BBM_OK;
-  if (!counted) {
-    list_count_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr);
-    rc = launch_status("bbm_build_sparse_index(count)");
+  const bool scan_in_fill = counts && nbr <= kScanInFillRows;
+  if (!scan_in_fill) {
+    if (!counts_in_row_ptr) {
+      list_count_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr);
+      rc = launch_status("bbm_build_sparse_index(count)");
+      if (rc) return rc;
+    }
+    list_scan_kernel<<<(unsigned)Mb, 64, 0, s>>>(nbr, row_ptr);
+    rc = launch_status("bbm_build_sparse_index(scan)");
     if (rc) return rc;
   }
-  list_scan_kernel<<<(unsigned)Mb, 64, 0, s>>>(nbr, row_ptr);
-  rc = launch_status("bbm_build_sparse_index(scan)");
-  if (rc) return rc;
-  list_fill_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr, col_idx);
+  list_fill_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr, scan_in_fill ? counts : nullptr, col_idx);
   rc = launch_status("bbm_build_sparse_index(fill)");
   if (rc || !sched) return rc;
   sched_kernel<<<(unsigned)(1 + Mb), kSchedThreads, 0, s>>>(row_ptr, col_idx, (int)Mb, (int)nbr, nbr * nbc, sched);
@@ -759,7 +778,7 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_sparse_index(con
   bbm::clear_error();
   const int rc = check_list_args("bbm_build_sparse_index", blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched);
   if (rc) return rc;
-  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, false, static_cast<hipStream_t>(stream));
+  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, nullptr, false, static_cast<hipStream_t>(stream));
 }
 
 extern "C" __attribute__((visibility("default"))) int bbm_build_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, int32_t* offset,
@@ -774,7 +793,9 @@ extern "C" __attribute__((visibility("default"))) int bbm_build_index(const uint
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (launch_one_kernel(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, offset, total_ones, nz_lo, nz_hi, nz_cnt, s))
     return launch_status("bbm_build_index(one launch)");
-  rc = launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, row_ptr, s);  // also pass 1 of the list
+  // the runs kernel's counts are pass 1 of the list: in nz_cnt for the fill kernel, and in row_ptr where a scan launch follows
+  const bool scan_launch = nbr > kScanInFillRows;
+  rc = launch_runs(blk_class, Mb, nbr, nbc, offset, total_ones, nz_lo, nz_hi, nz_cnt, scan_launch ? row_ptr : nullptr, s);
   if (rc) return rc;
-  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, true, s);
+  return launch_list(blk_class, Mb, nbr, nbc, row_ptr, col_idx, sched, nz_cnt, scan_launch, s);
 }
