@@ -283,17 +283,33 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   // K fragment of MFMA k-step t, key block kb: row 32*kb + lq, chunk 2t + hh.
   const int kaddr = (lq % NBLK) * KBLK + (lq / NBLK) * D + hh * 8;
   // S^T = K Q^T for the 64 keys of one LDS tile x this wave's 32 queries
+  // The K fragments go through a ring of kRing register sets, each requested kRing matrix instructions before the one
+  // that consumes it; the scheduling hints pin that order (left to itself the compiler issues every LDS read right
+  // before its MFMA, which then waits out the LDS latency: d=128 dense -1.2 %, tree -3 %; a ring of 8 costs the d=64
+  // kernel its third wave per SIMD, the same treatment of the V fragments of the second product gains nothing).
   auto qk = [&](const __bf16* ks, f32x16 (&s)[2]) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) s[kb] = s_init;
+    constexpr int NF = 2 * KS, kRing = 4;
+    auto frag = [&](int n) {  // fragment n: MFMA k-step n / 2, key block n % 2
+      return *reinterpret_cast<const bf16x8*>(ks + kaddr + (n & 1) * (32 / NBLK) * D + (n >> 1) * 16);
+    };
+    bf16x8 ring[kRing];
 #pragma unroll
-    for (int t = 0; t < KS; ++t) {
+    for (int n = 0; n < kRing; ++n) ring[n] = frag(n);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + kaddr + kb * (32 / NBLK) * D + t * 16);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s[kb], 0, 0, 0);
-      }
+    for (int n = 0; n < NF; ++n) {
+      const bf16x8 kf = ring[n % kRing];
+      if (n + kRing < NF) ring[n % kRing] = frag(n + kRing);
+      s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[n >> 1], s[n & 1], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, kRing, 0);  // kRing LDS reads, then (MFMA, LDS read) pairs, then the last MFMAs
+#pragma unroll
+    for (int n = 0; n < NF - kRing; ++n) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, kRing, 0);
   };
 
   // V fragment (transposing read) of 16-key step u, half a, column block db: the lane addresses row
