@@ -171,28 +171,70 @@ __global__ __launch_bounds__(kExpandThreads) void rcm_expand_kernel(const uint64
   }
 }
 
-// One advance, one work-group: order the candidates the expansion found and make them the next level -- or, when it
-// found none (a component is finished, or nothing has started yet), start the next component.
-__global__ __launch_bounds__(kOrderThreads) void rcm_advance_kernel(const int32_t* __restrict__ degree, const int32_t* __restrict__ parent_pos,
-                                                                   const int32_t* __restrict__ cand, uint64_t* keys, int32_t* order,
+// Ranking of the candidates the expansion found (many work-groups): a thread ranks one candidate by counting the
+// smaller keys -- every work-group stages all keys of the level through LDS, building them from the candidate list
+// as it goes --, places it behind the nodes ordered so far and marks it visited.  Reads the state, changes none of it
+// (the advance that follows does).  One work-group ranking a level of 3500 nodes alone takes 0.3 ms.
+constexpr int kRankWGs = 256, kRankThreads = 256, kRankStage = 4;  // kRankStage keys of a thread's staging share in flight
+__global__ __launch_bounds__(kRankThreads) void rcm_rank_kernel(const int32_t* __restrict__ degree, const int32_t* __restrict__ parent_pos,
+                                                                const int32_t* __restrict__ cand, int32_t* __restrict__ order,
+                                                                uint64_t* visited, const int32_t* __restrict__ state) {
+  __shared__ __attribute__((aligned(16))) uint64_t chunk_s[kRankChunk + 8];
+  const int tid = threadIdx.x;
+  if (state[kStDone]) return;
+  const int n_done = state[kStLvlHi], L = state[kStCand];
+  auto key_of = [&](int c) {
+    const int v = cand[c];
+    return level_key(parent_pos[v], degree[v], v);
+  };
+  for (int c0 = (int)blockIdx.x * kRankThreads; c0 < L; c0 += (int)gridDim.x * kRankThreads) {  // uniform in the work-group
+    const int c = c0 + tid;
+    const uint64_t mine = c < L ? key_of(c) : 0;
+    int r = 0;
+    for (int j0 = 0; j0 < L; j0 += kRankChunk) {
+      const int n = min(kRankChunk, L - j0);
+      __syncthreads();  // the previous chunk has been read
+      for (int j = tid; j < n; j += kRankStage * kRankThreads) {  // a key is three dependent loads: keep several going
+        int v[kRankStage], pp[kRankStage], dg[kRankStage];
+#pragma unroll
+        for (int t = 0; t < kRankStage; ++t) v[t] = j + t * kRankThreads < n ? cand[j0 + j + t * kRankThreads] : 0;
+#pragma unroll
+        for (int t = 0; t < kRankStage; ++t) {
+          pp[t] = parent_pos[v[t]];
+          dg[t] = degree[v[t]];
+        }
+#pragma unroll
+        for (int t = 0; t < kRankStage; ++t)
+          if (j + t * kRankThreads < n) chunk_s[j + t * kRankThreads] = level_key(pp[t], dg[t], v[t]);
+      }
+      if (tid < 8) chunk_s[n + tid] = ~0ull;  // pad to a multiple of 8 with keys that count for nobody
+      __syncthreads();
+      for (int j = 0; j < n; j += 8) {  // 8 keys per LDS round trip
+        uint64_t k[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) k[t] = chunk_s[j + t];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) r += k[t] < mine ? 1 : 0;
+      }
+    }
+    if (c < L) {
+      const int v = (int)(mine & 0xfffffull);
+      order[n_done + r] = v;
+      atomicOr(reinterpret_cast<unsigned long long*>(&visited[v >> 6]), 1ull << (v & 63));
+    }
+  }
+}
+
+// One advance, one work-group: make the candidates the expansion found (ranked and placed by rcm_rank_kernel) the next
+// level -- or, when it found none (a component is finished, or nothing has started yet), start the next component.
+__global__ __launch_bounds__(kOrderThreads) void rcm_advance_kernel(const int32_t* __restrict__ degree, int32_t* order,
                                                                    uint64_t* visited, int32_t* state, int N) {
-  __shared__ uint64_t chunk_s[kRankChunk];
   __shared__ unsigned long long min_s[kOrderThreads / 64];
   const int tid = threadIdx.x;
   if (state[kStDone]) return;
   const int n_done = state[kStLvlHi], L = state[kStCand];  // every placed node lies below the end of the current level
   __syncthreads();                                         // everyone has read the state before thread 0 rewrites it
   if (L > 0) {
-    for (int c = tid; c < L; c += kOrderThreads) {
-      const int v = cand[c];
-      keys[c] = level_key(parent_pos[v], degree[v], v);
-    }
-    __threadfence();
-    __syncthreads();
-    rank_level(keys, L, chunk_s, tid, [&](int r, int v) {
-      order[n_done + r] = v;
-      atomicOr(reinterpret_cast<unsigned long long*>(&visited[v >> 6]), 1ull << (v & 63));
-    });
     if (tid == 0) {
       state[kStLvlLo] = n_done;
       state[kStLvlHi] = n_done + L;
@@ -419,12 +461,13 @@ extern "C" __attribute__((visibility("default"))) int bbm_rcm_order(const uint8_
   rcm_pack_kernel<<<(unsigned)N, kPackThreads, 0, s>>>(mask, (int)N, row_stride_bytes, W, bits, degree, parent, visited, claimed, state);
   int rc = launch_status("bbm_rcm_order (pack)");
   if (rc != BBM_OK) return rc;
-  // the first advance starts the first component; then kRounds rounds of (parallel expansion, advance); the finisher
+  // the first advance starts the first component; then kRounds rounds of (parallel expansion, ranking, advance); the finisher
   // walks whatever is left and writes perm.  Kernels that find the walk finished return at once.
-  rcm_advance_kernel<<<1, kOrderThreads, 0, s>>>(degree, parent, cand, keys, order, visited, state, (int)N);
+  rcm_advance_kernel<<<1, kOrderThreads, 0, s>>>(degree, order, visited, state, (int)N);
   for (int r = 0; r < kRounds; ++r) {
     rcm_expand_kernel<<<kExpandWGs, kExpandThreads, 0, s>>>(bits, order, visited, claimed, parent, cand, state, W);
-    rcm_advance_kernel<<<1, kOrderThreads, 0, s>>>(degree, parent, cand, keys, order, visited, state, (int)N);
+    rcm_rank_kernel<<<kRankWGs, kRankThreads, 0, s>>>(degree, parent, cand, order, visited, state);
+    rcm_advance_kernel<<<1, kOrderThreads, 0, s>>>(degree, order, visited, state, (int)N);
   }
   rc = launch_status("bbm_rcm_order (rounds)");
   if (rc != BBM_OK) return rc;
