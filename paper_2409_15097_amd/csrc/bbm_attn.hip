@@ -718,11 +718,11 @@ inline size_t partial_bytes(int64_t Mb, int64_t nbr, int64_t hbp, int d, int Br)
 
 // A LIST-mode launch of fewer than kSplitBelow work-groups leaves most of the 256 CUs idle (a few block rows of new
 // tokens against a long key/value cache): every block row is then computed in split_parts() equal parts -- as many as
-// give every CU one work-group, but no more than leave a part kSplitMinTiles block columns.  A part costs a prologue,
-// a parked partial result, two device-wide fences and a share of the merge: with 20 tiles per row, 8 parts were 3.5
-// times slower than none; with 260 tiles per row and 64 rows, 2 / 4 / 8 parts took 0.193 / 0.146 / 0.205 ms against
-// 0.32 ms unsplit (the fences of 512 work-groups cost more than the second work-group per CU gains).
-constexpr int kSplitBelow = 128, kSplitTarget = 256, kSplitMax = 8, kSplitMinTiles = 32;
+// give every CU two work-groups, but no more than leave a part kSplitMinTiles block columns.  A part costs a prologue,
+// a parked partial result, a device-wide fence and a share of the merge: with 20 tiles per row, 8 parts were 3.5
+// times slower than none; with 260 tiles per row and 64 rows, 4 / 8 parts take 0.114 / 0.108 ms against 0.32 ms
+// unsplit (while every wave fenced for itself, 8 parts were slower than 4: 0.205 against 0.146 ms).
+constexpr int kSplitBelow = 128, kSplitTarget = 512, kSplitMax = 8, kSplitMinTiles = 32;
 inline int split_parts(int64_t total_wgs, int64_t nbc) {
   if (total_wgs >= kSplitBelow) return 1;
   const int64_t s = std::min<int64_t>(std::min<int64_t>(kSplitMax, kSplitTarget / total_wgs), nbc / kSplitMinTiles);
