@@ -48,7 +48,7 @@ extern "C" {
 #define BBM_MODE_LIST 2           /* walk the compact per-row list of non-zero blocks; element mask skipped on blocks
                                      flagged full; rows the split schedule cut are computed part by part by extra
                                      work-groups and merged; a launch of fewer than 128 work-groups (B*H*nbr) over at
-                                     least 64 block columns computes EVERY block row in min(8, 256 / (B*H*nbr), nbc / 32)
+                                     least 64 block columns computes EVERY block row in min(8, 512 / (B*H*nbr), nbc / 32)
                                      equal parts instead                                                               */
 #define BBM_MODE_DENSE_BASELINE 3 /* paper Sec. 3 "naive masking": visit every block, apply the element mask everywhere */
 #define BBM_MODE_AUTO 4           /* LIST if the index carries list and schedule, else RUNS, else BITMAP               */
