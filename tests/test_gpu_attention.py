@@ -124,7 +124,21 @@ def test_deterministic():
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(l1, l2)
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "C2b", "C4d"])
+@pytest.mark.parametrize("name", ["C3q", "C3qL"])
+def test_full_size_decode_shapes(name):
+    """The two decode-time bench rows (tree tokens as the only queries; C3qL is the small launch that computes every
+    block row in parts) at their full sizes and in bench.py's configuration, every output against the oracle."""
+    bbm = _bbm()
+    cfg = make_config(name)
+    assert cfg["q"].shape[2] != cfg["k"].shape[2]
+    O_ref, lse_ref = oracle.masked_attention(cfg["q"], cfg["k"], cfg["v"], cfg["mask"])
+    for Br, mode in ((128, "AUTO"), (64, "LIST"), (128, "BITMAP")):
+        print(f"full {name} Br={Br} mode={mode}", flush=True)
+        o, lse = _gpu_attn_rect(cfg["q"], cfg["k"], cfg["v"], cfg["mask"], Br, mode)
+        assert_attention_close(o, lse, O_ref, lse_ref)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "C2b", "C4d", "C4w"])
 def test_full_size_sampled_rows(name):
     """At the benchmark sizes the oracle evaluates sampled query rows one by one (same launch configuration as bench.py)."""
     bbm = _bbm()
