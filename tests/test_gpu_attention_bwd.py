@@ -201,7 +201,7 @@ def test_deterministic():
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "C2b", "C4d"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "C2b", "C4d", "C4w"])
 def test_full_size_sampled_rows_and_columns(name):
     """At the benchmark sizes the oracle evaluates sampled query rows (dQ) and sampled keys (dK, dV) one by one."""
     bbm = _bbm()
