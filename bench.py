@@ -25,6 +25,20 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0              # MI355X HBM3E
 
 
+def roofline(kernel: str, algo_flops: float, algo_bytes: float, ms: float, traffic):
+    """The roof that bounds a kernel is decided by its algorithmic intensity against the ridge of the two peaks
+    (2500 TFLOP/s bf16 MFMA over 8000 GB/s HBM = 312.5 flop/byte); both fractions are reported either way."""
+    sec = ms * 1e-3
+    tflops, gbs = algo_flops / sec / 1e12, algo_bytes / sec / 1e9
+    intensity, ridge = algo_flops / algo_bytes, MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    hbm = intensity < ridge
+    return {"bound": "hbm" if hbm else "mfma", "kernel": kernel, "achieved": gbs if hbm else tflops,
+            "peak": HBM_PEAK_GBS if hbm else MFMA_BF16_PEAK_TFLOPS, "unit": "GB/s" if hbm else "TFLOP/s",
+            "frac": gbs / HBM_PEAK_GBS if hbm else tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+            "algo_bytes": algo_bytes, "algo_flops": algo_flops, "intensity_flop_per_byte": intensity,
+            "ridge_flop_per_byte": ridge, "mfma_frac": tflops / MFMA_BF16_PEAK_TFLOPS, "hbm_frac": gbs / HBM_PEAK_GBS}
+
+
 def profiled_traffic_bytes(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, each scaled by the
     copy-kernel factor), or None if no summary exists for this kernel and workload."""
@@ -165,9 +179,16 @@ def measure_mask(bbm, name, Br, warmup, steps, torch, backward=False):
         res["bwd_mfma_frac"] = res["bwd_tflops_visited"] / MFMA_BF16_PEAK_TFLOPS
         res["bwd_executed_tflops"] = 3.5 * flops / (res["bwd_ms"] * 1e-3) / 1e12
         res["fwd_bwd_ms"] = res["attn_ms"] + res["bwd_ms"]
+        # algorithmic HBM bytes of the backward pass: Q, K, V, O, dO read once, dQ, dK, dV written once, lse, and the packed
+        # words of partial tiles once per kernel
+        res["bwd_algo_bytes"] = 8.0 * B * H * N * d * 2 + 4.0 * B * H * N + 2 * census["partial"] * (B // Mb) * Br * 8.0
         del d_o, dq, dk, dv, ws_b
     # algorithmic HBM bytes of the attention kernel: Q, K, V read once, O written once, lse, packed words of partial tiles
     res["attn_algo_bytes"] = 2.0 * B * H * (Nq + N) * d * 2 + 4.0 * B * H * Nq + census["partial"] * (B // Mb) * Br * 8.0
+    # both roofs per workload: the fraction of the HBM peak the algorithmic bytes would need over the kernel's duration,
+    # next to the fraction of the MFMA peak; the larger one names the roof the kernel is closer to
+    res["attn_hbm_frac"] = res["attn_algo_bytes"] / (res["attn_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+    res["attn_nearer_roof"] = "hbm" if res["attn_hbm_frac"] > res["attn_mfma_frac"] else "mfma"
     del mask, q, k, v, idx, out, lse, ws
     torch.cuda.empty_cache()
     return res, cfg
@@ -269,12 +290,8 @@ def main():
         "attn_ms": main_res["attn_ms"], "attn_tflops_visited": main_res["attn_tflops_visited"],
         "dense_tile_ms": main_res["dense_tile_ms"], "dense_tile_tflops": main_res["dense_tile_tflops"],
         "preprocess_ms": main_res["preprocess_ms"], "preprocess_gbs": main_res["preprocess_gbs"],
-        "roofline": {"bound": "mfma", "kernel": "attn_fwd_kernel", "achieved": main_res["attn_tflops_visited"],
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": main_res["attn_tflops_visited"] / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": profiled_traffic_bytes("attn_fwd_kernel", a.workload),
-                     "algo_bytes": main_res["attn_algo_bytes"],
-                     "hbm_frac_of_algo_bytes": main_res["attn_algo_bytes"] / (main_res["attn_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": roofline("attn_fwd_kernel", flops, main_res["attn_algo_bytes"], main_res["attn_ms"],
+                             profiled_traffic_bytes("attn_fwd_kernel", a.workload)),
         "per_mask": rows,
     }
     if not a.no_backward:
@@ -282,10 +299,9 @@ def main():
         # tile (S, dP, dV, dK, dQ) = 2.5 x the forward; the two-kernel split executes 7 (S and dP twice).
         out["backward"] = {
             "bwd_ms": main_res["bwd_ms"], "col_index_ms": main_res["col_index_ms"], "fwd_bwd_ms": main_res["fwd_bwd_ms"],
-            "roofline": {"bound": "mfma", "kernel": "attn_bwd_dq_kernel + attn_bwd_dkv_kernel",
-                         "achieved": main_res["bwd_tflops_visited"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": main_res["bwd_mfma_frac"], "executed_tflops": main_res["bwd_executed_tflops"],
-                         "traffic": profiled_traffic_bytes("attn_bwd_kernels", a.workload)}}
+            "roofline": dict(roofline("attn_bwd_dq_kernel + attn_bwd_dkv_kernel", 2.5 * flops, main_res["bwd_algo_bytes"],
+                                      main_res["bwd_ms"], profiled_traffic_bytes("attn_bwd_kernels", a.workload)),
+                             executed_tflops=main_res["bwd_executed_tflops"])}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(main_cfg, a.Br)
     print(json.dumps(out))
