@@ -58,6 +58,9 @@ extern "C" {
 typedef struct bbm_index {
   int32_t Br, Bc;             /* tile size the index was built for                                   */
   int64_t Mb, nbr, nbc;       /* planes, block rows, block columns                                   */
+  int64_t Nq, Nk;             /* query rows and key columns of the mask the index was built from (the packed mask's
+                                 row stride is Nq, so a tensor of another length must be refused even where it gives
+                                 the same block counts)                                                   */
   const uint8_t* blk_class;   /* [Mb, nbr, nbc] BBM_BLOCK_*                                          */
   const uint8_t* bin_blk_mat; /* [Mb, nbr, nbc] 0/1, the paper's BinBlkMat                           */
   const int32_t* offset;      /* [Mb, nbr] first block of the longest run of full blocks             */
@@ -174,6 +177,10 @@ size_t bbm_sched_bytes(int64_t Mb, int64_t nbr);
 
 /*
  * Bytes of device workspace bbm_attn_fwd needs for this problem (0 if none).  Negative sizes return 0.
+ * Layout: (8 + B*H*ceil(N/Br)) int32 queue counters, rounded up to 256 bytes -- the only part that has to be zero --
+ * then room for partial results: (d/2 + 2) * 2*Br floats per record, one record per (cut part, batch, head) resp.
+ * per (block row, part, batch, head) of a small launch.  The room for cut rows stops at 32 MiB; a schedule whose parts
+ * need more records than the workspace holds is not followed (those rows are computed whole by one work-group).
  */
 size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int Br, int Bc, int mode);
 
@@ -193,15 +200,17 @@ size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
  *   softmax_scale    finite and > 0 (1/sqrt(d) is the usual choice; the paper does not name one).
  *   packed_mask      device in, uint64 [Mb][ceil(N/64)][N] from bbm_build_block_mask.
  *   idx              host pointer; idx->Bc must be 64 and idx->Br one of 64, 128, 256; idx->Mb == Mb;
- *                    idx->nbr/nbc must equal ceil(N/Br), ceil(N/Bc).  Members needed per mode:
+ *                    idx->Nq = idx->Nk = N and idx->nbr/nbc = ceil(N/Br), ceil(N/Bc).  Members needed per mode:
  *                    BITMAP: bin_blk_mat;  RUNS: bin_blk_mat, offset, total_ones, nz_lo, nz_hi;
  *                    LIST: row_ptr, col_idx, sched;  DENSE_BASELINE: none.
  *   mode             BBM_MODE_*.
  *   workspace        device scratch of at least bbm_attn_fwd_workspace_bytes(...) bytes, 16-byte aligned (may be NULL
  *                    if 0).  LIST mode keeps its queue counters and the partial results of cut block rows there.
- *                    The workspace must be ZERO-FILLED ONCE after it is allocated; every call puts back the zeros it
- *                    disturbed, so the same workspace can serve any number of later calls (of any shape that fits)
- *                    without being cleared again.  Two calls that overlap in time (different streams) must not
+ *                    The workspace's counters (see bbm_attn_fwd_workspace_bytes; zero-filling all of it is fine too)
+ *                    must be ZERO-FILLED ONCE after it is allocated; every call puts back the zeros it disturbed, so
+ *                    the same workspace can serve any number of later calls of the same (B, H, N, d, Br) without being
+ *                    cleared again.  Before a call of another shape clear the counters again: one shape's partial
+ *                    results may lie where another shape's counters do.  Two calls that overlap in time (different streams) must not
  *                    share a workspace.
  * Arithmetic: QK^T and PV on bf16 MFMA with fp32 accumulation; Q is multiplied by softmax_scale*log2(e) and
  * rounded to bf16 once, so the first product yields base-2 exponents directly; softmax statistics in fp32; P rounded
@@ -217,12 +226,13 @@ int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* ls
 /*
  * bbm_attn_fwd for Nq queries against Nk keys per (batch, head): q and o are [B][H][Nq][d], k and v [B][H][Nk][d], lse
  * [B][H][Nq], packed_mask [Mb][ceil(Nk/64)][Nq] from bbm_build_block_mask_rect, idx->nbr = ceil(Nq/Br), idx->nbc =
- * ceil(Nk/Bc).  Everything else as bbm_attn_fwd, which is this call with Nq = Nk = N; the workspace size is
+ * ceil(Nk/Bc), idx->Nq = Nq, idx->Nk = Nk.  Everything else as bbm_attn_fwd, which is this call with Nq = Nk = N; the workspace size is
  * bbm_attn_fwd_workspace_bytes(B, H, Nq, ...).
  */
 int bbm_attn_fwd_rect(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t Nq,
                       int64_t Nk, int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask,
                       const bbm_index* idx, int mode, void* workspace, size_t workspace_bytes, void* stream);
+
 
 /*
  * Per-column list of non-zero blocks, the transpose of the list of bbm_build_sparse_index: what the dK/dV step of
@@ -280,7 +290,8 @@ size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
  *                    aligned; holds the queue counters, D and the log-sum-exp in the form the second kernel consumes,
  *                    and the fp32 partial sums of cut rows and columns (an upper bound: most of it is never touched).
  *                    Like the forward workspace it must be ZERO-FILLED ONCE after it is allocated; every call puts
- *                    back the zeros it disturbed.  Two calls that overlap in time must not share a workspace.
+ *                    back the zeros it disturbed (its two counter arrays come first: 8 + B*H*nbr and 8 + B*H*nbc int32,
+ *                    each rounded up to 256 bytes); clear them again before a call of another shape.  Two calls that overlap in time must not share a workspace.
  * Arithmetic: all five products on bf16 MFMA with fp32 accumulation; Q (dQ step) resp. K (dK/dV step) is multiplied by
  * softmax_scale*log2(e) and rounded to bf16 once; P and dS are rounded to bf16 before the products that consume them.
  * Two kernels, no floating-point atomics: the same inputs give bit-identical outputs (parts of a cut row or column are

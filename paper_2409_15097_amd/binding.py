@@ -20,6 +20,7 @@ class BbmError(RuntimeError):
 
 class _CIndex(C.Structure):
     _fields_ = [("Br", C.c_int32), ("Bc", C.c_int32), ("Mb", C.c_int64), ("nbr", C.c_int64), ("nbc", C.c_int64),
+                ("Nq", C.c_int64), ("Nk", C.c_int64),
                 ("blk_class", C.c_void_p), ("bin_blk_mat", C.c_void_p), ("offset", C.c_void_p),
                 ("total_ones", C.c_void_p), ("nz_lo", C.c_void_p), ("nz_hi", C.c_void_p), ("nz_cnt", C.c_void_p),
                 ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("sched", C.c_void_p),
@@ -137,7 +138,8 @@ class BlockIndex:
 
     def c_struct(self) -> _CIndex:
         g = lambda t: None if t is None else t.data_ptr()
-        return _CIndex(self.Br, self.Bc, self.Mb, self.nbr, self.nbc, g(self.blk_class), g(self.bin_blk_mat),
+        return _CIndex(self.Br, self.Bc, self.Mb, self.nbr, self.nbc, self.N, self.N if self.Nk is None else self.Nk,
+                       g(self.blk_class), g(self.bin_blk_mat),
                        g(self.offset), g(self.total_ones), g(self.nz_lo), g(self.nz_hi), g(self.nz_cnt),
                        g(self.row_ptr), g(self.col_idx), g(self.sched), g(self.col_ptr), g(self.row_idx), g(self.col_sched))
 
@@ -272,25 +274,60 @@ def bbm_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIn
                              stream=stream)
 
 
-def bbm_attn_fwd_rect(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIndex, mode: int = BBM_MODE_AUTO,
-                      softmax_scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
-                      lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
-    """q: bf16 CUDA tensor [B,H,Nq,d], k, v: [B,H,Nk,d], contiguous.  Returns (O bf16 [B,H,Nq,d], lse fp32 [B,H,Nq]).
-    Equal Nq and Nk go through the square entry point of the library."""
+_workspaces = {}
+
+
+def _cached_workspace(kind: str, nbytes: int, device, stream, shape) -> torch.Tensor:
+    """One workspace per (kind, device, stream), grown on demand.  The library leaves its counters at zero after every
+    call, but where the counters end and the partial results begin depends on the problem's shape: the workspace is
+    zero-filled when it is allocated and again whenever the shape changes (on the stream that uses it)."""
+    key = (kind, device.index, _stream(stream).value)
+    ws, last_shape = _workspaces.get(key, (None, None))
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.zeros(max(16, nbytes), dtype=torch.uint8, device=device)
+        torch.cuda.synchronize(device)          # zero before any stream may use it
+    elif last_shape != shape:
+        with (torch.cuda.stream(stream) if stream is not None else _null_ctx()):
+            ws.zero_()
+    _workspaces[key] = (ws, shape)
+    return ws
+
+
+def _fwd_args(q, k, v, idx, softmax_scale, out, lse, stream):
     assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
     assert v.shape == k.shape and k.shape[:2] == q.shape[:2] and k.shape[3] == q.shape[3]
     assert k.dtype == q.dtype and v.dtype == q.dtype
     B, H, N, d = q.shape
     Nk = k.shape[2]
+    assert idx.N == N and (idx.N if idx.Nk is None else idx.Nk) == Nk, "the index was built for a mask of another size"
     if softmax_scale is None:
         softmax_scale = float(d) ** -0.5
-    if out is None:
-        out = torch.empty_like(q)
-    if lse is None:
-        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    ctx = torch.cuda.stream(stream) if stream is not None else _null_ctx()
+    with ctx:                                   # temporaries belong to the stream the kernels run on
+        if out is None:
+            out = torch.empty_like(q)
+        if lse is None:
+            lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    return B, H, N, Nk, d, softmax_scale, out, lse
+
+
+class _null_ctx:
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        return False
+
+
+def bbm_attn_fwd_rect(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIndex, mode: int = BBM_MODE_AUTO,
+                      softmax_scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
+                      lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """q: bf16 CUDA tensor [B,H,Nq,d], k, v: [B,H,Nk,d], contiguous.  Returns (O bf16 [B,H,Nq,d], lse fp32 [B,H,Nq]).
+    Equal Nq and Nk go through the square entry point of the library."""
+    B, H, N, Nk, d, softmax_scale, out, lse = _fwd_args(q, k, v, idx, softmax_scale, out, lse, stream)
     need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx.Br, idx.Bc, mode)
-    if workspace is None and need > 0:
-        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)   # the library wants it zero-filled once
+    if workspace is None and need > 0 and (mode == BBM_MODE_LIST or idx.sched is not None):
+        workspace = _cached_workspace("fwd", need, q.device, stream, (B, H, N, d, idx.Br))
     cs = idx.c_struct()
     ws_bytes = 0 if workspace is None else workspace.numel()
     if Nk == N:
@@ -316,13 +353,15 @@ def bbm_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Ten
         assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == q.shape
     B, H, N, d = q.shape
     assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.shape == (B, H, N)
+    assert idx.N == N and idx.Nk in (None, N), "the index was built for a mask of another size"
     if softmax_scale is None:
         softmax_scale = float(d) ** -0.5
-    dq = torch.empty_like(q) if dq is None else dq
-    dk = torch.empty_like(q) if dk is None else dk
-    dv = torch.empty_like(q) if dv is None else dv
-    if workspace is None:   # the library wants it zero-filled once
-        workspace = torch.zeros(bbm_attn_bwd_workspace_bytes(B, H, N, d, idx.Br), dtype=torch.uint8, device=q.device)
+    with (torch.cuda.stream(stream) if stream is not None else _null_ctx()):
+        dq = torch.empty_like(q) if dq is None else dq
+        dk = torch.empty_like(q) if dk is None else dk
+        dv = torch.empty_like(q) if dv is None else dv
+    if workspace is None:   # the library wants its counters zero-filled once
+        workspace = _cached_workspace("bwd", bbm_attn_bwd_workspace_bytes(B, H, N, d, idx.Br), q.device, stream, (B, H, N, d, idx.Br))
     cs = idx.c_struct()
     _check(lib.bbm_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv),
                             B, H, N, d, softmax_scale, idx.Mb, _ptr(idx.packed_mask), C.byref(cs), _ptr(workspace),

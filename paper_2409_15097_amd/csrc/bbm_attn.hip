@@ -58,6 +58,7 @@ struct AttnParams {
   int32_t n_extra;    // leading work-groups that serve the queue of cut-row parts (LIST mode)
   int32_t G;          // (batch, head) planes whose block rows are interleaved in launch order
   int32_t split;      // parts per block row when the launch is too small to fill the chip (LIST mode), else 1
+  int32_t part_cap;   // records of `partials` the workspace holds; a schedule whose parts need more is not followed
 };
 
 __device__ __forceinline__ float partner_max(float x) {
@@ -602,6 +603,12 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
                                              bbm::kSchedRowInts * (int64_t)(own_m * P.nbr + own_rank));
     nparts_all = hdr.x;
     split_T = hdr.y;
+    // a workspace too small for the partial results of every (part, head) item: no row is computed in parts
+    // (the same decision in every work-group: it depends on the header and the launch only)
+    if ((int64_t)nparts_all * P.hbp > (int64_t)P.part_cap) {
+      nparts_all = 0;
+      split_T = 0x7fffffff;
+    }
   }
   // ---- LIST mode, the first n_extra work-groups: before their own block row they serve the queue of cut-row parts
   // (nothing to do, and no cost, when the schedule cut no row)
@@ -711,9 +718,15 @@ inline size_t queue_bytes(int64_t Mb, int64_t nbr, int64_t hbp) {
   const size_t n = (size_t)(8 + Mb * nbr * hbp) * sizeof(int32_t);
   return (n + kQueueAlign - 1) / kQueueAlign * kQueueAlign;
 }
+// one parked partial result: the fp32 accumulators of a work-group plus its running maximum and sum
+inline size_t record_bytes(int d, int Br) { return (size_t)((d / 32 * 16 + 2) * (Br * 2)) * sizeof(float); }
+// Partial results of cut rows: at most Mb*nbr cut parts exist (T >= 2 * mean list length), one record per (cut part,
+// head-batch); in practice a handful of rows is cut (8 parts x 16 heads = 4.4 MB on the long-context workload), so
+// the workspace asked for stops at kPartialCapBytes and a schedule that would need more is not followed (the rows
+// are then computed whole: slower, same results up to the rounding order of the merge).
+constexpr size_t kPartialCapBytes = 32u << 20;
 inline size_t partial_bytes(int64_t Mb, int64_t nbr, int64_t hbp, int d, int Br) {
-  // at most Mb*nbr cut parts exist (T >= 2 * mean list length); one record per (cut part, head-batch)
-  return (size_t)(Mb * nbr * hbp) * (size_t)((d / 32 * 16 + 2) * (Br * 2)) * sizeof(float);
+  return std::min((size_t)(Mb * nbr * hbp) * record_bytes(d, Br), kPartialCapBytes);
 }
 
 // A LIST-mode launch of fewer than kSplitBelow work-groups leaves most of the 256 CUs idle (a few block rows of new
@@ -730,12 +743,16 @@ inline int split_parts(int64_t total_wgs, int64_t nbc) {
 }
 
 template <int D, int NW>
-int launch(AttnParams& P, int64_t Mb, void* workspace, hipStream_t s) {
+int launch(AttnParams& P, int64_t Mb, void* workspace, size_t workspace_bytes, hipStream_t s) {
   if (P.mode == BBM_MODE_LIST) {
+    const size_t qb = queue_bytes(Mb, P.nbr, P.hbp);
+    const int64_t cap = (int64_t)std::min<size_t>((workspace_bytes - qb) / record_bytes(D, NW * 32), 0x7fffffff);
     P.queue = static_cast<int32_t*>(workspace);
-    P.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + queue_bytes(Mb, P.nbr, P.hbp));
+    P.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + qb);
+    P.part_cap = (int32_t)cap;
     P.n_extra = P.total_wgs < kExtraWGs ? P.total_wgs : kExtraWGs;
     P.split = split_parts(P.total_wgs, P.nbc);
+    while (P.split > 1 && (int64_t)P.total_wgs * P.split > cap) --P.split;  // every (row, part, head) parks a record
     if (P.split > 1)
       attn_fwd_kernel<D, NW, 2><<<(unsigned)(P.total_wgs * P.split), NW * 64, 0, s>>>(P);
     else
@@ -754,7 +771,8 @@ extern "C" __attribute__((visibility("default"))) size_t bbm_attn_fwd_workspace_
   // sized for the larger of the two plane counts a caller may use (Mb = 1 or Mb = B): both give Mb*hbp = B*H
   // (N counts the queries; the number of keys is not known here, so the largest split of a small launch is assumed)
   const int64_t nbr = (N + Br - 1) / Br;
-  return queue_bytes(1, nbr, B * H) + partial_bytes(1, nbr, B * H, d, Br) * (size_t)split_parts(B * H * nbr, 1 << 30);
+  const int split = split_parts(B * H * nbr, 1 << 30);
+  return queue_bytes(1, nbr, B * H) + (split > 1 ? (size_t)(B * H * nbr * split) * record_bytes(d, Br) : partial_bytes(1, nbr, B * H, d, Br));
 }
 
 namespace {
@@ -777,6 +795,9 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   if (idx->Bc != kBc || (idx->Br != 64 && idx->Br != 128 && idx->Br != 256))
     return fail(BBM_EUNSUPPORTED, "%s: tile (Br=%d, Bc=%d) has no kernel instance (Br in {64,128,256}, Bc = 64)", fn, idx->Br, idx->Bc);
   const int64_t nbr = ceil_div(N, idx->Br), nbc = ceil_div(Nk, idx->Bc);
+  if (idx->Nq != N || idx->Nk != Nk)
+    return fail(BBM_EINVAL, "%s: index built for a mask of %lld x %lld does not match %lld queries x %lld keys", fn, (long long)idx->Nq,
+                (long long)idx->Nk, (long long)N, (long long)Nk);
   if (idx->Mb != Mb || idx->nbr != nbr || idx->nbc != nbc)
     return fail(BBM_EINVAL, "%s: index (Mb=%lld, nbr=%lld, nbc=%lld) does not match the problem (Mb=%lld, nbr=%lld, nbc=%lld)", fn,
                 (long long)idx->Mb, (long long)idx->nbr, (long long)idx->nbc, (long long)Mb, (long long)nbr, (long long)nbc);
@@ -803,6 +824,7 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   }
   if (nbr * nbc >= (1ll << 31) || B * H * nbr >= (1ll << 31) || N >= (1ll << 31) || Nk >= (1ll << 31))
     return fail(BBM_EUNSUPPORTED, "%s: problem too large for 32-bit tile counters", fn);
+  hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx->Br, idx->Bc, mode);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(BBM_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
@@ -838,16 +860,16 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   P.hbp = (int32_t)(Mb == 1 ? B * H : H);
   P.n_extra = 0;
   P.split = 1;
+  P.part_cap = 0;
   P.G = interleaved_planes(B * H, 2 * Nk * d * (int64_t)sizeof(__bf16));
-  hipStream_t s = static_cast<hipStream_t>(stream);
   if (d == 64) {
-    if (idx->Br == 64) return launch<64, 2>(P, Mb, workspace, s);
-    if (idx->Br == 128) return launch<64, 4>(P, Mb, workspace, s);
-    return launch<64, 8>(P, Mb, workspace, s);
+    if (idx->Br == 64) return launch<64, 2>(P, Mb, workspace, workspace_bytes, s);
+    if (idx->Br == 128) return launch<64, 4>(P, Mb, workspace, workspace_bytes, s);
+    return launch<64, 8>(P, Mb, workspace, workspace_bytes, s);
   }
-  if (idx->Br == 64) return launch<128, 2>(P, Mb, workspace, s);
-  if (idx->Br == 128) return launch<128, 4>(P, Mb, workspace, s);
-  return launch<128, 8>(P, Mb, workspace, s);
+  if (idx->Br == 64) return launch<128, 2>(P, Mb, workspace, workspace_bytes, s);
+  if (idx->Br == 128) return launch<128, 4>(P, Mb, workspace, workspace_bytes, s);
+  return launch<128, 8>(P, Mb, workspace, workspace_bytes, s);
 }
 }  // namespace
 
@@ -864,3 +886,4 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd_rect(const vo
   return attn_fwd_impl("bbm_attn_fwd_rect", q, k, v, o, lse, B, H, Nq, Nk, d, softmax_scale, Mb, packed_mask, idx, mode, workspace, workspace_bytes,
                        stream);
 }
+

@@ -898,6 +898,9 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_bwd(const void* q
   if (idx->Bc != 64 || (idx->Br != 64 && idx->Br != 128 && idx->Br != 256))
     return fail(BBM_EUNSUPPORTED, "bbm_attn_bwd: tile (Br=%d, Bc=%d) has no kernel instance (Br in {64,128,256}, Bc = 64)", idx->Br, idx->Bc);
   const int64_t nbr = ceil_div(N, idx->Br), nbc = ceil_div(N, idx->Bc);
+  if (idx->Nq != N || idx->Nk != N)
+    return fail(BBM_EINVAL, "bbm_attn_bwd: index built for a mask of %lld x %lld does not match N=%lld", (long long)idx->Nq, (long long)idx->Nk,
+                (long long)N);
   if (idx->Mb != Mb || idx->nbr != nbr || idx->nbc != nbc)
     return fail(BBM_EINVAL, "bbm_attn_bwd: index (Mb=%lld, nbr=%lld, nbc=%lld) does not match the problem (Mb=%lld, nbr=%lld, nbc=%lld)",
                 (long long)idx->Mb, (long long)idx->nbr, (long long)idx->nbc, (long long)Mb, (long long)nbr, (long long)nbc);

@@ -75,7 +75,7 @@ def test_index_builders_reject_bad_arguments(bbm):
 
 def _idx(bbm, Br=128, Bc=64, Mb=1, N=256, **ptrs):
     from paper_2409_15097_amd.binding import _CIndex
-    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), *([None] * 13))
+    s = _CIndex(Br, Bc, Mb, -(-N // Br), -(-N // Bc), N, N, *([None] * 13))
     for k, v in ptrs.items():
         setattr(s, k, v)
     return s
@@ -110,11 +110,25 @@ def test_attn_fwd_rejects_bad_arguments(bbm):
     assert _attn(bbm, idx, mode=bbm.BBM_MODE_AUTO) == bbm.BBM_EINVAL          # AUTO falls back to BITMAP, which needs bin_blk_mat
 
 
+def test_index_built_for_another_length_is_refused_even_with_equal_block_counts(bbm):
+    """N = 200 and N = 256 both give 2 x 4 blocks at 128 x 64, but the packed mask's row stride differs."""
+    idx = _idx(bbm, N=200)
+    assert (idx.nbr, idx.nbc) == (2, 4)
+    assert _attn(bbm, idx, N=256) == bbm.BBM_EINVAL and "does not match" in bbm.bbm_last_error()
+    assert _bwd(bbm, _idx(bbm, N=200, row_ptr=0x2000, col_idx=0x3000, col_ptr=0x4000, row_idx=0x5000), N=256) == bbm.BBM_EINVAL
+    assert "does not match" in bbm.bbm_last_error()
+
+
 def test_workspace_query_and_check(bbm):
     need = bbm.bbm_attn_fwd_workspace_bytes(4, 16, 4096, 64, 128, 64, bbm.BBM_MODE_LIST)
     assert need > 0 and need == bbm.bbm_attn_fwd_workspace_bytes(4, 16, 4096, 64, 128, 64, bbm.BBM_MODE_AUTO)
     assert bbm.bbm_attn_fwd_workspace_bytes(4, 16, 4096, 64, 128, 64, bbm.BBM_MODE_BITMAP) == 0
     assert bbm.bbm_attn_fwd_workspace_bytes(0, 16, 4096, 64, 128, 64, bbm.BBM_MODE_LIST) == 0
+    # counters (8 + B*H*nbr ints, rounded to 256 bytes) + partial records of (d/2 + 2) * 2*Br floats, capped at 32 MiB
+    assert need == 8448 + (32 << 20)
+    assert bbm.bbm_attn_fwd_workspace_bytes(2, 8, 2048, 64, 128, 64, bbm.BBM_MODE_LIST) == 1280 + 256 * 34 * 256 * 4
+    # a small launch (B*H*nbr = 64 < 128 work-groups): 8 parts per block row, each parking a record
+    assert bbm.bbm_attn_fwd_workspace_bytes(1, 32, 256, 128, 128, 64, bbm.BBM_MODE_LIST) == 512 + 64 * 8 * 66 * 256 * 4
     idx = _idx(bbm, row_ptr=0x2000, col_idx=0x3000, sched=0x4000)
     assert _attn(bbm, idx, mode=bbm.BBM_MODE_LIST) == bbm.BBM_EWORKSPACE          # no workspace given
     assert "workspace" in bbm.bbm_last_error()
