@@ -32,7 +32,8 @@ extern "C" {
 #define BBM_OK 0
 #define BBM_EINVAL (-1)       /* NULL / misaligned pointer, non-positive size, inconsistent arguments */
 #define BBM_EUNSUPPORTED (-2) /* no kernel instance for this (d, Br, Bc) or block size               */
-#define BBM_EWORKSPACE (-3)   /* workspace smaller than bbm_attn_fwd_workspace_bytes()               */
+#define BBM_EWORKSPACE (-3)   /* workspace smaller than bbm_attn_fwd_workspace_bytes(), or a problem beyond the static
+                                 scratch of bbm_attn_fwd_static                                       */
 #define BBM_EHIP (-4)         /* the HIP runtime reported a launch failure                            */
 
 /* Block classes written by bbm_build_block_mask (paper Appendix A: the block sum decides both outputs). */
@@ -233,6 +234,27 @@ int bbm_attn_fwd_rect(const void* q, const void* k, const void* v, void* o, floa
                       int64_t Nk, int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask,
                       const bbm_index* idx, int mode, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * bbm_attn_fwd_rect for callers that cannot allocate device memory and have no workspace to hand over: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the workspace),
+ * same kernels, same results; the queue counters and partial results of LIST mode live in a 32 MiB array that is part
+ * of the library's device code (every GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing.
+ *   - Limit: the counters, 4 * (8 + B*H*ceil(Nq/Br)) bytes, plus one partial record must fit in the 32 MiB, else
+ *     BBM_EWORKSPACE (use bbm_attn_fwd_rect with a workspace).  What fits beyond that decides how the work is cut: a
+ *     small launch computes its block rows in as many parts as find room, and a schedule whose cut parts do not all
+ *     find room is not followed (same results up to the rounding order of the merge; slower on such masks).
+ *   - The call clears the counters it uses with a fill kernel on `stream` before the attention kernel; the array
+ *     otherwise keeps the last call's contents.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams, or
+ *     different host threads without ordering) race.  Calls on different GPUs do not interact.
+ *   - The current device must be the one `stream` and the data pointers belong to.  The first call on a device looks up
+ *     the array's address (which loads the library's device code there): make that call outside graph capture.
+ * Errors: as bbm_attn_fwd_rect, BBM_EWORKSPACE as above, BBM_EUNSUPPORTED for device ordinals of 64 and above.
+ */
+int bbm_attn_fwd_static(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t Nq,
+                        int64_t Nk, int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask,
+                        const bbm_index* idx, int mode, void* stream);
 
 /*
  * Per-column list of non-zero blocks, the transpose of the list of bbm_build_sparse_index: what the dK/dV step of

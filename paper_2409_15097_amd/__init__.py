@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     BBM_MODE_BITMAP, BBM_MODE_RUNS, BBM_MODE_LIST, BBM_MODE_DENSE_BASELINE, BBM_MODE_AUTO,
     BBM_OK, BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EWORKSPACE, BBM_EHIP,
     BbmError, BlockIndex, lib, library_path,
-    bbm_last_error, bbm_version, bbm_build_block_mask, bbm_build_block_mask_rect, bbm_attn_fwd_rect, bbm_build_runs, bbm_build_sparse_index,
+    bbm_last_error, bbm_version, bbm_build_block_mask, bbm_build_block_mask_rect, bbm_attn_fwd_rect, bbm_attn_fwd_static, bbm_build_runs, bbm_build_sparse_index,
     bbm_build_index, bbm_build_col_index, bbm_col_sched_bytes, bbm_attn_bwd_workspace_bytes, bbm_attn_bwd,
     bbm_attn_fwd_workspace_bytes, bbm_attn_fwd, bbm_sched_bytes, build_index, bf16_from_bits,
     bbm_rcm_workspace_bytes, bbm_rcm_order, bbm_permute_mask, bbm_gather_rows,

@@ -48,6 +48,8 @@ def _load():
     L.bbm_attn_fwd_rect.restype = ci
     L.bbm_attn_fwd_rect.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, C.c_float, i64, vp, C.POINTER(_CIndex), ci,
                                     vp, C.c_size_t, vp]
+    L.bbm_attn_fwd_static.restype = ci
+    L.bbm_attn_fwd_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, C.c_float, i64, vp, C.POINTER(_CIndex), ci, vp]
     L.bbm_build_runs.restype = ci
     L.bbm_build_runs.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
     L.bbm_build_sparse_index.restype = ci
@@ -336,6 +338,17 @@ def bbm_attn_fwd_rect(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: Bl
     else:
         _check(lib.bbm_attn_fwd_rect(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, N, Nk, d, softmax_scale, idx.Mb,
                                      _ptr(idx.packed_mask), C.byref(cs), mode, _ptr(workspace), ws_bytes, _stream(stream)))
+    return out, lse
+
+
+def bbm_attn_fwd_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: BlockIndex, out: torch.Tensor,
+                        lse: torch.Tensor, mode: int = BBM_MODE_AUTO, softmax_scale: Optional[float] = None, stream=None):
+    """bbm_attn_fwd_rect without a workspace: the library's own static scratch serves LIST mode.  Nothing is allocated
+    here either: the caller passes out and lse."""
+    B, H, N, Nk, d, softmax_scale, out, lse = _fwd_args(q, k, v, idx, softmax_scale, out, lse, stream)
+    cs = idx.c_struct()
+    _check(lib.bbm_attn_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, N, Nk, d, softmax_scale, idx.Mb,
+                                   _ptr(idx.packed_mask), C.byref(cs), mode, _stream(stream)))
     return out, lse
 
 

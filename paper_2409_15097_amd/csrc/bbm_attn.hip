@@ -16,6 +16,7 @@
 #include "bbm_internal.h"
 
 #include <algorithm>
+#include <mutex>
 
 namespace {
 
@@ -775,10 +776,46 @@ extern "C" __attribute__((visibility("default"))) size_t bbm_attn_fwd_workspace_
   return queue_bytes(1, nbr, B * H) + (split > 1 ? (size_t)(B * H * nbr * split) * record_bytes(d, Br) : partial_bytes(1, nbr, B * H, d, Br));
 }
 
+// ---- Scratch of bbm_attn_fwd_static: a file-scope device array instead of a caller's workspace, for callers that
+// cannot allocate.  Every GPU the library runs on holds its own copy at its own address; host code only ever uses the
+// address hipGetSymbolAddress returned for the current device, never the array's name.
+constexpr size_t kStaticScratchBytes = 32u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device, kept afterwards).
+int static_scratch_address(const char* fn, void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return bbm::fail(BBM_EHIP, "%s: hipGetDevice: %s", fn, hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return bbm::fail(BBM_EUNSUPPORTED, "%s: device %d is beyond the %d devices the static scratch serves", fn, dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return bbm::fail(BBM_EHIP, "%s: hipGetSymbolAddress(scratch): %s", fn, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return BBM_OK;
+}
+
+// The queue counters at the head of the scratch must be zero when the attention kernel starts.  (A fill kernel, not a
+// memset: a caller may be recording the stream into a graph.)
+__global__ __launch_bounds__(256) void clear_counters_kernel(int32_t* counters, int n) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t < n) counters[t] = 0;
+}
+}  // namespace
+
 namespace {
 int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H, int64_t N, int64_t Nk,
                   int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask, const bbm_index* idx, int mode,
-                  void* workspace, size_t workspace_bytes, void* stream) {
+                  void* workspace, size_t workspace_bytes, void* stream, bool use_static) {
   using namespace bbm;
   clear_error();
   if (!q || !k || !v || !o) return fail(BBM_EINVAL, "%s: q, k, v, o must not be NULL", fn);
@@ -825,10 +862,28 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   if (nbr * nbc >= (1ll << 31) || B * H * nbr >= (1ll << 31) || N >= (1ll << 31) || Nk >= (1ll << 31))
     return fail(BBM_EUNSUPPORTED, "%s: problem too large for 32-bit tile counters", fn);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const size_t need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx->Br, idx->Bc, mode);
-  if (need > 0 && (!workspace || workspace_bytes < need))
-    return fail(BBM_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
-  if (need > 0 && !aligned(workspace, 16)) return fail(BBM_EINVAL, "%s: workspace must be 16-byte aligned", fn);
+  if (use_static) {
+    workspace = nullptr;
+    workspace_bytes = 0;
+    if (mode == BBM_MODE_LIST) {
+      // the counters and at least one partial result per (batch, head) must fit; what else fits decides whether cut
+      // rows and small launches are computed in parts (see launch())
+      const size_t floor_bytes = queue_bytes(Mb, nbr, Mb == 1 ? B * H : H) + record_bytes(d, idx->Br);
+      if (floor_bytes > kStaticScratchBytes)
+        return fail(BBM_EWORKSPACE, "%s: B*H*ceil(Nq/Br) = %lld block rows need %zu bytes of counters, beyond the static scratch of %zu bytes; "
+                    "use bbm_attn_fwd_rect with a workspace", fn, (long long)(B * H * nbr), floor_bytes, kStaticScratchBytes);
+      if (int rc = static_scratch_address(fn, &workspace)) return rc;
+      workspace_bytes = kStaticScratchBytes;
+      const int n_counters = (int)(8 + B * H * nbr);
+      clear_counters_kernel<<<(unsigned)((n_counters + 255) / 256), 256, 0, s>>>(static_cast<int32_t*>(workspace), n_counters);
+      if (int rc = launch_status(fn)) return rc;
+    }
+  } else {
+    const size_t need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx->Br, idx->Bc, mode);
+    if (need > 0 && (!workspace || workspace_bytes < need))
+      return fail(BBM_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
+    if (need > 0 && !aligned(workspace, 16)) return fail(BBM_EINVAL, "%s: workspace must be 16-byte aligned", fn);
+  }
 
   AttnParams P;
   P.q = static_cast<const __bf16*>(q);
@@ -876,7 +931,7 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
 extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B, int64_t H,
                             int64_t N, int d, float softmax_scale, int64_t Mb, const uint64_t* packed_mask,
                             const bbm_index* idx, int mode, void* workspace, size_t workspace_bytes, void* stream) {
-  return attn_fwd_impl("bbm_attn_fwd", q, k, v, o, lse, B, H, N, N, d, softmax_scale, Mb, packed_mask, idx, mode, workspace, workspace_bytes, stream);
+  return attn_fwd_impl("bbm_attn_fwd", q, k, v, o, lse, B, H, N, N, d, softmax_scale, Mb, packed_mask, idx, mode, workspace, workspace_bytes, stream, false);
 }
 
 extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd_rect(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B,
@@ -884,6 +939,11 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd_rect(const vo
                                  const uint64_t* packed_mask, const bbm_index* idx, int mode, void* workspace,
                                  size_t workspace_bytes, void* stream) {
   return attn_fwd_impl("bbm_attn_fwd_rect", q, k, v, o, lse, B, H, Nq, Nk, d, softmax_scale, Mb, packed_mask, idx, mode, workspace, workspace_bytes,
-                       stream);
+                       stream, false);
 }
 
+extern "C" __attribute__((visibility("default"))) int bbm_attn_fwd_static(const void* q, const void* k, const void* v, void* o, float* lse, int64_t B,
+                                   int64_t H, int64_t Nq, int64_t Nk, int d, float softmax_scale, int64_t Mb,
+                                   const uint64_t* packed_mask, const bbm_index* idx, int mode, void* stream) {
+  return attn_fwd_impl("bbm_attn_fwd_static", q, k, v, o, lse, B, H, Nq, Nk, d, softmax_scale, Mb, packed_mask, idx, mode, nullptr, 0, stream, true);
+}

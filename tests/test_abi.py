@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(bbm):
                      "bbm_build_sparse_index", "bbm_build_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes",
                      "bbm_attn_fwd", "bbm_build_col_index", "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes",
                      "bbm_attn_bwd", "bbm_build_block_mask_rect", "bbm_attn_fwd_rect", "bbm_rcm_workspace_bytes",
-                     "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows"}
+                     "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows", "bbm_attn_fwd_static"}
     raw = C.CDLL(bbm.library_path())
     for n in names:
         assert getattr(raw, n) is not None
@@ -35,7 +35,8 @@ def test_binding_has_the_same_names(bbm):
               "bbm_build_index",
               "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd", "bbm_build_col_index",
               "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd", "bbm_build_block_mask_rect",
-              "bbm_attn_fwd_rect", "bbm_rcm_workspace_bytes", "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows"):
+              "bbm_attn_fwd_rect", "bbm_rcm_workspace_bytes", "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows",
+              "bbm_attn_fwd_static"):
         assert callable(getattr(bbm, n))
 
 
@@ -117,6 +118,21 @@ def test_index_built_for_another_length_is_refused_even_with_equal_block_counts(
     assert _attn(bbm, idx, N=256) == bbm.BBM_EINVAL and "does not match" in bbm.bbm_last_error()
     assert _bwd(bbm, _idx(bbm, N=200, row_ptr=0x2000, col_idx=0x3000, col_ptr=0x4000, row_idx=0x5000), N=256) == bbm.BBM_EINVAL
     assert "does not match" in bbm.bbm_last_error()
+
+
+def test_static_scratch_entry_point_validates_like_the_workspace_one_and_states_its_limit(bbm):
+    L = bbm.lib
+    idx = _idx(bbm, row_ptr=0x2000, col_idx=0x3000, sched=0x4000)
+    call = lambda B=1, H=1, N=256, q=FAKE, index=idx, mode=bbm.BBM_MODE_LIST: L.bbm_attn_fwd_static(
+        q, FAKE, FAKE, FAKE, None, B, H, N, N, 64, 0.125, 1, FAKE, C.byref(index), mode, None)
+    assert call(q=None) == bbm.BBM_EINVAL and "bbm_attn_fwd_static" in bbm.bbm_last_error()
+    assert call(N=512) == bbm.BBM_EINVAL
+    assert call(mode=17) == bbm.BBM_EINVAL
+    assert call(index=_idx(bbm), mode=bbm.BBM_MODE_LIST) == bbm.BBM_EINVAL       # LIST needs the list
+    # 2^23 block rows x heads: 32 MiB of counters alone do not fit the static scratch
+    big = _idx(bbm, N=65536, Br=64, row_ptr=0x2000, col_idx=0x3000, sched=0x4000)
+    assert call(B=64, H=128, N=65536, index=big) == bbm.BBM_EWORKSPACE
+    assert "static scratch" in bbm.bbm_last_error() and "bbm_attn_fwd_rect" in bbm.bbm_last_error()
 
 
 def test_workspace_query_and_check(bbm):
