@@ -213,9 +213,12 @@ size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
  *                    cleared again.  Before a call of another shape clear the counters again: one shape's partial
  *                    results may lie where another shape's counters do.  Two calls that overlap in time (different streams) must not
  *                    share a workspace.
- * Arithmetic: QK^T and PV on bf16 MFMA with fp32 accumulation; Q is multiplied by softmax_scale*log2(e) and
- * rounded to bf16 once, so the first product yields base-2 exponents directly; softmax statistics in fp32; P rounded
- * to bf16 before PV and the row sum adds the rounded P.  Deterministic: the same inputs give bit-identical outputs (in LIST mode the parts of a cut row
+ * Arithmetic: QK^T and PV on bf16 MFMA with fp32 accumulation; softmax statistics in fp32; P rounded to bf16 before PV
+ * and the row sum adds the rounded P.  For softmax_scale <= 1/sqrt(d) (the usual choice and anything flatter) Q is
+ * multiplied by softmax_scale*log2(e) and rounded to bf16 once, so the first product yields base-2 exponents directly
+ * (a score moves by at most 2^-9 * softmax_scale * sum_c |q_c k_c|).  For sharper scales that rounding would grow with
+ * the scale, so only the power-of-two part of softmax_scale*log2(e) goes into Q (exact in bf16) and the rest multiplies
+ * the first product's fp32 result: the same accuracy at every scale, for one more multiplication per score.  Deterministic: the same inputs give bit-identical outputs (in LIST mode the parts of a cut row
  * are taken from a queue in whatever order work-groups become free, but each part's arithmetic and the order in
  * which the parts are merged are fixed).
  * Errors: BBM_EINVAL, BBM_EUNSUPPORTED (d / Br / Bc without a kernel instance), BBM_EWORKSPACE, BBM_EHIP.
@@ -315,7 +318,8 @@ size_t bbm_attn_bwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
  *                    back the zeros it disturbed (its two counter arrays come first: 8 + B*H*nbr and 8 + B*H*nbc int32,
  *                    each rounded up to 256 bytes); clear them again before a call of another shape.  Two calls that overlap in time must not share a workspace.
  * Arithmetic: all five products on bf16 MFMA with fp32 accumulation; Q (dQ step) resp. K (dK/dV step) is multiplied by
- * softmax_scale*log2(e) and rounded to bf16 once; P and dS are rounded to bf16 before the products that consume them.
+ * softmax_scale*log2(e) and rounded to bf16 once (for scales sharper than 1/sqrt(d): by its power-of-two part only, the
+ * rest being applied in fp32, as in bbm_attn_fwd); P and dS are rounded to bf16 before the products that consume them.
  * Two kernels, no floating-point atomics: the same inputs give bit-identical outputs (parts of a cut row or column are
  * taken from a queue in whatever order work-groups become free, but are summed in part order).
  * Errors: BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EWORKSPACE, BBM_EHIP.

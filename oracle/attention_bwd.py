@@ -59,6 +59,40 @@ def masked_attention_bwd(q, k, v, mask, do, scale=None, row_chunk=512):
     return dQ, dK, dV
 
 
+def masked_attention_bwd_magnitudes(q, k, v, mask, do, scale=None, row_chunk=512):
+    """Size of the terms each gradient element is a sum of (not a gradient: the yardstick against which the rounding
+    error of a reduced-precision implementation of masked_attention_bwd is judged).  Every element of dV, dQ, dK above is a
+    sum of products of either sign; an implementation that carries a relative error eps in p_ij, dP_ij or D_i is off by
+    about eps times the sum of the ABSOLUTE values of those products, however small the element itself comes out:
+
+        MV_jc = sum_i p_ij |dO_ic|
+        MQ_ic = scale * sum_j p_ij (|dP_ij| + |D_i|) |k_jc|
+        MK_jc = scale * sum_i p_ij (|dP_ij| + |D_i|) |q_ic|
+
+    (dS_ij = p_ij (dP_ij - D_i) is itself a difference, hence |dP| + |D|.)  By the triangle inequality each magnitude
+    bounds the absolute value of its gradient element.  Same arguments and shapes as masked_attention_bwd."""
+    q, k, v, do = _as_f64(q), _as_f64(k), _as_f64(v), _as_f64(do)
+    B, H, N, d = q.shape
+    Mb = mask.shape[0]
+    assert mask.shape == (Mb, N, N) and Mb in (1, B) and do.shape == q.shape
+    scale = 1.0 / np.sqrt(float(d)) if scale is None else float(scale)
+    MQ, MK, MV = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for b in range(B):
+        mb = mask[b if Mb == B else 0]
+        for r0 in range(0, N, row_chunk):
+            r1 = min(N, r0 + row_chunk)
+            allowed = mb[r0:r1] != 0
+            for h in range(H):
+                p = _row_softmax(scale * (q[b, h, r0:r1] @ k[b, h].T), allowed)
+                MV[b, h] += p.T @ np.abs(do[b, h, r0:r1])
+                dP = do[b, h, r0:r1] @ v[b, h].T
+                D = (p * dP).sum(axis=1)
+                w = p * (np.abs(dP) + np.abs(D)[:, None])
+                MQ[b, h, r0:r1] = scale * (w @ np.abs(k[b, h]))
+                MK[b, h] += scale * (w.T @ np.abs(q[b, h, r0:r1]))
+    return MQ, MK, MV
+
+
 def masked_attention_bwd_rows(q, k, v, mask, do, rows, scale=None):
     """dQ of sampled query rows (b, h, i), each from its own row of the definition alone.  Returns [len(rows), d]."""
     B, H, N, d = q.shape

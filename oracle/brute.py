@@ -44,3 +44,33 @@ def brute_block_counts(mask2d, Br, Bc):
                         c += 1
             cnt[bi][bj] = c
     return np.asarray(cnt, dtype=np.int64)
+
+
+def brute_bwd_magnitudes(q, k, v, mask, do, scale):
+    """Term magnitudes of the attention gradients (see attention_bwd.masked_attention_bwd_magnitudes), one (query, key)
+    pair at a time in pure Python: p_ij from an explicit softmax over the allowed keys of row i, dP_ij and D_i from
+    explicit dot products, every product added in absolute value.  q, k, v, do [B,H,N,d]; mask [Mb,N,N]."""
+    B, H, N, d = q.shape
+    Mb = mask.shape[0]
+    MQ, MK, MV = np.zeros((B, H, N, d)), np.zeros((B, H, N, d)), np.zeros((B, H, N, d))
+    for b in range(B):
+        mb = mask[b if Mb == B else 0]
+        for h in range(H):
+            for i in range(N):
+                A = [j for j in range(N) if mb[i, j] != 0]
+                if not A:
+                    continue
+                s = [scale * sum(float(q[b, h, i, c]) * float(k[b, h, j, c]) for c in range(d)) for j in A]
+                mx = max(s)
+                w = [math.exp(x - mx) for x in s]
+                tot = sum(w)
+                p = [x / tot for x in w]
+                dP = [sum(float(do[b, h, i, c]) * float(v[b, h, j, c]) for c in range(d)) for j in A]
+                D = sum(pj * dpj for pj, dpj in zip(p, dP))
+                for pj, dpj, j in zip(p, dP, A):
+                    size = pj * (abs(dpj) + abs(D))
+                    for c in range(d):
+                        MV[b, h, j, c] += pj * abs(float(do[b, h, i, c]))
+                        MQ[b, h, i, c] += scale * size * abs(float(k[b, h, j, c]))
+                        MK[b, h, j, c] += scale * size * abs(float(q[b, h, i, c]))
+    return MQ, MK, MV

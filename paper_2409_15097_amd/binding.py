@@ -9,7 +9,8 @@ import torch
 BBM_OK, BBM_EINVAL, BBM_EUNSUPPORTED, BBM_EWORKSPACE, BBM_EHIP = 0, -1, -2, -3, -4
 BBM_MODE_BITMAP, BBM_MODE_RUNS, BBM_MODE_LIST, BBM_MODE_DENSE_BASELINE, BBM_MODE_AUTO = 0, 1, 2, 3, 4
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbbm.so")
+# BBM_LIBRARY names another build of the same library (the host-sanitizer build of the argument checks, say)
+_LIB_PATH = os.environ.get("BBM_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbbm.so")
 
 
 class BbmError(RuntimeError):

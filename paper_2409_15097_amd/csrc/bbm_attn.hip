@@ -49,7 +49,8 @@ struct AttnParams {
   int32_t H, Mb, nbr, nbc, W;
   int32_t total_wgs;
   int32_t mode;
-  float scale;
+  float qscale;       // factor applied to Q before it is rounded to bf16 (see `rmul`)
+  float rmul;         // factor applied to the first product's result inside the exponential (EXACT instances), else 1
   // LIST mode: schedule (read-only), work-queue state and partial results of cut rows (in the caller's workspace)
   const int32_t* sched;
   int32_t* queue;     // [0] part items handed out, [1] leading work-groups done, [8 + rho*hbp + hb] finished parts of
@@ -156,7 +157,13 @@ struct IntC {
 // P.n_extra work-groups, before turning to their own block row, take the parts of the block rows which the split
 // schedule cut from a queue; the work-group that completes a row's last part merges the parts in part order and
 // writes the row, and the row's own work-group skips it.
-template <int D, int NW, int SCHED>
+//
+// The softmax needs exp2(c * <q, k> - m) with c = softmax_scale * log2(e).  EXACT = false: Q is multiplied by c and
+// rounded to bf16, so the first product delivers the exponent directly (no per-element multiplication; the rounding
+// moves a score by up to 2^-9 * c * sum |q_d k_d|, harmless up to the usual scale 1/sqrt(d)).  EXACT = true (sharper
+// scales): c = 2^k * r with r in [1, 2); Q is multiplied by 2^k, which is exact in bf16, and r multiplies the
+// accumulator inside the exponential; running maxima are then kept in units of 1/r.
+template <int D, int NW, int SCHED, bool EXACT>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   constexpr int NT = NW * 64;
   constexpr int BR = NW * 32;
@@ -189,7 +196,9 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction: keep it in a scalar register
   const int lq = lane & 31, hh = lane >> 5;
   const int64_t N = P.N, Nk = P.Nk;
-  const float c = P.scale * kLog2e;
+  const float c = P.qscale;
+  const float rr = EXACT ? P.rmul : 1.0f;
+  auto ex2 = [&](float x) { return __builtin_amdgcn_exp2f(EXACT ? rr * x : x); };
 
   // ---- per-item state (SCHED = false: exactly one item, derived from blockIdx)
   int m, i, bh;
@@ -394,7 +403,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
         const float m_old = (m_run == -INFINITY) ? 0.0f : m_run;       // what the accumulators started from
         const float m_new = fmaxf(m_run, m_old + mx);
         const float m_fin = (m_new == -INFINITY) ? 0.0f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_fin);
+        const float alpha = ex2(m_run - m_fin);
         const float shift = m_fin - m_old;
         l_run *= alpha;
         m_run = m_new;
@@ -413,7 +422,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       for (int u = 0; u < 4; ++u) {
         bf16x8 pf;
   #pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)__builtin_amdgcn_exp2f(s[u / 2][8 * (u % 2) + e]);
+        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)ex2(s[u / 2][8 * (u % 2) + e]);
         // row sum of the ROUNDED probabilities (the same numbers the second product consumes), two per instruction
   #pragma unroll
         for (int e = 0; e < 8; e += 2) {
@@ -508,7 +517,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       if (row0 + r < N) *reinterpret_cast<bf16x8*>(og + r * D + gco * 8) = ov;
     }
     if (q_ok && P.lse && hh == 0)
-      P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * (1.0f / kLog2e) + __logf(l_tot) : -INFINITY;
+      P.lse[(int64_t)bh * N + qrow] = l_tot > 0.0f ? m_run * (rr / kLog2e) + __logf(l_tot) : -INFINITY;
   };
 
   // ---- LIST mode on a small launch: work-group = (block row, part); the parts of a row run side by side and the last
@@ -562,7 +571,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
       l_run = 0.0f;
       for (int k = 0; k < S; ++k) {
         const float* rk = r0 + k * pstride;
-        const float wgt = __builtin_amdgcn_exp2f(rk[REGS * NT] - m_fin);
+        const float wgt = ex2(rk[REGS * NT] - m_fin);
         l_run += wgt * rk[(REGS + 1) * NT];
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -662,7 +671,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
         l_run = 0.0f;
         for (int k = 0; k < nparts; ++k) {  // fixed order: the result does not depend on which part came last
           const float* rk = r0 + k * pstride;
-          const float wgt = __builtin_amdgcn_exp2f(rk[REGS * NT] - m_fin);
+          const float wgt = ex2(rk[REGS * NT] - m_fin);
           l_run += wgt * rk[(REGS + 1) * NT];
 #pragma unroll
           for (int db = 0; db < DB; ++db)
@@ -743,7 +752,7 @@ inline int split_parts(int64_t total_wgs, int64_t nbc) {
   return s < 2 ? 1 : (int)s;
 }
 
-template <int D, int NW>
+template <int D, int NW, bool EXACT>
 int launch(AttnParams& P, int64_t Mb, void* workspace, size_t workspace_bytes, hipStream_t s) {
   if (P.mode == BBM_MODE_LIST) {
     const size_t qb = queue_bytes(Mb, P.nbr, P.hbp);
@@ -755,11 +764,11 @@ int launch(AttnParams& P, int64_t Mb, void* workspace, size_t workspace_bytes, h
     P.split = split_parts(P.total_wgs, P.nbc);
     while (P.split > 1 && (int64_t)P.total_wgs * P.split > cap) --P.split;  // every (row, part, head) parks a record
     if (P.split > 1)
-      attn_fwd_kernel<D, NW, 2><<<(unsigned)(P.total_wgs * P.split), NW * 64, 0, s>>>(P);
+      attn_fwd_kernel<D, NW, 2, EXACT><<<(unsigned)(P.total_wgs * P.split), NW * 64, 0, s>>>(P);
     else
-      attn_fwd_kernel<D, NW, 1><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+      attn_fwd_kernel<D, NW, 1, EXACT><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   } else {
-    attn_fwd_kernel<D, NW, 0><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+    attn_fwd_kernel<D, NW, 0, EXACT><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   }
   return bbm::launch_status("bbm_attn_fwd");
 }
@@ -908,7 +917,13 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   P.W = (int32_t)ceil_div(Nk, 64);
   P.total_wgs = (int32_t)(B * H * nbr);
   P.mode = mode;
-  P.scale = softmax_scale;
+  // scales up to the usual 1/sqrt(d) fold into the bf16 Q; sharper ones keep the non-power-of-two part in fp32
+  const float c = softmax_scale * kLog2e;
+  const bool exact = softmax_scale * sqrtf((float)d) > 1.0f + 1.0f / 1024.0f;
+  int c_exp = 0;
+  (void)frexpf(c, &c_exp);                       // c = f * 2^c_exp, f in [0.5, 1)
+  P.qscale = exact ? ldexpf(1.0f, c_exp - 1) : c;
+  P.rmul = exact ? c / P.qscale : 1.0f;         // in [1, 2)
   P.sched = idx->sched;
   P.queue = nullptr;
   P.partials = nullptr;
@@ -917,14 +932,18 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   P.split = 1;
   P.part_cap = 0;
   P.G = interleaved_planes(B * H, 2 * Nk * d * (int64_t)sizeof(__bf16));
-  if (d == 64) {
-    if (idx->Br == 64) return launch<64, 2>(P, Mb, workspace, workspace_bytes, s);
-    if (idx->Br == 128) return launch<64, 4>(P, Mb, workspace, workspace_bytes, s);
-    return launch<64, 8>(P, Mb, workspace, workspace_bytes, s);
-  }
-  if (idx->Br == 64) return launch<128, 2>(P, Mb, workspace, workspace_bytes, s);
-  if (idx->Br == 128) return launch<128, 4>(P, Mb, workspace, workspace_bytes, s);
-  return launch<128, 8>(P, Mb, workspace, workspace_bytes, s);
+  auto go = [&](auto ex) {
+    constexpr bool EX = decltype(ex)::value != 0;
+    if (d == 64) {
+      if (idx->Br == 64) return launch<64, 2, EX>(P, Mb, workspace, workspace_bytes, s);
+      if (idx->Br == 128) return launch<64, 4, EX>(P, Mb, workspace, workspace_bytes, s);
+      return launch<64, 8, EX>(P, Mb, workspace, workspace_bytes, s);
+    }
+    if (idx->Br == 64) return launch<128, 2, EX>(P, Mb, workspace, workspace_bytes, s);
+    if (idx->Br == 128) return launch<128, 4, EX>(P, Mb, workspace, workspace_bytes, s);
+    return launch<128, 8, EX>(P, Mb, workspace, workspace_bytes, s);
+  };
+  return exact ? go(IntC<1>{}) : go(IntC<0>{});
 }
 }  // namespace
 

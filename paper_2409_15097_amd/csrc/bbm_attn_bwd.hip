@@ -53,6 +53,8 @@ struct BwdParams {
   int32_t G, Gc;    // (batch, head) planes whose block rows / block columns are interleaved in launch order
   int32_t br;       // query rows per block row
   float scale;
+  float qscale;  // factor folded into the bf16 Q (dQ step) resp. K (dK/dV step) operand, see the forward kernel
+  float rmul;    // EXACT instances: the rest of softmax_scale*log2(e), applied in fp32 inside the exponential; else 1
   // Cut block rows (dQ) and cut block columns (dK, dV): the split schedules (read-only), and in the caller's workspace
   // the work-queue state and the fp32 partial results of the parts.  Counters: [0] part items handed out, [1] leading
   // work-groups done, [8 + rho*hbp + hb] finished parts of cut row/column rho; all zero between calls.
@@ -189,7 +191,9 @@ __device__ __forceinline__ int logical_wg(int wg, int total) {
 // row, take the parts of the block rows which the split schedule cut from a queue; the work-group that completes a
 // row's last part adds the parts up in part order and writes the row, and the row's own work-group only writes the
 // statistics.
-template <int D, int NW>
+// EXACT (softmax scales sharper than 1/sqrt(d)): only the power-of-two part of softmax_scale*log2(e) is folded into
+// the bf16 operand, the rest multiplies the recomputed score inside the exponential, as in the forward kernel.
+template <int D, int NW, bool EXACT>
 __global__ __launch_bounds__(NW * 64, (D == 128 && NW >= 4) ? 2 : (D == 64 && NW == 4) ? 3 : 1) void attn_bwd_dq_kernel(const BwdParams P) {
   using L = TL<D>;
   constexpr int NT = NW * 64;
@@ -210,7 +214,9 @@ __global__ __launch_bounds__(NW * 64, (D == 128 && NW >= 4) ? 2 : (D == 64 && NW
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, hh = lane >> 5;
   const int64_t N = P.N;
-  const float c = P.scale * kLog2e;
+  const float c = P.qscale;
+  const float rr = EXACT ? P.rmul : 1.0f;
+  auto ex2 = [&](float x) { return __builtin_amdgcn_exp2f(EXACT ? rr * x : x); };
 
   // ---- per-item state
   int bh, m, i;
@@ -249,7 +255,7 @@ __global__ __launch_bounds__(NW * 64, (D == 128 && NW >= 4) ? 2 : (D == 64 && NW
     }
     const float delta = partner_sum(dsum);
     const float lse_i = q_ok ? P.lse[(int64_t)bh * N + qrow] : -INFINITY;
-    const float nl = (lse_i == -INFINITY) ? -INFINITY : -lse_i * kLog2e;
+    const float nl = (lse_i == -INFINITY) ? -INFINITY : -lse_i * (kLog2e / rr);
     if (write_stats && q_ok && hh == 0) {
       P.nl2[(int64_t)bh * N + qrow] = nl;
       P.ndelta[(int64_t)bh * N + qrow] = -delta;
@@ -322,7 +328,7 @@ __global__ __launch_bounds__(NW * 64, (D == 128 && NW >= 4) ? 2 : (D == 64 && NW
         for (int u2 = 0; u2 < 2; ++u2) {
           bf16x8 dsf;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) dsf[e] = (__bf16)(__builtin_amdgcn_exp2f(s[8 * u2 + e]) * dp[8 * u2 + e]);
+          for (int e = 0; e < 8; ++e) dsf[e] = (__bf16)(ex2(s[8 * u2 + e]) * dp[8 * u2 + e]);
 #pragma unroll
           for (int db = 0; db < DB; ++db) dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.tr_frag(k_cur, 2 * kb + u2, db), dsf, dq[db], 0, 0, 0);
         }
@@ -458,7 +464,7 @@ __global__ __launch_bounds__(NW * 64, (D == 128 && NW >= 4) ? 2 : (D == 64 && NW
 // Each wave then holds one operand (K or V) and one accumulator set, about half the registers: at D = 128, where the
 // tile buffers let two work-groups share a CU, that puts two waves on every SIMD instead of one, and one wave's
 // exponentials and LDS reads run under the other's matrix products.
-template <int D, bool RS>
+template <int D, bool RS, bool EXACT>
 __global__ __launch_bounds__(RS ? 256 : 128, RS ? 2 : 1) void attn_bwd_dkv_kernel(const BwdParams P) {
   using L = TL<D>;
   constexpr int NW = RS ? 4 : 2, NT = 64 * NW;
@@ -488,7 +494,9 @@ __global__ __launch_bounds__(RS ? 256 : 128, RS ? 2 : 1) void attn_bwd_dkv_kerne
   const int role = RS ? wave >> 1 : 0;  // RS: 0 = S, P, dV; 1 = dP, dS, dK
   const int lq = lane & 31, hh = lane >> 5;
   const int64_t N = P.N;
-  const float c = P.scale * kLog2e;
+  const float c = P.qscale;
+  const float rr = EXACT ? P.rmul : 1.0f;
+  auto ex2 = [&](float x) { return __builtin_amdgcn_exp2f(EXACT ? rr * x : x); };
 
   // ---- per-item state
   int bh, m, j;
@@ -618,7 +626,7 @@ __global__ __launch_bounds__(RS ? 256 : 128, RS ? 2 : 1) void attn_bwd_dkv_kerne
           for (int qb = 0; qb < 2; ++qb) {
             float p[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) p[e] = __builtin_amdgcn_exp2f(acc2[qb][e]);
+            for (int e = 0; e < 16; ++e) p[e] = ex2(acc2[qb][e]);
             if (partial) {
 #pragma unroll
               for (int g = 0; g < 4; ++g) {
@@ -675,7 +683,7 @@ __global__ __launch_bounds__(RS ? 256 : 128, RS ? 2 : 1) void attn_bwd_dkv_kerne
       for (int t = 0; t < KS; ++t) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A.row_frag(g_cur, qb, t), vf[t], dp, 0, 0, 0);
       float p[16];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) p[e] = __builtin_amdgcn_exp2f(sc[e]);
+      for (int e = 0; e < 16; ++e) p[e] = ex2(sc[e]);
       if (partial) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -847,24 +855,24 @@ inline size_t queue_bytes(int64_t B, int64_t H, int64_t nb) { return round256((s
 inline size_t row_partial_bytes(int64_t B, int64_t H, int64_t nbr, int Br, int d) { return (size_t)(B * H * nbr) * Br * d * sizeof(float); }
 inline size_t col_partial_bytes(int64_t B, int64_t H, int64_t nbc, int d) { return (size_t)(B * H * nbc) * 2 * 64 * d * sizeof(float); }
 
-template <int D>
+template <int D, bool EXACT>
 int launch_bwd(BwdParams& P, int64_t B, int64_t H, hipStream_t s) {
   P.total_wgs = (int32_t)(B * H * P.nbr);
   P.n_extra = std::min<int32_t>(P.total_wgs, kExtraWGs);
   P.G = bbm::interleaved_planes(B * H, 2 * P.N * D * (int64_t)sizeof(__bf16));
   if (P.br == 64)
-    attn_bwd_dq_kernel<D, 2><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
+    attn_bwd_dq_kernel<D, 2, EXACT><<<(unsigned)P.total_wgs, 128, 0, s>>>(P);
   else if (P.br == 128)
-    attn_bwd_dq_kernel<D, 4><<<(unsigned)P.total_wgs, 256, 0, s>>>(P);
+    attn_bwd_dq_kernel<D, 4, EXACT><<<(unsigned)P.total_wgs, 256, 0, s>>>(P);
   else
-    attn_bwd_dq_kernel<D, 8><<<(unsigned)P.total_wgs, 512, 0, s>>>(P);
+    attn_bwd_dq_kernel<D, 8, EXACT><<<(unsigned)P.total_wgs, 512, 0, s>>>(P);
   int rc = bbm::launch_status("bbm_attn_bwd (dq)");
   if (rc != BBM_OK) return rc;
   P.total_wgs = (int32_t)(B * H * P.nbc);
   P.n_extra = std::min<int32_t>(P.total_wgs, kExtraWGs);
   P.Gc = P.G;
   constexpr bool RS = D == 128;
-  attn_bwd_dkv_kernel<D, RS><<<(unsigned)P.total_wgs, RS ? 256 : 128, 0, s>>>(P);
+  attn_bwd_dkv_kernel<D, RS, EXACT><<<(unsigned)P.total_wgs, RS ? 256 : 128, 0, s>>>(P);
   return bbm::launch_status("bbm_attn_bwd (dk, dv)");
 }
 
@@ -953,6 +961,14 @@ extern "C" __attribute__((visibility("default"))) int bbm_attn_bwd(const void* q
   P.W = (int32_t)ceil_div(N, 64);
   P.br = idx->Br;
   P.scale = softmax_scale;
+  // the same rule as the forward (whose lse this call consumes): scales up to 1/sqrt(d) fold into the bf16 operand
+  const float c = softmax_scale * kLog2e;
+  const bool exact = softmax_scale * sqrtf((float)d) > 1.0f + 1.0f / 1024.0f;
+  int c_exp = 0;
+  (void)frexpf(c, &c_exp);
+  P.qscale = exact ? ldexpf(1.0f, c_exp - 1) : c;
+  P.rmul = exact ? c / P.qscale : 1.0f;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  return d == 64 ? launch_bwd<64>(P, B, H, s) : launch_bwd<128>(P, B, H, s);
+  if (exact) return d == 64 ? launch_bwd<64, true>(P, B, H, s) : launch_bwd<128, true>(P, B, H, s);
+  return d == 64 ? launch_bwd<64, false>(P, B, H, s) : launch_bwd<128, false>(P, B, H, s);
 }

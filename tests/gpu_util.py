@@ -66,37 +66,79 @@ def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
 
 
 # Tolerances for bf16 inputs/outputs against the fp64 oracle (max-abs, mean-abs on O; max-abs on finite lse).
-# lse: the kernel multiplies Q by scale*log2(e) and rounds it to bf16 once per block row (relative error <= 2^-9 per
-# element), which moves a score by at most 2^-9 * scale * sum_d |q_d k_d| (about 0.64 * sqrt(d) * 2^-9 = 1.0e-2 / 1.4e-2
-# for N(0,1) inputs at d = 64 / 128 if every rounding error had the same sign; a few 1e-3 in practice), and lse moves by
-# no more than the largest score error; the row sum adds bf16-rounded probabilities (<= 2^-9 relative, 2e-3).
-O_MAX_ABS, O_MEAN_ABS, LSE_MAX_ABS = 2e-2, 2e-3, 1.6e-2
+# O: the bars the task states, at every softmax scale.  lse: two roundings set it.  The row sum adds bf16-rounded
+# probabilities (relative error <= 2^-9 each, so |d ln l| <= 2e-3).  Up to the usual scale 1/sqrt(d) the kernel rounds
+# Q * scale * log2(e) to bf16 once per block row, which moves a score by at most 2^-9 * scale * sum_d |q_d k_d|; with
+# errors of random sign that is a few 1e-3 for N(0,1) inputs at d = 64 and 128, and lse moves by no more than the largest
+# score error of its row.  Largest error observed over the full outputs of all full-size workloads: 6.8e-3 (packed
+# sequences, d = 64); the bar is 1e-2.  (Sharper scales do not round the scale into Q at all: 3.6e-3 observed.)
+O_MAX_ABS, O_MEAN_ABS, LSE_MAX_ABS = 2e-2, 2e-3, 1.0e-2
 
 
-def assert_attention_close(o_gpu: torch.Tensor, lse_gpu: torch.Tensor, O_ref: np.ndarray, lse_ref: np.ndarray):
+def record_maxima(tag: str, **values):
+    """Appends the observed error maxima of a parity case to the file named by BBM_MAXIMA_FILE (if set), one JSON line
+    per case: the source of the tolerance table in the design notes."""
+    import json
+    import os
+    path = os.environ.get("BBM_MAXIMA_FILE")
+    if path:
+        with open(path, "a") as f:
+            f.write(json.dumps(dict(case=tag, **{k: float(v) for k, v in values.items()})) + "\n")
+
+
+def attention_errors(o_gpu: torch.Tensor, lse_gpu: torch.Tensor, O_ref: np.ndarray, lse_ref: np.ndarray):
+    """(max-abs of O, sum-abs of O, element count, max-abs of finite lse); asserts the exact parts: no NaN, -inf rows."""
     o = bf16_result_to_f64(o_gpu)
     l = lse_gpu.cpu().numpy().astype(np.float64)
     assert not np.isnan(o).any() and not np.isnan(l).any()
     err = np.abs(o - O_ref)
-    assert err.max() <= O_MAX_ABS, f"max-abs {err.max()}"
-    assert err.mean() <= O_MEAN_ABS, f"mean-abs {err.mean()}"
     fin = np.isfinite(lse_ref)
     assert np.array_equal(np.isfinite(l), fin)
     assert np.all(l[~fin] == -np.inf)
-    if fin.any():
-        assert np.abs(l[fin] - lse_ref[fin]).max() <= LSE_MAX_ABS
-    return err.max(), err.mean()
+    lse_err = float(np.abs(l[fin] - lse_ref[fin]).max()) if fin.any() else 0.0
+    return float(err.max()), float(err.sum()), err.size, lse_err
 
 
-# Gradients (bf16 outputs against the fp64 oracle).  The forward bar (2e-2 max-abs, 2e-3 mean-abs) is stated for O, a
-# convex combination of N(0,1) values; dQ, dK, dV are sums over keys resp. queries whose magnitude grows with the
-# number of terms, and every error source is relative to the terms (bf16 rounding of P, dS and of the result: 2^-9
-# each; the rounding of Q*scale*log2(e) resp. K*scale*log2(e), which moves a probability by up to about 1 %).  So
-# the same two bars are applied relative to the size of the tensor: G = max(1, max |reference|).
-def assert_grad_close(name: str, got_f64: np.ndarray, ref: np.ndarray):
+def assert_attention_close(o_gpu: torch.Tensor, lse_gpu: torch.Tensor, O_ref: np.ndarray, lse_ref: np.ndarray, tag=None):
+    mx, total, n, lse_err = attention_errors(o_gpu, lse_gpu, O_ref, lse_ref)
+    if tag:
+        record_maxima(tag, o_max=mx, o_mean=total / n, lse_max=lse_err)
+    assert mx <= O_MAX_ABS, f"max-abs {mx}"
+    assert total / n <= O_MEAN_ABS, f"mean-abs {total / n}"
+    assert lse_err <= LSE_MAX_ABS, f"lse max-abs {lse_err}"
+    return mx, total / n
+
+
+# Gradients (bf16 outputs against the fp64 oracle).  The forward bars are stated for O, a convex combination of N(0,1)
+# values.  A gradient element is a sum of products of either sign (dV_jc = sum_i p_ij dO_ic, ...), and what a bf16
+# implementation gets wrong is relative to the PRODUCTS: p carries the forward's lse error (up to 0.7 %, the same
+# sign for a whole row) and its own bf16 rounding, dS = p (dP - D) the rounding of O inside D.  So the bar per element
+# is relative to the element's term magnitude M (oracle.masked_attention_bwd_magnitudes: the same sums with every
+# product in absolute value), plus the output format's rounding of the element itself, plus a small floor:
+#     |error| <= GRAD_TERM * M + 2^-8 * |reference| + GRAD_FLOOR,     mean |error| <= GRAD_TERM_MEAN * mean M + GRAD_FLOOR.
+# GRAD_TERM is about twice the largest ratio observed over the full-size workloads and the small cases.  Nothing in
+# it depends on the tensor's overall size.  Where no magnitudes are at hand (rows and keys sampled out of heads that
+# are not compared whole) the cruder form |error| <= 2e-2 * (1 + |reference|) is used.
+GRAD_TERM, GRAD_TERM_MEAN, GRAD_OUT, GRAD_FLOOR = 2e-2, 5e-3, 2.0 ** -8, 1e-3
+GRAD_ABS, GRAD_REL = O_MAX_ABS, 2e-2
+
+
+def assert_grad_close(name: str, got_f64: np.ndarray, ref: np.ndarray, mag=None, tag=None):
     assert not np.isnan(got_f64).any(), name
-    G = max(1.0, float(np.abs(ref).max()))
     err = np.abs(got_f64 - ref)
-    assert err.max() <= O_MAX_ABS * G, f"{name}: max-abs {err.max()} at scale {G}"
-    assert err.mean() <= O_MEAN_ABS * G, f"{name}: mean-abs {err.mean()} at scale {G}"
+    if mag is None:
+        excess = err - GRAD_REL * np.abs(ref)
+        if tag:
+            record_maxima(f"{tag} {name}", max=err.max(), mean=err.mean(), ref_max=np.abs(ref).max(), abs_part_needed=max(0.0, float(excess.max())))
+        assert excess.max() <= GRAD_ABS, f"{name}: an element is off by {excess.max():.3e} beyond {GRAD_REL} of its reference value"
+        return err.max(), err.mean()
+    assert mag.shape == ref.shape and np.all(mag >= np.abs(ref) - 1e-9)
+    over = err - GRAD_OUT * np.abs(ref) - GRAD_FLOOR          # what the term-relative part has to cover
+    ratio = float((over / np.maximum(mag, 1e-30)).max())
+    mean_ratio = float(max(0.0, err.mean() - GRAD_FLOOR) / max(float(mag.mean()), 1e-30))
+    if tag:
+        record_maxima(f"{tag} {name}", max=err.max(), mean=err.mean(), ref_max=np.abs(ref).max(), mag_max=mag.max(), term_ratio=max(0.0, ratio),
+                      mean_ratio=mean_ratio)
+    assert ratio <= GRAD_TERM, f"{name}: an element is off by {ratio:.3e} of its term magnitude (max-abs error {err.max():.3e})"
+    assert mean_ratio <= GRAD_TERM_MEAN, f"{name}: mean-abs error {err.mean():.3e} is {mean_ratio:.3e} of the mean term magnitude"
     return err.max(), err.mean()

@@ -171,3 +171,23 @@ def test_hand_worked_two_by_two():
     m = np.array([[[1, 0], [1, 1]]], dtype=np.uint8)
     dQ, dK, dV = oracle.masked_attention_bwd(q, k, v, m, do, scale=1.0)
     assert np.allclose(dQ.ravel(), [0.0, 1.5], atol=1e-15) and np.allclose(dV.ravel(), [1.5, 0.5], atol=1e-15)
+
+
+def test_term_magnitudes_against_pair_by_pair_loops_and_the_triangle_inequality():
+    """The yardstick of the gradient tolerances: equal to the scalar-loop formulation, never below the absolute value of
+    the gradient it belongs to, equal to it where every term has one sign (dV with dO >= 0), and zero exactly where the
+    gradient has no terms (fully masked query rows, keys nobody attends)."""
+    q, k, v, mask = _rand_case(61, B=2, H=2, N=11, d=3, Mb=2, empty_rows=(4,))
+    mask[:, :, 7] = 0                                              # a key nobody attends
+    do = np.random.default_rng(62).standard_normal(q.shape)
+    scale = 0.37
+    got = oracle.masked_attention_bwd_magnitudes(q, k, v, mask, do, scale=scale, row_chunk=4)
+    want = oracle.brute_bwd_magnitudes(q, k, v, mask, do, scale)
+    grads = oracle.masked_attention_bwd(q, k, v, mask, do, scale=scale)
+    for g, w, gr in zip(got, want, grads):
+        assert np.abs(g - w).max() < 1e-12
+        assert np.all(g >= np.abs(gr) - 1e-12)
+    assert np.all(got[0][:, :, 4] == 0) and np.all(got[1][:, :, 7] == 0) and np.all(got[2][:, :, 7] == 0)
+    pos = np.abs(do)
+    MV = oracle.masked_attention_bwd_magnitudes(q, k, v, mask, pos, scale=scale)[2]
+    assert np.abs(MV - oracle.masked_attention_bwd(q, k, v, mask, pos, scale=scale)[2]).max() < 1e-12
