@@ -62,14 +62,16 @@ def masked_attention_bwd(q, k, v, mask, do, scale=None, row_chunk=512):
 def masked_attention_bwd_magnitudes(q, k, v, mask, do, scale=None, row_chunk=512):
     """Size of the terms each gradient element is a sum of (not a gradient: the yardstick against which the rounding
     error of a reduced-precision implementation of masked_attention_bwd is judged).  Every element of dV, dQ, dK above is a
-    sum of products of either sign; an implementation that carries a relative error eps in p_ij, dP_ij or D_i is off by
-    about eps times the sum of the ABSOLUTE values of those products, however small the element itself comes out:
+    sum of products of either sign; an implementation that carries a relative error eps in p_ij, dP_ij or the terms of
+    D_i is off by about eps times the sum of the ABSOLUTE values of those products, however small the element itself
+    comes out:
 
         MV_jc = sum_i p_ij |dO_ic|
-        MQ_ic = scale * sum_j p_ij (|dP_ij| + |D_i|) |k_jc|
-        MK_jc = scale * sum_i p_ij (|dP_ij| + |D_i|) |q_ic|
+        MQ_ic = scale * sum_j p_ij (|dP_ij| + Dabs_i) |k_jc|,      Dabs_i = sum_c |dO_ic| |O_ic|
+        MK_jc = scale * sum_i p_ij (|dP_ij| + Dabs_i) |q_ic|
 
-    (dS_ij = p_ij (dP_ij - D_i) is itself a difference, hence |dP| + |D|.)  By the triangle inequality each magnitude
+    (dS_ij = p_ij (dP_ij - D_i) is itself a difference, and D_i = <dO_i, O_i> a sum of either sign formed from an output
+    O that an implementation holds in rounded form; hence |dP| + Dabs.)  By the triangle inequality each magnitude
     bounds the absolute value of its gradient element.  Same arguments and shapes as masked_attention_bwd."""
     q, k, v, do = _as_f64(q), _as_f64(k), _as_f64(v), _as_f64(do)
     B, H, N, d = q.shape
@@ -86,8 +88,8 @@ def masked_attention_bwd_magnitudes(q, k, v, mask, do, scale=None, row_chunk=512
                 p = _row_softmax(scale * (q[b, h, r0:r1] @ k[b, h].T), allowed)
                 MV[b, h] += p.T @ np.abs(do[b, h, r0:r1])
                 dP = do[b, h, r0:r1] @ v[b, h].T
-                D = (p * dP).sum(axis=1)
-                w = p * (np.abs(dP) + np.abs(D)[:, None])
+                Dabs = (np.abs(do[b, h, r0:r1]) * np.abs(p @ v[b, h])).sum(axis=1)
+                w = p * (np.abs(dP) + Dabs[:, None])
                 MQ[b, h, r0:r1] = scale * (w @ np.abs(k[b, h]))
                 MK[b, h] += scale * (w.T @ np.abs(q[b, h, r0:r1]))
     return MQ, MK, MV

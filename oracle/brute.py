@@ -49,7 +49,7 @@ def brute_block_counts(mask2d, Br, Bc):
 def brute_bwd_magnitudes(q, k, v, mask, do, scale):
     """Term magnitudes of the attention gradients (see attention_bwd.masked_attention_bwd_magnitudes), one (query, key)
     pair at a time in pure Python: p_ij from an explicit softmax over the allowed keys of row i, dP_ij and D_i from
-    explicit dot products, every product added in absolute value.  q, k, v, do [B,H,N,d]; mask [Mb,N,N]."""
+    explicit dot products, every product added in absolute value (D_i enters as sum_c |dO_ic| |O_ic|).  q, k, v, do [B,H,N,d]; mask [Mb,N,N]."""
     B, H, N, d = q.shape
     Mb = mask.shape[0]
     MQ, MK, MV = np.zeros((B, H, N, d)), np.zeros((B, H, N, d)), np.zeros((B, H, N, d))
@@ -66,9 +66,10 @@ def brute_bwd_magnitudes(q, k, v, mask, do, scale):
                 tot = sum(w)
                 p = [x / tot for x in w]
                 dP = [sum(float(do[b, h, i, c]) * float(v[b, h, j, c]) for c in range(d)) for j in A]
-                D = sum(pj * dpj for pj, dpj in zip(p, dP))
+                out = [sum(pj * float(v[b, h, j, c]) for pj, j in zip(p, A)) for c in range(d)]          # O_i
+                d_abs = sum(abs(float(do[b, h, i, c])) * abs(out[c]) for c in range(d))
                 for pj, dpj, j in zip(p, dP, A):
-                    size = pj * (abs(dpj) + abs(D))
+                    size = pj * (abs(dpj) + d_abs)
                     for c in range(d):
                         MV[b, h, j, c] += pj * abs(float(do[b, h, i, c]))
                         MQ[b, h, i, c] += scale * size * abs(float(k[b, h, j, c]))

@@ -115,11 +115,12 @@ def assert_attention_close(o_gpu: torch.Tensor, lse_gpu: torch.Tensor, O_ref: np
 # sign for a whole row) and its own bf16 rounding, dS = p (dP - D) the rounding of O inside D.  So the bar per element
 # is relative to the element's term magnitude M (oracle.masked_attention_bwd_magnitudes: the same sums with every
 # product in absolute value), plus the output format's rounding of the element itself, plus a small floor:
-#     |error| <= GRAD_TERM * M + 2^-8 * |reference| + GRAD_FLOOR,     mean |error| <= GRAD_TERM_MEAN * mean M + GRAD_FLOOR.
-# GRAD_TERM is about twice the largest ratio observed over the full-size workloads and the small cases.  Nothing in
+#     |error| <= GRAD_TERM * M + 2^-8 * |reference| + GRAD_FLOOR,     mean |error| <= GRAD_TERM_MEAN * mean M.
+# GRAD_TERM is about twice the largest ratio observed over the full-size workloads and the small cases (0.67 %; dV of
+# the tiny random-block mask), GRAD_TERM_MEAN likewise.  Nothing in
 # it depends on the tensor's overall size.  Where no magnitudes are at hand (rows and keys sampled out of heads that
 # are not compared whole) the cruder form |error| <= 2e-2 * (1 + |reference|) is used.
-GRAD_TERM, GRAD_TERM_MEAN, GRAD_OUT, GRAD_FLOOR = 2e-2, 5e-3, 2.0 ** -8, 1e-3
+GRAD_TERM, GRAD_TERM_MEAN, GRAD_OUT, GRAD_FLOOR = 1.5e-2, 5e-3, 2.0 ** -8, 1e-3
 GRAD_ABS, GRAD_REL = O_MAX_ABS, 2e-2
 
 
@@ -135,7 +136,7 @@ def assert_grad_close(name: str, got_f64: np.ndarray, ref: np.ndarray, mag=None,
     assert mag.shape == ref.shape and np.all(mag >= np.abs(ref) - 1e-9)
     over = err - GRAD_OUT * np.abs(ref) - GRAD_FLOOR          # what the term-relative part has to cover
     ratio = float((over / np.maximum(mag, 1e-30)).max())
-    mean_ratio = float(max(0.0, err.mean() - GRAD_FLOOR) / max(float(mag.mean()), 1e-30))
+    mean_ratio = float(err.mean() / max(float(mag.mean()), 1e-30))
     if tag:
         record_maxima(f"{tag} {name}", max=err.max(), mean=err.mean(), ref_max=np.abs(ref).max(), mag_max=mag.max(), term_ratio=max(0.0, ratio),
                       mean_ratio=mean_ratio)
