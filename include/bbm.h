@@ -48,9 +48,11 @@ extern "C" {
                                      skip the element mask inside [offset, offset + total_ones)                        */
 #define BBM_MODE_LIST 2           /* walk the compact per-row list of non-zero blocks; element mask skipped on blocks
                                      flagged full; rows the split schedule cut are computed part by part by extra
-                                     work-groups and merged; a launch of fewer than 128 work-groups (B*H*nbr) over at
-                                     least 64 block columns computes EVERY block row in min(8, 512 / (B*H*nbr), nbc / 32)
-                                     equal parts instead                                                               */
+                                     work-groups and merged                                                            */
+/* Small launches, all three schedules above: fewer than 128 work-groups (B*H*nbr) over at least 64 block columns leave
+ * most of the chip idle, so EVERY block row is computed in min(8, 512 / (B*H*nbr), nbc / 32) equal parts (of its list, resp.
+ * of the block columns) by as many work-groups and merged in part order.  This needs the workspace; BITMAP and RUNS, which
+ * otherwise need none, run one work-group per block row when none is given. */
 #define BBM_MODE_DENSE_BASELINE 3 /* paper Sec. 3 "naive masking": visit every block, apply the element mask everywhere */
 #define BBM_MODE_AUTO 4           /* LIST if the index carries list and schedule, else RUNS, else BITMAP               */
 
@@ -177,7 +179,9 @@ int bbm_build_index(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t n
 size_t bbm_sched_bytes(int64_t Mb, int64_t nbr);
 
 /*
- * Bytes of device workspace bbm_attn_fwd needs for this problem (0 if none).  Negative sizes return 0.
+ * Bytes of device workspace bbm_attn_fwd needs for this problem (0 if none).  Negative sizes return 0.  LIST (and AUTO)
+ * must be given it; for BITMAP and RUNS it is what a small launch (see the modes) needs to be computed in parts, and
+ * optional.
  * Layout: (8 + B*H*ceil(N/Br)) int32 queue counters, rounded up to 256 bytes -- the only part that has to be zero --
  * then room for partial results: (d/2 + 2) * 2*Br floats per record, one record per (cut part, batch, head) resp.
  * per (block row, part, batch, head) of a small launch.  The room for cut rows stops at 32 MiB; a schedule whose parts

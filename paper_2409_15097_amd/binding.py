@@ -329,7 +329,7 @@ def bbm_attn_fwd_rect(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: Bl
     Equal Nq and Nk go through the square entry point of the library."""
     B, H, N, Nk, d, softmax_scale, out, lse = _fwd_args(q, k, v, idx, softmax_scale, out, lse, stream)
     need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx.Br, idx.Bc, mode)
-    if workspace is None and need > 0 and (mode == BBM_MODE_LIST or idx.sched is not None):
+    if workspace is None and need > 0:
         workspace = _cached_workspace("fwd", need, q.device, stream, (B, H, N, d, idx.Br))
     cs = idx.c_struct()
     ws_bytes = 0 if workspace is None else workspace.numel()

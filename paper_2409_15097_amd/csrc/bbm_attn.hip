@@ -79,22 +79,24 @@ constexpr uint32_t kNoTile = 0xffffffffu;  // sentinel after the last entry of a
 // Builds, in LDS, the ascending list of tiles one block row visits inside one schedule window; entry =
 // block column | (1 << 31 if the element mask can be skipped there).  Returns the number of entries (uniform).
 // `win` counts windows of kWin block columns.  (BITMAP, RUNS and DENSE_BASELINE; LIST mode copies its list instead.)
+// [clo, chi): the block columns this work-group is responsible for (all of them unless the block row is computed in
+// parts).
 template <int NW>
-__device__ __forceinline__ int build_window(const AttnParams& P, int m, int i, int win, uint32_t* tiles_s, int* cnt_s) {
+__device__ __forceinline__ int build_window(const AttnParams& P, int m, int i, int win, uint32_t* tiles_s, int* cnt_s, int clo, int chi) {
   constexpr int NT = NW * 64;
   constexpr int CH = kWin / 64;  // 64-column chunks per window
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t r = (int64_t)m * P.nbr + i;
   int count;
   if (P.mode == BBM_MODE_DENSE_BASELINE) {
-    const int j0 = win * kWin;
-    count = min(kWin, P.nbc - j0);
+    const int j0 = clo + win * kWin;
+    count = min(kWin, chi - j0);
     for (int t = tid; t < count; t += NT) tiles_s[t] = (uint32_t)(j0 + t);
   } else {
-    int lo = 0, hi = P.nbc, run_lo = 0, run_hi = 0;
+    int lo = clo, hi = chi, run_lo = 0, run_hi = 0;
     if (P.mode == BBM_MODE_RUNS) {
-      lo = P.nz_lo[r];
-      hi = P.nz_hi[r];
+      lo = max(clo, P.nz_lo[r]);
+      hi = min(chi, P.nz_hi[r]);
       run_lo = P.offset[r];
       run_hi = run_lo + P.total_ones[r];
     }
@@ -136,14 +138,17 @@ __device__ __forceinline__ int build_window(const AttnParams& P, int m, int i, i
   return count;
 }
 
-// Number of schedule windows of one block row (uniform).
-__device__ __forceinline__ int num_windows(const AttnParams& P, int m, int i) {
+// Number of schedule windows of the block columns [clo, chi) of one block row (uniform).
+__device__ __forceinline__ int num_windows(const AttnParams& P, int m, int i, int clo, int chi) {
+  int lo = clo, hi = chi;
   if (P.mode == BBM_MODE_RUNS) {
     const int64_t r = (int64_t)m * P.nbr + i;
-    const int lo = P.nz_lo[r] & ~63, hi = P.nz_hi[r];
-    return (hi - lo + kWin - 1) / kWin;
+    lo = max(clo, P.nz_lo[r]);
+    hi = min(chi, P.nz_hi[r]);
   }
-  return (P.nbc + kWin - 1) / kWin;
+  if (hi <= lo) return 0;
+  if (P.mode != BBM_MODE_DENSE_BASELINE) lo &= ~63;
+  return (hi - lo + kWin - 1) / kWin;
 }
 
 template <int V>
@@ -529,15 +534,24 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     i = P.nbr - 1 - (rest - bh * P.nbr);
     m = (P.Mb == 1) ? 0 : bh / P.H;
     const int hb = (P.Mb == 1) ? bh : bh - m * P.H;
-    const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
-    const int p_row = rp[0], n_row = rp[1] - rp[0];
-    const int chunk = (n_row + S - 1) / S;
-    const int p0 = p_row + part * chunk, nt = max(0, min(chunk, n_row - part * chunk));
-    const uint32_t* __restrict__ list = P.col_idx + (int64_t)m * P.nbr * P.nbc + p0;
     begin_item();
-    if (nt > 0) {
-      run_list(list, nt, list[0]);
-    } else if (Q_VIA_LDS && q_pending) {  // nothing to compute: let the Q copies land before anyone reuses the slabs
+    if (P.mode == BBM_MODE_LIST) {  // equal shares of the row's list
+      const int32_t* rp = P.row_ptr + (int64_t)m * (P.nbr + 1) + i;
+      const int p_row = rp[0], n_row = rp[1] - rp[0];
+      const int chunk = (n_row + S - 1) / S;
+      const int p0 = p_row + part * chunk, nt = max(0, min(chunk, n_row - part * chunk));
+      const uint32_t* __restrict__ list = P.col_idx + (int64_t)m * P.nbr * P.nbc + p0;
+      if (nt > 0) run_list(list, nt, list[0]);
+    } else {  // BITMAP, RUNS: equal shares of the block columns
+      const int chunk = (P.nbc + S - 1) / S;
+      const int clo = part * chunk, chi = min(P.nbc, clo + chunk);
+      const int nwin = num_windows(P, m, i, clo, chi);
+      for (int win = 0; win < nwin; ++win) {
+        const int count = build_window<NW>(P, m, i, win, tiles_s, cnt_s, clo, chi);
+        if (count > 0) run_window(count, false);
+      }
+    }
+    if (Q_VIA_LDS && q_pending) {  // nothing was computed: let the Q copies land before anyone reuses the slabs
       __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
       q_pending = false;
@@ -709,9 +723,9 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     } else {
       i = P.nbr - 1 - own_rank;  // from the last row up: long rows first for causal-like masks
       begin_item();
-      const int nwin = num_windows(P, m, i);
+      const int nwin = num_windows(P, m, i, 0, P.nbc);
       for (int win = 0; win < nwin; ++win) {
-        const int count = build_window<NW>(P, m, i, win, tiles_s, cnt_s);
+        const int count = build_window<NW>(P, m, i, win, tiles_s, cnt_s, 0, P.nbc);
         if (count > 0) run_window(count, false);
       }
       write_output();
@@ -754,19 +768,23 @@ inline int split_parts(int64_t total_wgs, int64_t nbc) {
 
 template <int D, int NW, bool EXACT>
 int launch(AttnParams& P, int64_t Mb, void* workspace, size_t workspace_bytes, hipStream_t s) {
-  if (P.mode == BBM_MODE_LIST) {
-    const size_t qb = queue_bytes(Mb, P.nbr, P.hbp);
-    const int64_t cap = (int64_t)std::min<size_t>((workspace_bytes - qb) / record_bytes(D, NW * 32), 0x7fffffff);
+  const size_t qb = queue_bytes(Mb, P.nbr, P.hbp);
+  const bool have_ws = workspace && bbm::aligned(workspace, 16) && workspace_bytes >= qb + record_bytes(D, NW * 32);
+  const int64_t cap = have_ws ? (int64_t)std::min<size_t>((workspace_bytes - qb) / record_bytes(D, NW * 32), 0x7fffffff) : 0;
+  if (have_ws) {
     P.queue = static_cast<int32_t*>(workspace);
     P.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + qb);
     P.part_cap = (int32_t)cap;
-    P.n_extra = P.total_wgs < kExtraWGs ? P.total_wgs : kExtraWGs;
-    P.split = split_parts(P.total_wgs, P.nbc);
+    // a launch too small to fill the chip computes every block row in parts (not the dense-tile baseline, which stands
+    // for the plain one-program-per-query-block kernel)
+    if (P.mode != BBM_MODE_DENSE_BASELINE) P.split = split_parts(P.total_wgs, P.nbc);
     while (P.split > 1 && (int64_t)P.total_wgs * P.split > cap) --P.split;  // every (row, part, head) parks a record
-    if (P.split > 1)
-      attn_fwd_kernel<D, NW, 2, EXACT><<<(unsigned)(P.total_wgs * P.split), NW * 64, 0, s>>>(P);
-    else
-      attn_fwd_kernel<D, NW, 1, EXACT><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
+  }
+  if (P.split > 1) {
+    attn_fwd_kernel<D, NW, 2, EXACT><<<(unsigned)(P.total_wgs * P.split), NW * 64, 0, s>>>(P);
+  } else if (P.mode == BBM_MODE_LIST) {
+    P.n_extra = P.total_wgs < kExtraWGs ? P.total_wgs : kExtraWGs;
+    attn_fwd_kernel<D, NW, 1, EXACT><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   } else {
     attn_fwd_kernel<D, NW, 0, EXACT><<<(unsigned)P.total_wgs, NW * 64, 0, s>>>(P);
   }
@@ -777,12 +795,14 @@ int launch(AttnParams& P, int64_t Mb, void* workspace, size_t workspace_bytes, h
 
 extern "C" __attribute__((visibility("default"))) size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int Br, int Bc, int mode) {
   if (B < 1 || H < 1 || N < 1 || Br < 1 || Bc < 1 || (d != 64 && d != 128)) return 0;
-  if (mode != BBM_MODE_LIST && mode != BBM_MODE_AUTO) return 0;
+  if (mode != BBM_MODE_LIST && mode != BBM_MODE_AUTO && mode != BBM_MODE_BITMAP && mode != BBM_MODE_RUNS) return 0;
   // sized for the larger of the two plane counts a caller may use (Mb = 1 or Mb = B): both give Mb*hbp = B*H
   // (N counts the queries; the number of keys is not known here, so the largest split of a small launch is assumed)
   const int64_t nbr = (N + Br - 1) / Br;
   const int split = split_parts(B * H * nbr, 1 << 30);
-  return queue_bytes(1, nbr, B * H) + (split > 1 ? (size_t)(B * H * nbr * split) * record_bytes(d, Br) : partial_bytes(1, nbr, B * H, d, Br));
+  if (split > 1) return queue_bytes(1, nbr, B * H) + (size_t)(B * H * nbr * split) * record_bytes(d, Br);
+  if (mode == BBM_MODE_BITMAP || mode == BBM_MODE_RUNS) return 0;  // these only ever use it for a small launch
+  return queue_bytes(1, nbr, B * H) + partial_bytes(1, nbr, B * H, d, Br);
 }
 
 // ---- Scratch of bbm_attn_fwd_static: a file-scope device array instead of a caller's workspace, for callers that
@@ -874,7 +894,7 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   if (use_static) {
     workspace = nullptr;
     workspace_bytes = 0;
-    if (mode == BBM_MODE_LIST) {
+    if (mode == BBM_MODE_LIST || (mode != BBM_MODE_DENSE_BASELINE && split_parts(B * H * nbr, nbc) > 1)) {
       // the counters and at least one partial result per (batch, head) must fit; what else fits decides whether cut
       // rows and small launches are computed in parts (see launch())
       const size_t floor_bytes = queue_bytes(Mb, nbr, Mb == 1 ? B * H : H) + record_bytes(d, idx->Br);
@@ -888,7 +908,8 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
       if (int rc = launch_status(fn)) return rc;
     }
   } else {
-    const size_t need = bbm_attn_fwd_workspace_bytes(B, H, N, d, idx->Br, idx->Bc, mode);
+    // LIST mode cannot do without its workspace; BITMAP and RUNS use one, if given, to compute a small launch in parts
+    const size_t need = mode == BBM_MODE_LIST ? bbm_attn_fwd_workspace_bytes(B, H, N, d, idx->Br, idx->Bc, mode) : 0;
     if (need > 0 && (!workspace || workspace_bytes < need))
       return fail(BBM_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
     if (need > 0 && !aligned(workspace, 16)) return fail(BBM_EINVAL, "%s: workspace must be 16-byte aligned", fn);
