@@ -117,10 +117,10 @@ def assert_attention_close(o_gpu: torch.Tensor, lse_gpu: torch.Tensor, O_ref: np
 # product in absolute value), plus the output format's rounding of the element itself, plus a small floor:
 #     |error| <= GRAD_TERM * M + 2^-8 * |reference| + GRAD_FLOOR,     mean |error| <= GRAD_TERM_MEAN * mean M.
 # GRAD_TERM is about twice the largest ratio observed over the full-size workloads and the small cases (0.67 %; dV of
-# the tiny random-block mask), GRAD_TERM_MEAN likewise.  Nothing in
+# the tiny random-block mask), GRAD_TERM_MEAN likewise (0.09 % observed).  Nothing in
 # it depends on the tensor's overall size.  Where no magnitudes are at hand (rows and keys sampled out of heads that
 # are not compared whole) the cruder form |error| <= 2e-2 * (1 + |reference|) is used.
-GRAD_TERM, GRAD_TERM_MEAN, GRAD_OUT, GRAD_FLOOR = 1.5e-2, 5e-3, 2.0 ** -8, 1e-3
+GRAD_TERM, GRAD_TERM_MEAN, GRAD_OUT, GRAD_FLOOR = 1.5e-2, 2e-3, 2.0 ** -8, 1e-3
 GRAD_ABS, GRAD_REL = O_MAX_ABS, 2e-2
 
 
