@@ -95,6 +95,9 @@ def parse():
     ap.add_argument("--only-kernel", default="",
                     help="profile helper: run only 'attn', 'dense' (dense-tile baseline), 'bwd', 'preprocess', 'index' or "
                          "'copy' (256 MiB device copy) launches of --workload")
+    ap.add_argument("--scaling", action="store_true",
+                    help="instead of the benchmark line: attention time against the number of non-zero blocks, for a window "
+                         "mask of fixed width (blocks grow like N) and the causal mask (blocks grow like N^2) at several N")
     ap.add_argument("--B", type=int, default=0, help="with --only-kernel: override the workload's batch size")
     ap.add_argument("--H", type=int, default=0, help="with --only-kernel: override the workload's head count")
     return ap.parse_args()
@@ -372,6 +375,38 @@ def only_kernel(a, bbm, torch):
     return 0
 
 
+def scaling_study(a, bbm, torch):
+    """Does the run time follow the number of non-zero blocks rather than N^2 (the method's claim, paper Sec. 4)?  One head
+    count and head dimension throughout (B=1, H=16, d=64); masks built on the device; Q, K, V seeded normal bf16."""
+    B, H, d, Br = 1, 16, 64, a.Br
+    rows = []
+    for family, sizes in (("window +-256", (2048, 4096, 8192, 16384, 32768)), ("causal", (2048, 4096, 8192, 16384))):
+        for N in sizes:
+            i = torch.arange(N, device="cuda", dtype=torch.int32)
+            mask = torch.empty((1, N, N), dtype=torch.uint8, device="cuda")
+            for r0 in range(0, N, 4096):                      # row slabs: the index difference matrix is never whole
+                diff = i[r0:r0 + 4096, None] - i[None, :]
+                mask[0, r0:r0 + 4096] = ((diff.abs() <= 256) if family.startswith("window") else (diff >= 0)).to(torch.uint8)
+            del diff
+            gen = torch.Generator(device="cuda").manual_seed(1234 + N)
+            q, k, v = (torch.randn((B, H, N, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+            idx = bbm.build_index(mask, Br, 64)
+            out = torch.empty_like(q)
+            lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+            ws = torch.zeros(max(16, bbm.bbm_attn_fwd_workspace_bytes(B, H, N, d, Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
+            tiles = visited_tiles(idx, B, H)
+            ms = time_gpu(lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws), a.warmup, a.steps)
+            dense_ms = time_gpu(lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_DENSE_BASELINE, out=out, lse=lse), 1, max(2, min(a.steps, 10)))
+            pre_ms = time_gpu(lambda: bbm.bbm_build_block_mask(mask, Br, 64, idx=idx), a.warmup, a.steps)
+            rows.append(dict(mask=family, N=N, nonzero_blocks=tiles // H, all_blocks=idx.nbr * idx.nbc, attn_ms=ms,
+                             us_per_1000_blocks_per_head=ms * 1e3 / (tiles / 1000.0) * H, dense_tile_ms=dense_ms,
+                             tflops_visited=4.0 * Br * 64 * d * tiles / (ms * 1e-3) / 1e12, preprocess_ms=pre_ms))
+            del mask, q, k, v, idx, out, lse, ws
+            torch.cuda.empty_cache()
+    print(json.dumps({"study": "attention time against non-zero blocks", "B": B, "H": H, "d": d, "Br": Br, "Bc": 64, "rows": rows}))
+    return 0
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -386,6 +421,8 @@ def main():
 
     if a.only_kernel:
         return only_kernel(a, bbm, torch)
+    if a.scaling:
+        return scaling_study(a, bbm, torch)
 
     main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch, not a.no_backward, not a.no_cold)
     rows = [main_res]
