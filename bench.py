@@ -325,7 +325,7 @@ def cpu_baseline(cfg, Br, budget_s=20.0, rows_per_chunk=2048):
                 break
         if done:
             break
-    return dict(value=flops / (t_idx + t_attn) / 1e12, unit="TFLOP/s (visited tiles)", cores=int(threads), kind="oracle",
+    return dict(value=flops / (t_idx + t_attn) / 1e12 if slabs else 0.0, unit="TFLOP/s (visited tiles)", cores=int(threads), kind="oracle",
                 sample=f"{slabs} slabs of up to {rows_per_chunk} query rows = {rows_done} of {B * H * Nq} (batch, head, query) rows of "
                        f"{cfg['name']} (N={N}, d={d}): block index of the slab's mask rows ({t_idx:.2f} s) + dense fp64 masked "
                        f"attention against all {N} keys ({t_attn:.2f} s)",
