@@ -15,4 +15,4 @@ void clear_error() { g_err[0] = '\0'; }
 }  // namespace bbm
 
 extern "C" __attribute__((visibility("default"))) const char* bbm_last_error(void) { return bbm::g_err; }
-extern "C" __attribute__((visibility("default"))) int bbm_version(void) { return 200; }  // 2.0.0: bbm_index carries the mask extents; bbm_attn_fwd_static added
+extern "C" __attribute__((visibility("default"))) int bbm_version(void) { return 200; }  // 0.2.0: bbm_index carries the mask extents; bbm_attn_fwd_static added
