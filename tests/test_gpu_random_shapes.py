@@ -1,0 +1,89 @@
+"""GPU parity on seeded random problem shapes: batch, heads, query and key counts (square, rectangular, ragged), head
+dimension, tile height, mask planes, mask structure and softmax scale are all drawn per case, every schedule runs, and
+O / lse are compared with the fp64 oracle element by element.  Half of the cases are small launches over many block
+columns, which every mask-aware schedule computes in parts."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import make_qkv
+from gpu_util import bf16_tensor, assert_attention_close, assert_index_equal, index_to_numpy
+
+pytestmark = pytest.mark.gpu
+
+MODES = ["BITMAP", "RUNS", "LIST", "DENSE_BASELINE", "AUTO"]
+
+
+def _random_mask(rng, Mb, Nq, Nk):
+    """Bands, full stripes, random 32 x 32 blocks, Bernoulli noise and fully masked rows, mixed at random per plane."""
+    out = np.zeros((Mb, Nq, Nk), dtype=np.uint8)
+    i, j = np.arange(Nq)[:, None], np.arange(Nk)[None, :]
+    for m in range(Mb):
+        kind = rng.integers(4)
+        if kind == 0:                                   # a band that follows the diagonal of the rectangle
+            centre = (i * Nk) // max(Nq, 1)
+            out[m] = np.abs(j - centre) <= rng.integers(8, max(9, Nk // 6))
+        elif kind == 1:                                 # random blocks: empty / full / half full
+            bi, bj = -(-Nq // 32), -(-Nk // 32)
+            cls = rng.choice(3, size=(bi, bj), p=[0.55, 0.25, 0.2])
+            blk = np.kron(cls, np.ones((32, 32), dtype=np.int64))[:Nq, :Nk]
+            out[m] = (blk == 1) | ((blk == 2) & (rng.random((Nq, Nk)) < 0.5))
+        elif kind == 2:                                 # causal against the end of the keys (new tokens at the end of a cache)
+            out[m] = j <= i + (Nk - Nq)
+        else:                                           # sparse noise
+            out[m] = rng.random((Nq, Nk)) < 0.02
+        if rng.random() < 0.5:
+            lo = int(rng.integers(0, max(1, Nk - 64)))
+            out[m][:, lo:lo + int(rng.integers(1, 200))] = 1            # keys everybody sees: full tiles
+        if rng.random() < 0.5:
+            r = int(rng.integers(0, Nq))
+            out[m][r:r + int(rng.integers(1, 40))] = 1                   # queries that see every key
+        dead = rng.integers(0, Nq, size=max(1, Nq // 12))
+        out[m][dead] = 0                                                 # fully masked rows
+    return out
+
+
+def _case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    small_launch = seed % 2 == 0
+    d = int(rng.choice([64, 128]))
+    Br = int(rng.choice([64, 128, 256]))
+    if small_launch:                                    # few block rows against >= 64 block columns
+        B, H = 1, int(rng.integers(1, 4))
+        Nq, Nk = int(rng.integers(1, 3 * Br)), int(rng.integers(4096, 9000))
+    else:
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        Nk = int(rng.integers(1, 1500))
+        Nq = Nk if rng.random() < 0.5 else int(rng.integers(1, 700))
+    Mb = B if rng.random() < 0.4 else 1
+    scale = [None, None, 0.05, 0.2, 0.4][int(rng.integers(5))]
+    q = make_qkv(B, H, Nq, d, seed=2000 + seed)[0]
+    _, k, v = make_qkv(B, H, Nk, d, seed=3000 + seed)
+    return dict(B=B, H=H, Nq=Nq, Nk=Nk, d=d, Br=Br, Mb=Mb, scale=scale, q=q, k=k, v=v, mask=_random_mask(rng, Mb, Nq, Nk))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shape(seed):
+    import paper_2409_15097_amd as bbm
+    c = _case(seed)
+    print(f"random case {seed}: B={c['B']} H={c['H']} Nq={c['Nq']} Nk={c['Nk']} d={c['d']} Br={c['Br']} Mb={c['Mb']} scale={c['scale']}", flush=True)
+    O_ref, lse_ref = oracle.masked_attention(c["q"], c["k"], c["v"], c["mask"], scale=c["scale"])
+    idx = bbm.build_index(torch.from_numpy(c["mask"]).cuda(), c["Br"], 64)
+    torch.cuda.synchronize()
+    assert_index_equal(index_to_numpy(idx), c["mask"], c["Br"], 64)
+    qt, kt, vt = (bf16_tensor(c[x]) for x in "qkv")
+    outs = {}
+    for mode in MODES:
+        o, lse = bbm.bbm_attn_fwd_rect(qt, kt, vt, idx, mode=getattr(bbm, "BBM_MODE_" + mode), softmax_scale=c["scale"])
+        torch.cuda.synchronize()
+        assert_attention_close(o, lse, O_ref, lse_ref)
+        outs[mode] = (o.clone(), lse.clone())
+    # same tile order and arithmetic: RUNS = BITMAP and AUTO = LIST, bit for bit (split or not, they split alike)
+    assert torch.equal(outs["RUNS"][0].view(torch.int16), outs["BITMAP"][0].view(torch.int16)) and torch.equal(outs["RUNS"][1], outs["BITMAP"][1])
+    assert torch.equal(outs["AUTO"][0].view(torch.int16), outs["LIST"][0].view(torch.int16)) and torch.equal(outs["AUTO"][1], outs["LIST"][1])
+    # the entry point without a workspace agrees with the one that takes one
+    o_st, lse_st = torch.empty_like(outs["LIST"][0]), torch.empty_like(outs["LIST"][1])
+    bbm.bbm_attn_fwd_static(qt, kt, vt, idx, o_st, lse_st, mode=bbm.BBM_MODE_LIST, softmax_scale=c["scale"])
+    torch.cuda.synchronize()
+    assert_attention_close(o_st, lse_st, O_ref, lse_ref)
