@@ -98,6 +98,10 @@ def parse():
     ap.add_argument("--scaling", action="store_true",
                     help="instead of the benchmark line: attention time against the number of non-zero blocks, for a window "
                          "mask of fixed width (blocks grow like N) and the causal mask (blocks grow like N^2) at several N")
+    ap.add_argument("--operands", action="store_true",
+                    help="instead of the benchmark: the matrix-only probe and the dense attention kernel on normal, four-valued and "
+                         "constant operands (how much of the gap to the published peak is the chip's clock under load)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured ceilings (matrix-only probe, device copy)")
     ap.add_argument("--B", type=int, default=0, help="with --only-kernel: override the workload's batch size")
     ap.add_argument("--H", type=int, default=0, help="with --only-kernel: override the workload's head count")
     return ap.parse_args()
@@ -407,6 +411,49 @@ def scaling_study(a, bbm, torch):
     return 0
 
 
+def measure_ceilings(bbm, torch):
+    """What this chip sustains, next to the published figures the roofline is quoted against: matrix instructions
+    alone (bbm_probe_mfma_bf16: one wave per SIMD, operands in registers) on constant and on normal operands, and a
+    256 MiB device-to-device copy.  Each probe launch is preceded by a shorter one, so the clock has settled."""
+    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    res = {}
+    for key, normal in (("mfma_bf16_constant_operands_tflops", False), ("mfma_bf16_normal_operands_tflops", True)):
+        bbm.bbm_probe_mfma_bf16(normal, 20000, sink)
+        ms = time_gpu(lambda: bbm.bbm_probe_mfma_bf16(normal, 100000, sink), 0, 1)
+        res[key] = bbm.bbm_probe_mfma_bf16_flop(100000) / (ms * 1e-3) / 1e12
+    src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    ms = time_gpu(lambda: dst.copy_(src), 3, 10)
+    res["device_copy_gbs"] = 2.0 * src.numel() / (ms * 1e-3) / 1e9
+    return res
+
+
+def operand_study(a, bbm, torch):
+    """The same dense attention launch on three kinds of operands.  The instruction stream is identical; what changes
+    is the power the arithmetic units draw, and with it the clock the chip holds."""
+    rows = []
+    gen = torch.Generator(device="cuda").manual_seed(99)
+    kinds = {
+        "normal(0,1)": lambda shape: tuple(torch.randn(shape, generator=gen, device="cuda").to(torch.bfloat16) for _ in range(3)),
+        "four values (+-0.5, +-1.5)": lambda shape: tuple((torch.randint(0, 4, shape, generator=gen, device="cuda").float() - 1.5).to(torch.bfloat16) for _ in range(3)),
+        "constant (0.5, 0.25, 1.0)": lambda shape: tuple(torch.full(shape, c, device="cuda", dtype=torch.bfloat16) for c in (0.5, 0.25, 1.0)),
+    }
+    for (B, H, N, d) in ((2, 32, 8192, 128), (4, 16, 4096, 64)):
+        mask = torch.ones((1, N, N), dtype=torch.uint8, device="cuda")
+        idx = bbm.build_index(mask, a.Br, 64)
+        out = torch.empty((B, H, N, d), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        ws = torch.zeros(max(16, bbm.bbm_attn_fwd_workspace_bytes(B, H, N, d, a.Br, 64, bbm.BBM_MODE_LIST)), dtype=torch.uint8, device="cuda")
+        for kind, make in kinds.items():
+            q, k, v = make((B, H, N, d))
+            ms = time_gpu(lambda: bbm.bbm_attn_fwd(q, k, v, idx, mode=bbm.BBM_MODE_AUTO, out=out, lse=lse, workspace=ws), a.warmup, a.steps)
+            rows.append(dict(B=B, H=H, N=N, d=d, operands=kind, attn_ms=ms, tflops=4.0 * B * H * N * N * d / (ms * 1e-3) / 1e12))
+        del mask, idx, out, lse, ws, q, k, v
+    print(json.dumps({"study": "dense attention forward against the kind of operands", "Br": a.Br, "Bc": 64,
+                      "ceilings": measure_ceilings(bbm, torch), "rows": rows}))
+    return 0
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -423,6 +470,8 @@ def main():
         return only_kernel(a, bbm, torch)
     if a.scaling:
         return scaling_study(a, bbm, torch)
+    if a.operands:
+        return operand_study(a, bbm, torch)
 
     main_res, main_cfg = measure_mask(bbm, a.workload, a.Br, a.warmup, a.steps, torch, not a.no_backward, not a.no_cold)
     rows = [main_res]
@@ -459,6 +508,12 @@ def main():
             "roofline": dict(roofline("attn_bwd_dq_kernel + attn_bwd_dkv_kernel", 2.5 * flops, main_res["bwd_algo_bytes"],
                                       main_res["bwd_ms"], profiled_traffic_bytes("attn_bwd_kernels", a.workload)),
                              executed_tflops=main_res["bwd_executed_tflops"])}
+    if not a.no_ceilings:
+        # measured on this chip in this run; the roofline above stays priced against the published peaks
+        out["ceilings"] = measure_ceilings(bbm, torch)
+        if out["roofline"]["bound"] == "mfma":
+            out["roofline"]["frac_of_measured_matrix_rate_normal_operands"] = (
+                out["roofline"]["achieved"] / out["ceilings"]["mfma_bf16_normal_operands_tflops"])
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(main_cfg, a.Br)
     print(json.dumps(out))

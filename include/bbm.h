@@ -372,6 +372,22 @@ int bbm_permute_mask(const uint8_t* mask, int64_t Mb, int64_t N, int64_t row_str
 int bbm_gather_rows(const void* in, const int32_t* perm, void* out, int64_t BH, int64_t N, int d, int inverse,
                     void* stream);
 
+/* ---- Hardware-ceiling probe (measurement aid, no part of the method) -------------------------------------------- */
+
+/*
+ * Launches one kernel that issues only `v_mfma_f32_32x32x16_bf16` instructions: 256 work-groups of 4 waves (one wave
+ * per SIMD of a 256-CU chip), each wave `iters` times a chain of 16 instructions over four accumulators, operands held
+ * in registers.  normal_operands = 0: every operand element is one small constant; != 0: seeded, nearly normal values
+ * of unit variance, different in every lane and fragment (the arithmetic units draw more power on such operands, and
+ * the chip lowers its clock accordingly, so this is the matrix rate a kernel fed with real data can be set against).
+ * The caller times the launch (events on `stream`); bbm_probe_mfma_bf16_flop(iters) is the flop count of one launch.
+ *   sink             device out, float [65536]: one value per thread, written so that the work cannot be dropped.
+ *   iters            1 .. 2^24 (100000 runs for about 25 ms).
+ * Errors: BBM_EINVAL, BBM_EHIP.
+ */
+int bbm_probe_mfma_bf16(int normal_operands, int64_t iters, float* sink, void* stream);
+double bbm_probe_mfma_bf16_flop(int64_t iters);
+
 #ifdef __cplusplus
 }
 #endif

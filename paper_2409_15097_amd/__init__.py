@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     bbm_last_error, bbm_version, bbm_build_block_mask, bbm_build_block_mask_rect, bbm_attn_fwd_rect, bbm_attn_fwd_static, bbm_build_runs, bbm_build_sparse_index,
     bbm_build_index, bbm_build_col_index, bbm_col_sched_bytes, bbm_attn_bwd_workspace_bytes, bbm_attn_bwd,
     bbm_attn_fwd_workspace_bytes, bbm_attn_fwd, bbm_sched_bytes, build_index, bf16_from_bits,
-    bbm_rcm_workspace_bytes, bbm_rcm_order, bbm_permute_mask, bbm_gather_rows,
+    bbm_rcm_workspace_bytes, bbm_rcm_order, bbm_permute_mask, bbm_gather_rows, bbm_probe_mfma_bf16, bbm_probe_mfma_bf16_flop,
 )

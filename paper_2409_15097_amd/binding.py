@@ -81,6 +81,10 @@ def _load():
     L.bbm_permute_mask.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     L.bbm_gather_rows.restype = ci
     L.bbm_gather_rows.argtypes = [vp, vp, vp, i64, i64, ci, ci, vp]
+    L.bbm_probe_mfma_bf16.restype = ci
+    L.bbm_probe_mfma_bf16.argtypes = [ci, i64, vp, vp]
+    L.bbm_probe_mfma_bf16_flop.restype = C.c_double
+    L.bbm_probe_mfma_bf16_flop.argtypes = [i64]
     return L
 
 
@@ -425,3 +429,17 @@ def bbm_gather_rows(x: torch.Tensor, perm: torch.Tensor, inverse: bool = False, 
         out = torch.empty_like(x)
     _check(lib.bbm_gather_rows(_ptr(x), _ptr(perm), _ptr(out), B * H, N, d, 1 if inverse else 0, _stream(stream)))
     return out
+
+
+def bbm_probe_mfma_bf16(normal_operands: bool, iters: int, sink: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Launches the matrix-instruction-only probe kernel (a measurement aid; the caller times it).  sink: float32 CUDA
+    tensor of at least 65536 elements (allocated if None); returned."""
+    if sink is None:
+        sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    assert sink.is_cuda and sink.dtype == torch.float32 and sink.is_contiguous() and sink.numel() >= 65536
+    _check(lib.bbm_probe_mfma_bf16(1 if normal_operands else 0, int(iters), _ptr(sink), _stream(stream)))
+    return sink
+
+
+def bbm_probe_mfma_bf16_flop(iters: int) -> float:
+    return float(lib.bbm_probe_mfma_bf16_flop(int(iters)))

@@ -7,7 +7,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libbbm.so")
-SOURCES = ["bbm_error.hip", "bbm_preprocess.hip", "bbm_index.hip", "bbm_colindex.hip", "bbm_attn.hip", "bbm_attn_bwd.hip", "bbm_reorder.hip"]
+SOURCES = ["bbm_error.hip", "bbm_preprocess.hip", "bbm_index.hip", "bbm_colindex.hip", "bbm_attn.hip", "bbm_attn_bwd.hip", "bbm_reorder.hip", "bbm_probe.hip"]
 
 # packed-fp32 VALU ops are switched off for device code (the host pass warns that it ignores the feature)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -18,12 +18,13 @@ def bbm():
 def test_every_declared_symbol_is_exported(bbm):
     hdr = open(os.path.join(ROOT, "include", "bbm.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(bbm_[a-z_]+)\s*\(", hdr))
+    names = set(re.findall(r"\b(bbm_[a-z0-9_]+)\s*\(", hdr))
     assert names == {"bbm_last_error", "bbm_version", "bbm_build_block_mask", "bbm_build_runs",
                      "bbm_build_sparse_index", "bbm_build_index", "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes",
                      "bbm_attn_fwd", "bbm_build_col_index", "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes",
                      "bbm_attn_bwd", "bbm_build_block_mask_rect", "bbm_attn_fwd_rect", "bbm_rcm_workspace_bytes",
-                     "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows", "bbm_attn_fwd_static"}
+                     "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows", "bbm_attn_fwd_static",
+                     "bbm_probe_mfma_bf16", "bbm_probe_mfma_bf16_flop"}
     raw = C.CDLL(bbm.library_path())
     for n in names:
         assert getattr(raw, n) is not None
@@ -36,7 +37,7 @@ def test_binding_has_the_same_names(bbm):
               "bbm_sched_bytes", "bbm_attn_fwd_workspace_bytes", "bbm_attn_fwd", "bbm_build_col_index",
               "bbm_col_sched_bytes", "bbm_attn_bwd_workspace_bytes", "bbm_attn_bwd", "bbm_build_block_mask_rect",
               "bbm_attn_fwd_rect", "bbm_rcm_workspace_bytes", "bbm_rcm_order", "bbm_permute_mask", "bbm_gather_rows",
-              "bbm_attn_fwd_static"):
+              "bbm_attn_fwd_static", "bbm_probe_mfma_bf16", "bbm_probe_mfma_bf16_flop"):
         assert callable(getattr(bbm, n))
 
 
@@ -219,3 +220,13 @@ def test_reorder_entry_points_reject_bad_arguments(bbm):
     assert L.bbm_gather_rows(FAKE, FAKE, C.c_void_p(0x2000), 2, 64, 60, 0, None) == bbm.BBM_EINVAL
     assert L.bbm_gather_rows(FAKE, FAKE, C.c_void_p(0x2008), 2, 64, 64, 0, None) == bbm.BBM_EINVAL
     assert L.bbm_gather_rows(FAKE, FAKE, FAKE, 2, 64, 64, 0, None) == bbm.BBM_EINVAL
+
+
+def test_matrix_probe_validates_and_counts_its_flop(bbm):
+    L = bbm.lib
+    assert L.bbm_probe_mfma_bf16(1, 1000, None, None) == bbm.BBM_EINVAL and "sink" in bbm.bbm_last_error()
+    assert L.bbm_probe_mfma_bf16(1, 0, FAKE, None) == bbm.BBM_EINVAL
+    assert L.bbm_probe_mfma_bf16(0, (1 << 24) + 1, FAKE, None) == bbm.BBM_EINVAL
+    # 256 work-groups x 4 waves x 16 instructions x 32*32*16 multiply-adds
+    assert bbm.bbm_probe_mfma_bf16_flop(1000) == 256 * 4 * 16 * 1000 * 2 * 32 * 32 * 16
+    assert bbm.bbm_probe_mfma_bf16_flop(0) == 0.0
