@@ -223,7 +223,10 @@ def measure_mask(bbm, name, Br, warmup, steps, torch, backward=False, cold=True)
     res["dense_tile_mfma_frac"] = res["dense_tile_tflops"] / MFMA_BF16_PEAK_TFLOPS
     res["speedup_vs_dense_tile"] = res["dense_tile_ms"] / res["attn_ms"]
     pre_ms = time_gpu(lambda: bbm.bbm_build_block_mask_rect(mask, Br, 64, idx=idx), warmup, steps)
-    pre_bytes = Mb * Nq * N * (1.0 + 1.0 / 8.0) + 2.0 * Mb * idx.nbr * idx.nbc
+    # algorithmic bytes of the block reduction: every mask byte read once; class and BinBlkMat bytes; the packed words of
+    # the non-zero blocks (those of empty blocks are not written)
+    nonzero_blocks = int((idx.blk_class != 0).sum())
+    pre_bytes = 1.0 * Mb * Nq * N + 2.0 * Mb * idx.nbr * idx.nbc + 8.0 * Br * nonzero_blocks
     res["preprocess_ms"] = pre_ms
     res["preprocess_gbs"] = pre_bytes / (pre_ms * 1e-3) / 1e9
     res["preprocess_hbm_frac"] = res["preprocess_gbs"] / HBM_PEAK_GBS

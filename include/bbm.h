@@ -99,6 +99,11 @@ int bbm_version(void);
  *   packed_mask      device out, uint64 [Mb][W][N] with W = ceil(N/64), word-column major: bit t of word
  *                    (m, w, r) is (mask[m][r][64*w + t] != 0), bits for columns >= N are zero; may be NULL.
  *                    Must be 8-byte aligned.  This is the form in which bbm_attn_fwd reads the element mask.
+ *                    Words are written per slab of one block row x 64 columns (rows [i*Br, (i+1)*Br) of word column
+ *                    w), and ONLY for slabs that hold a set bit: an all-zero slab keeps whatever the buffer held.
+ *                    With Bc = 64 a slab is a block and the unwritten ones are exactly the BBM_BLOCK_EMPTY blocks,
+ *                    which no schedule visits (BBM_MODE_DENSE_BASELINE takes their zeros from the class bytes); on a
+ *                    sparse mask that is most of the output, and the writes cost more than their share of the bytes.
  * Errors: BBM_EINVAL (NULL mask/blk_class, Mb/N < 1, stride < N, misaligned packed_mask),
  *         BBM_EUNSUPPORTED (block size outside the ranges above), BBM_EHIP.
  */
@@ -207,7 +212,7 @@ size_t bbm_attn_fwd_workspace_bytes(int64_t B, int64_t H, int64_t N, int d, int 
  *   idx              host pointer; idx->Bc must be 64 and idx->Br one of 64, 128, 256; idx->Mb == Mb;
  *                    idx->Nq = idx->Nk = N and idx->nbr/nbc = ceil(N/Br), ceil(N/Bc).  Members needed per mode:
  *                    BITMAP: bin_blk_mat;  RUNS: bin_blk_mat, offset, total_ones, nz_lo, nz_hi;
- *                    LIST: row_ptr, col_idx, sched;  DENSE_BASELINE: none.
+ *                    LIST: row_ptr, col_idx, sched;  DENSE_BASELINE: bin_blk_mat or blk_class (an empty block has no packed words).
  *   mode             BBM_MODE_*.
  *   workspace        device scratch of at least bbm_attn_fwd_workspace_bytes(...) bytes, 16-byte aligned (may be NULL
  *                    if 0).  LIST mode keeps its queue counters and the partial results of cut block rows there.

@@ -75,6 +75,7 @@ __device__ __forceinline__ float partner_sum(float x) {
 
 constexpr int kWin = 1024;               // tiles per schedule window (block columns, or list entries)
 constexpr uint32_t kNoTile = 0xffffffffu;  // sentinel after the last entry of a window
+constexpr uint32_t kZeroWord = 0x40000000u;  // entry flag: the tile's mask words are all zero and are not in memory
 
 // Builds, in LDS, the ascending list of tiles one block row visits inside one schedule window; entry =
 // block column | (1 << 31 if the element mask can be skipped there).  Returns the number of entries (uniform).
@@ -91,7 +92,9 @@ __device__ __forceinline__ int build_window(const AttnParams& P, int m, int i, i
   if (P.mode == BBM_MODE_DENSE_BASELINE) {
     const int j0 = clo + win * kWin;
     count = min(kWin, chi - j0);
-    for (int t = tid; t < count; t += NT) tiles_s[t] = (uint32_t)(j0 + t);
+    // an empty block's packed words are never written by the block reduction: flag it, the mask word is then 0
+    const uint8_t* row = P.bin_blk_mat + r * P.nbc;
+    for (int t = tid; t < count; t += NT) tiles_s[t] = (uint32_t)(j0 + t) | (row[j0 + t] == 0 ? kZeroWord : 0u);
   } else {
     int lo = clo, hi = chi, run_lo = 0, run_hi = 0;
     if (P.mode == BBM_MODE_RUNS) {
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7));
   };
 
-  auto tile_of = [](uint32_t e) { return e == kNoTile ? -1 : (int)(e & 0x7fffffffu); };
+  auto tile_of = [](uint32_t e) { return e == kNoTile ? -1 : (int)(e & 0x3fffffffu); };
   const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
   // One tile: S^T = K Q^T, mask, online softmax and O^T += V^T P^T for tile e0 whose K and V sit in buffer PB; the
@@ -377,7 +380,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     if (e1 != kNoTile) {
       load_tile_async(Kg, tile_of(e1), k_oth, KBLK);
       load_tile_async(Vg, tile_of(e1), v_oth, VBLK);
-      if ((e1 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e1) * N];
+      if ((e1 >> 30) == 0) mw_nxt = mrow[(int64_t)tile_of(e1) * N];
+      else mw_nxt = 0;
     }
 
     if (live) {
@@ -450,7 +454,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const AttnParams P) {
     mw_nxt = 0;
     load_tile_async(Kg, tile_of(e0), k_s0, KBLK);
     load_tile_async(Vg, tile_of(e0), v_s0, VBLK);
-    if ((e0 >> 31) == 0) mw_nxt = mrow[(int64_t)tile_of(e0) * N];
+    if ((e0 >> 30) == 0) mw_nxt = mrow[(int64_t)tile_of(e0) * N];
   };
 
   // Runs the tiles listed in tiles_s[0 .. count) (followed by sentinels) through the pipeline; `started` says that
@@ -884,6 +888,8 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
         return fail(BBM_EINVAL, "%s: LIST mode needs row_ptr, col_idx and sched", fn);
       break;
     case BBM_MODE_DENSE_BASELINE:
+      // empty blocks have no packed words in memory: the kernel takes their zeros from the class bytes
+      if (!idx->bin_blk_mat && !idx->blk_class) return fail(BBM_EINVAL, "%s: DENSE_BASELINE mode needs idx->bin_blk_mat or idx->blk_class", fn);
       break;
     default:
       return fail(BBM_EINVAL, "%s: unknown mode %d", fn, mode);
@@ -922,7 +928,7 @@ int attn_fwd_impl(const char* fn, const void* q, const void* k, const void* v, v
   P.o = static_cast<__bf16*>(o);
   P.lse = lse;
   P.packed = packed_mask;
-  P.bin_blk_mat = idx->bin_blk_mat;
+  P.bin_blk_mat = idx->bin_blk_mat ? idx->bin_blk_mat : idx->blk_class;  // either is zero exactly on empty blocks
   P.offset = idx->offset;
   P.total_ones = idx->total_ones;
   P.nz_lo = idx->nz_lo;

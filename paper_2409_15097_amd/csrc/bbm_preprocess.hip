@@ -43,6 +43,7 @@ __global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* _
                                                                 uint64_t* __restrict__ packed) {
   __shared__ __attribute__((aligned(8))) uint16_t stage[kWordsPerWG * (kMaxBr + 1) * 4];  // [word][row in block (+1 pad)][quarter]
   __shared__ uint32_t acc[kWaves][64];                  // per wave, per lane: any16 | all16 << 16
+  __shared__ uint32_t word_any[kWordsPerWG];            // per 64-column word: does any of the block row's rows set a bit?
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t c0 = (int64_t)blockIdx.x * kColsPerWG;
@@ -95,6 +96,11 @@ __global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* _
       any_v |= a & 0xffffu;
       all_v &= a >> 16;
     }
+    {  // four lanes of 16 columns make one packed word
+      uint32_t w_any = any_v | __shfl_xor(any_v, 1);
+      w_any |= __shfl_xor(w_any, 2);
+      if ((lane & 3) == 0) word_any[lane >> 2] = w_any;
+    }
     const int g = Bc / 16;  // lanes per block column
     for (int s = 1; s < g; s <<= 1) {
       any_v |= __shfl_xor(any_v, s);
@@ -110,12 +116,15 @@ __global__ __launch_bounds__(kThreads) void block_reduce_kernel(const uint8_t* _
   }
 
   if (packed) {
+    // Words of a (block row x 64 columns) slab without a single set bit are not written: no schedule reads them (the
+    // mask-everywhere baseline takes the zero from the class byte), and on sparse masks they are most of the output.
+    __syncthreads();
     const int64_t W = (N + 63) / 64;
     const int64_t w0 = c0 / 64;
     const uint64_t* stage64 = reinterpret_cast<const uint64_t*>(stage);
     for (int t = threadIdx.x; t < kWordsPerWG * rows; t += kThreads) {
       const int wl = t / rows, rl = t - wl * rows;
-      if (w0 + wl < W) packed[(m * W + w0 + wl) * Nr + r0 + rl] = stage64[wl * BrP + rl];
+      if (w0 + wl < W && word_any[wl] != 0) packed[(m * W + w0 + wl) * Nr + r0 + rl] = stage64[wl * BrP + rl];
     }
   }
 }

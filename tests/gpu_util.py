@@ -62,7 +62,16 @@ def assert_index_equal(got: dict, mask: np.ndarray, Br: int, Bc: int):
         Mb, _, nbc = want["cls"].shape
         assert np.array_equal(got["col_sched"][-4 * Mb * nbc:], want["col_sched"][-4 * Mb * nbc:])     # launch-order records
     if got["packed_mask"] is not None:
-        assert np.array_equal(got["packed_mask"], oracle.packed_bits(mask))
+        # words of a (block row x 64 columns) slab that holds no allowed pair are not written (nothing reads them);
+        # every other word is compared bit for bit
+        ref = oracle.packed_bits(mask)
+        Mb, W, Nq = ref.shape
+        nbr = -(-Nq // Br)
+        nonzero = np.zeros((Mb, W, nbr * Br), dtype=bool)
+        nonzero[:, :, :Nq] = ref != 0
+        written = np.repeat(nonzero.reshape(Mb, W, nbr, Br).any(axis=3), Br, axis=2)[:, :, :Nq]
+        assert got["packed_mask"].shape == ref.shape
+        assert np.array_equal(got["packed_mask"][written], ref[written])
 
 
 # Tolerances for bf16 inputs/outputs against the fp64 oracle (max-abs, mean-abs on O; max-abs on finite lse).

@@ -110,6 +110,8 @@ def test_attn_fwd_rejects_bad_arguments(bbm):
     assert _attn(bbm, idx, mode=bbm.BBM_MODE_RUNS) == bbm.BBM_EINVAL
     assert _attn(bbm, idx, mode=bbm.BBM_MODE_LIST) == bbm.BBM_EINVAL
     assert _attn(bbm, idx, mode=bbm.BBM_MODE_AUTO) == bbm.BBM_EINVAL          # AUTO falls back to BITMAP, which needs bin_blk_mat
+    # the mask-everywhere baseline takes the zeros of empty blocks from the class bytes (their packed words are not written)
+    assert _attn(bbm, idx, mode=bbm.BBM_MODE_DENSE_BASELINE) == bbm.BBM_EINVAL and "blk_class" in bbm.bbm_last_error()
 
 
 def test_index_built_for_another_length_is_refused_even_with_equal_block_counts(bbm):

@@ -87,6 +87,34 @@ def test_custom_scales_meet_the_same_bars(name, N):
             assert_attention_close(o, lse, O_ref, lse_ref, tag=f"fwd {name} N={N} scale={scale} {mode}")
 
 
+@pytest.mark.parametrize("Br", [64, 128, 256])
+def test_index_rebuilt_in_place_for_a_sparser_mask(Br):
+    """The block reduction writes packed words only for (block row x 64 column) slabs that hold a set bit, so an index
+    rebuilt in place keeps the previous mask's words wherever the new mask has an empty block.  No schedule may see
+    them, the mask-everywhere baseline included."""
+    from gpu_util import index_to_numpy, assert_index_equal
+    bbm = _bbm()
+    cfg = small_variant("C4", N=1024, B=1, H=2)
+    O_ref, lse_ref = oracle.masked_attention(cfg["q"], cfg["k"], cfg["v"], cfg["mask"])
+    q, k, v = (bf16_tensor(cfg[x]) for x in "qkv")
+    idx = bbm.build_index(torch.ones((1, 1024, 1024), dtype=torch.uint8, device="cuda"), Br, 64)
+    assert bool((idx.packed_mask == -1).all())                       # the all-ones mask: every word written, all bits set
+    mask = torch.from_numpy(cfg["mask"]).cuda()
+    bbm.build_index(mask, Br, 64, idx=idx)
+    torch.cuda.synchronize()
+    assert_index_equal(index_to_numpy(idx), cfg["mask"], Br, 64)
+    cls = idx.blk_class.cpu().numpy()[0]
+    assert (cls == 0).any()
+    words = idx.packed_mask.cpu().numpy()[0]                             # [W][N]
+    for i, j in np.argwhere(cls == 0)[:50]:
+        assert np.all(words[j, i * Br:(i + 1) * Br] == -1)           # untouched: still the old mask's words
+    for mode in MODES:
+        print(f"rebuilt index Br={Br} mode={mode}", flush=True)
+        o, lse = bbm.bbm_attn_fwd(q, k, v, idx, mode=_mode(bbm, mode))
+        torch.cuda.synchronize()
+        assert_attention_close(o, lse, O_ref, lse_ref)
+
+
 def test_key_permutation_changes_blocks_but_not_output():
     """Permuting keys/values together with the mask columns scrambles the block matrix; O must not move."""
     cfg = small_variant("C2", N=1024, B=1, H=2)
