@@ -49,9 +49,10 @@ extern "C" {
 #define BBM_MODE_LIST 2           /* walk the compact per-row list of non-zero blocks; element mask skipped on blocks
                                      flagged full; rows the split schedule cut are computed part by part by extra
                                      work-groups and merged                                                            */
-/* Small launches, all three schedules above: fewer than 128 work-groups (B*H*nbr) over at least 64 block columns leave
- * most of the chip idle, so EVERY block row is computed in min(8, 512 / (B*H*nbr), nbc / 32) equal parts (of its list, resp.
- * of the block columns) by as many work-groups and merged in part order.  This needs the workspace; BITMAP and RUNS, which
+/* Small launches, all three schedules above: at most 256 work-groups (B*H*nbr) over long rows leave compute units idle
+ * or with a single work-group, so EVERY block row is computed in min(8, 512 / (B*H*nbr), nbc / t) equal parts (of its
+ * list, resp. of the block columns) by as many work-groups and merged in part order; t = 32 block columns below 128
+ * work-groups, 64 from there on; fewer than 2 parts means none.  This needs the workspace; BITMAP and RUNS, which
  * otherwise need none, run one work-group per block row when none is given. */
 #define BBM_MODE_DENSE_BASELINE 3 /* paper Sec. 3 "naive masking": visit every block, apply the element mask everywhere */
 #define BBM_MODE_AUTO 4           /* LIST if the index carries list and schedule, else RUNS, else BITMAP               */

@@ -757,16 +757,19 @@ inline size_t partial_bytes(int64_t Mb, int64_t nbr, int64_t hbp, int d, int Br)
   return std::min((size_t)(Mb * nbr * hbp) * record_bytes(d, Br), kPartialCapBytes);
 }
 
-// A LIST-mode launch of fewer than kSplitBelow work-groups leaves most of the 256 CUs idle (a few block rows of new
-// tokens against a long key/value cache): every block row is then computed in split_parts() equal parts -- as many as
-// give every CU two work-groups, but no more than leave a part kSplitMinTiles block columns.  A part costs a prologue,
-// a parked partial result, a device-wide fence and a share of the merge: with 20 tiles per row, 8 parts were 3.5
-// times slower than none; with 260 tiles per row and 64 rows, 4 / 8 parts take 0.114 / 0.108 ms against 0.32 ms
-// unsplit (while every wave fenced for itself, 8 parts were slower than 4: 0.205 against 0.146 ms).
-constexpr int kSplitBelow = 128, kSplitTarget = 512, kSplitMax = 8, kSplitMinTiles = 32;
+// A launch of at most kSplitUpTo work-groups leaves CUs idle or with a single work-group (a few block rows of new
+// tokens against a long key/value cache; one long sequence with few heads): every block row is then computed in
+// split_parts() equal parts -- as many as give every CU two work-groups, but no more than leave a part kSplitMinTiles
+// block columns (twice that from kSplitWide work-groups on: with every CU already busy, parts of 16 tiles on average lost
+// 5 % on a causal mask of 4096, parts of 64 gained 24-39 % from 8192 on).  A part costs a prologue, a parked partial
+// result, a device-wide fence and a share of the merge: with 20 tiles per row, 8 parts were 3.5 times slower than none;
+// with 260 tiles per row and 64 rows, 4 / 8 parts take 0.114 / 0.108 ms against 0.32 ms unsplit; 128 rows of 256 tiles:
+// 0.265 ms unsplit, 0.154 / 0.114 / 0.144 with 2 / 4 / 8 parts; 384 and 512 rows lose 14-40 % with 2.
+constexpr int kSplitUpTo = 256, kSplitWide = 128, kSplitTarget = 512, kSplitMax = 8, kSplitMinTiles = 32;
 inline int split_parts(int64_t total_wgs, int64_t nbc) {
-  if (total_wgs >= kSplitBelow) return 1;
-  const int64_t s = std::min<int64_t>(std::min<int64_t>(kSplitMax, kSplitTarget / total_wgs), nbc / kSplitMinTiles);
+  if (total_wgs > kSplitUpTo) return 1;
+  const int64_t min_tiles = total_wgs < kSplitWide ? kSplitMinTiles : 2 * kSplitMinTiles;
+  const int64_t s = std::min<int64_t>(std::min<int64_t>(kSplitMax, kSplitTarget / total_wgs), nbc / min_tiles);
   return s < 2 ? 1 : (int)s;
 }
 

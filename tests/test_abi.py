@@ -145,13 +145,16 @@ def test_workspace_query_and_check(bbm):
     assert bbm.bbm_attn_fwd_workspace_bytes(0, 16, 4096, 64, 128, 64, bbm.BBM_MODE_LIST) == 0
     # counters (8 + B*H*nbr ints, rounded to 256 bytes) + partial records of (d/2 + 2) * 2*Br floats, capped at 32 MiB
     assert need == 8448 + (32 << 20)
-    assert bbm.bbm_attn_fwd_workspace_bytes(2, 8, 2048, 64, 128, 64, bbm.BBM_MODE_LIST) == 1280 + 256 * 34 * 256 * 4
-    # a small launch (B*H*nbr = 64 < 128 work-groups): 8 parts per block row, each parking a record
+    assert bbm.bbm_attn_fwd_workspace_bytes(4, 8, 2048, 64, 128, 64, bbm.BBM_MODE_LIST) == 2304 + 512 * 34 * 256 * 4
+    # B*H*nbr = 256 work-groups: still a small launch if its rows are long, 2 parts per block row
+    assert bbm.bbm_attn_fwd_workspace_bytes(2, 8, 2048, 64, 128, 64, bbm.BBM_MODE_LIST) == 1280 + 256 * 2 * 34 * 256 * 4
+    # a small launch (B*H*nbr = 64 work-groups): 8 parts per block row, each parking a record
     assert bbm.bbm_attn_fwd_workspace_bytes(1, 32, 256, 128, 128, 64, bbm.BBM_MODE_LIST) == 512 + 64 * 8 * 66 * 256 * 4
     # BITMAP and RUNS ask for the same on a small launch (optional there) and for nothing otherwise
     for mode in (bbm.BBM_MODE_BITMAP, bbm.BBM_MODE_RUNS):
         assert bbm.bbm_attn_fwd_workspace_bytes(1, 32, 256, 128, 128, 64, mode) == 512 + 64 * 8 * 66 * 256 * 4
-        assert bbm.bbm_attn_fwd_workspace_bytes(2, 8, 2048, 64, 128, 64, mode) == 0
+        assert bbm.bbm_attn_fwd_workspace_bytes(2, 8, 2048, 64, 128, 64, mode) == 1280 + 256 * 2 * 34 * 256 * 4
+        assert bbm.bbm_attn_fwd_workspace_bytes(4, 8, 2048, 64, 128, 64, mode) == 0
     assert bbm.bbm_attn_fwd_workspace_bytes(1, 32, 256, 128, 128, 64, bbm.BBM_MODE_DENSE_BASELINE) == 0
     idx = _idx(bbm, row_ptr=0x2000, col_idx=0x3000, sched=0x4000)
     assert _attn(bbm, idx, mode=bbm.BBM_MODE_LIST) == bbm.BBM_EWORKSPACE          # no workspace given

@@ -372,3 +372,40 @@ def test_small_launch_computes_every_block_row_in_parts():
             assert int(ws[:4 * (8 + B * H * nbr)].view(torch.int32).abs().sum()) == 0
             assert torch.all(os_[0, :, 128:192] == 0)
         assert torch.all(o1[0, :, 128:192] == 0)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_launch_of_128_to_256_work_groups_over_long_rows_is_computed_in_parts(d):
+    """One sequence, 8 heads, 2048 new queries against 8300 keys (130 block columns): 256 work-groups at Br = 64 and 128
+    at Br = 128 (2 parts each: at least 64 block columns per part), 64 at Br = 256 (4 parts of at least 32).  Every
+    schedule against the oracle, and against its own unsplit run."""
+    bbm = _bbm()
+    B, H, Nq, Nk = 1, 8, 2048, 8300
+    q = make_qkv(B, H, Nq, d, seed=51)[0]
+    _, k, v = make_qkv(B, H, Nk, d, seed=52)
+    rng = np.random.default_rng(53)
+    i, j = np.arange(Nq)[:, None], np.arange(Nk)[None, :]
+    mask = (j <= i + (Nk - Nq)).astype(np.uint8)[None]          # causal, aligned to the end of the cache
+    mask[0] &= (rng.random((Nq, Nk)) < 0.9).astype(np.uint8)     # with holes: partial tiles everywhere
+    mask[0, :, 1024:3072] = 1                                    # and a stretch of full ones
+    mask[0, 700:830] = 0                                         # fully masked rows (a whole block row at Br = 64 and 128)
+    O_ref, lse_ref = oracle.masked_attention(q, k, v, mask)
+    qt, kt, vt = (bf16_tensor(x) for x in (q, k, v))
+    none = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    for Br in (64, 128, 256):
+        idx = bbm.build_index(torch.from_numpy(mask).cuda(), Br, 64)
+        need = bbm.bbm_attn_fwd_workspace_bytes(B, H, Nq, d, Br, 64, bbm.BBM_MODE_BITMAP)
+        parts = {64: 2, 128: 4, 256: 8}[Br]          # the query does not know the key count: room for 512 / work-groups parts
+        assert need == -(-(8 + H * idx.nbr) * 4 // 256) * 256 + H * idx.nbr * parts * (d // 2 + 2) * 2 * Br * 4
+        ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+        for mode in ("LIST", "BITMAP", "RUNS"):
+            print(f"mid-size launch d={d} Br={Br} mode={mode}", flush=True)
+            o, lse = bbm.bbm_attn_fwd_rect(qt, kt, vt, idx, mode=_mode(bbm, mode), workspace=ws)
+            torch.cuda.synchronize()
+            assert_attention_close(o, lse, O_ref, lse_ref)
+            assert int(ws[:4 * (8 + H * idx.nbr)].view(torch.int32).abs().sum()) == 0
+            if mode != "LIST":                                   # LIST cannot run without its workspace
+                ou, lu = bbm.bbm_attn_fwd_rect(qt, kt, vt, idx, mode=_mode(bbm, mode), workspace=none)
+                torch.cuda.synchronize()
+                assert_attention_close(ou, lu, O_ref, lse_ref)
+                assert not torch.equal(o.view(torch.int16), ou.view(torch.int16))      # another order of the sums
