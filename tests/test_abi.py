@@ -235,3 +235,15 @@ def test_matrix_probe_validates_and_counts_its_flop(bbm):
     # 256 work-groups x 4 waves x 16 instructions x 32*32*16 multiply-adds
     assert bbm.bbm_probe_mfma_bf16_flop(1000) == 256 * 4 * 16 * 1000 * 2 * 32 * 32 * 16
     assert bbm.bbm_probe_mfma_bf16_flop(0) == 0.0
+
+
+def test_package_imports_without_the_library_and_fails_loudly_at_first_use():
+    """`python -m paper_2409_15097_amd.build` has to import the package before a library exists; every use of the
+    binding without one raises (there is no fallback)."""
+    import subprocess, sys
+    code = ("import paper_2409_15097_amd as bbm\n"
+            "try:\n    bbm.bbm_version()\nexcept ImportError as e:\n    print('IMPORT-ERROR', 'no fallback' in str(e))\n"
+            "else:\n    print('LOADED')\n")
+    env = dict(os.environ, BBM_LIBRARY="/nonexistent/libbbm.so")
+    out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, env=env, capture_output=True, text=True, timeout=120)
+    assert out.stdout.strip() == "IMPORT-ERROR True", out.stdout + out.stderr
