@@ -8,7 +8,8 @@ import torch
 
 import oracle
 from workloads import make_qkv
-from gpu_util import bf16_tensor, assert_attention_close, assert_index_equal, index_to_numpy
+from gpu_util import (bf16_tensor, bf16_result_to_f64, assert_attention_close, assert_grad_close, assert_index_equal,
+                      index_to_numpy)
 
 pytestmark = pytest.mark.gpu
 
@@ -87,3 +88,48 @@ def test_random_shape(seed):
     bbm.bbm_attn_fwd_static(qt, kt, vt, idx, o_st, lse_st, mode=bbm.BBM_MODE_LIST, softmax_scale=c["scale"])
     torch.cuda.synchronize()
     assert_attention_close(o_st, lse_st, O_ref, lse_ref)
+
+
+def _square_case(seed):
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([64, 128]))
+    Br = int(rng.choice([64, 128, 256]))
+    B, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    N = int(rng.integers(1, 1400))
+    Mb = B if rng.random() < 0.5 else 1
+    scale = [None, None, 0.05, 0.3][int(rng.integers(4))]
+    q, k, v = make_qkv(B, H, N, d, seed=6000 + seed)
+    d_o = make_qkv(B, H, N, d, seed=7000 + seed)[0]
+    mask = _random_mask(rng, Mb, N, N)
+    if rng.random() < 0.5:                               # a few keys everybody attends and a few nobody does: long and empty block columns
+        mask[:, :, int(rng.integers(0, N))] = 1
+        mask[:, :, int(rng.integers(0, N))] = 0
+    return dict(B=B, H=H, N=N, d=d, Br=Br, Mb=Mb, scale=scale, q=q, k=k, v=v, d_o=d_o, mask=mask)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_square_shape_backward(seed):
+    """The backward pass (column list, dQ, dK, dV) on seeded random square problems, element by element against the oracle,
+    each element judged against the size of the terms it sums."""
+    import paper_2409_15097_amd as bbm
+    c = _square_case(seed)
+    print(f"random backward case {seed}: B={c['B']} H={c['H']} N={c['N']} d={c['d']} Br={c['Br']} Mb={c['Mb']} scale={c['scale']}", flush=True)
+    ref = oracle.masked_attention_bwd(c["q"], c["k"], c["v"], c["mask"], c["d_o"], scale=c["scale"])
+    mags = oracle.masked_attention_bwd_magnitudes(c["q"], c["k"], c["v"], c["mask"], c["d_o"], scale=c["scale"])
+    idx = bbm.build_index(torch.from_numpy(c["mask"]).cuda(), c["Br"], 64, columns=True)
+    torch.cuda.synchronize()
+    assert_index_equal(index_to_numpy(idx), c["mask"], c["Br"], 64)
+    qt, kt, vt, dot = (bf16_tensor(c[x]) for x in ("q", "k", "v", "d_o"))
+    o, lse = bbm.bbm_attn_fwd(qt, kt, vt, idx, softmax_scale=c["scale"])
+    grads = bbm.bbm_attn_bwd(qt, kt, vt, o, dot, lse, idx, softmax_scale=c["scale"])
+    torch.cuda.synchronize()
+    for name, g, r, m in zip(("dQ", "dK", "dV"), grads, ref, mags):
+        assert_grad_close(name, bf16_result_to_f64(g), r, mag=m)
+    # rows without an allowed key and keys nobody attends: exact zeros
+    dead_q = ~np.broadcast_to(c["mask"].any(axis=2)[:, None], (c["mask"].shape[0], c["H"], c["N"]))
+    dead_k = ~np.broadcast_to(c["mask"].any(axis=1)[:, None], (c["mask"].shape[0], c["H"], c["N"]))
+    if c["Mb"] == 1:
+        dead_q, dead_k = np.broadcast_to(dead_q, (c["B"], c["H"], c["N"])), np.broadcast_to(dead_k, (c["B"], c["H"], c["N"]))
+    assert torch.all(grads[0][torch.from_numpy(np.array(dead_q)).cuda()] == 0)
+    assert torch.all(grads[1][torch.from_numpy(np.array(dead_k)).cuda()] == 0)
+    assert torch.all(grads[2][torch.from_numpy(np.array(dead_k)).cuda()] == 0)
