@@ -15,4 +15,4 @@ void clear_error() { g_err[0] = '\0'; }
 }  // namespace bbm
 
 extern "C" __attribute__((visibility("default"))) const char* bbm_last_error(void) { return bbm::g_err; }
-extern "C" __attribute__((visibility("default"))) int bbm_version(void) { return 200; }  // 0.2.0: bbm_index carries the mask extents; bbm_attn_fwd_static added
+extern "C" __attribute__((visibility("default"))) int bbm_version(void) { return 300; }  // 0.3.0: packed words of all-zero slabs are no longer written; DENSE_BASELINE needs the class bytes; bbm_probe_mfma_bf16 added
