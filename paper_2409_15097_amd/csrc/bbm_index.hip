@@ -267,25 +267,27 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(const int32_t* __r
       ncut += 1;
     }
   }
-  pre[0][tid + 1] = nparts;
-  pre[1][tid + 1] = ncut;
-  if (tid == 0) pre[0][0] = pre[1][0] = 0;
-  __syncthreads();
-  if (tid < 2) {  // one thread per column: serial inclusive scan over 256 entries
-    int run = 0;
-    for (int t = 1; t <= kSchedThreads; ++t) {
-      run += pre[tid][t];
-      pre[tid][t] = run;
-    }
+  // exclusive scan over the threads: inside each wave with register moves, then the four wave totals through LDS
+  const int lane = tid & 63, wave = tid >> 6;
+  const int q_in_wave = wave_excl_scan(nparts, lane), rho_in_wave = wave_excl_scan(ncut, lane);
+  if (lane == 63) {
+    pre[0][wave] = q_in_wave + nparts;
+    pre[1][wave] = rho_in_wave + ncut;
   }
   __syncthreads();
+  int q = q_in_wave, rho = rho_in_wave, all_parts = 0, all_cut = 0;
+  for (int w = 0; w < kSchedThreads / 64; ++w) {
+    q += w < wave ? pre[0][w] : 0;
+    rho += w < wave ? pre[1][w] : 0;
+    all_parts += pre[0][w];
+    all_cut += pre[1][w];
+  }
   if (tid == 0) {
-    sched[kSchedNParts] = pre[0][kSchedThreads];
+    sched[kSchedNParts] = all_parts;
     sched[kSchedSplitT] = T;
-    sched[kSchedNCutRows] = pre[1][kSchedThreads];
+    sched[kSchedNCutRows] = all_cut;
     for (int x = 3; x < kSchedPartBase; ++x) sched[x] = 0;
   }
-  int q = pre[0][tid], rho = pre[1][tid];
   for (int r = r_lo; r < r_hi; ++r) {
     const int32_t* rp = first_entry(r);
     const int c = rp[1] - rp[0];
