@@ -186,6 +186,129 @@ __device__ __forceinline__ int launch_rank(const int* len, const int* gmax, int 
   return rank;
 }
 
+// Sum over the 64 lanes, returned in every lane.
+__device__ __forceinline__ int wave_sum(int x) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d);
+  return x;
+}
+
+// list_fill_kernel and sched_kernel in one launch, for index stages that already have every row's list length
+// (`counts` = the runs kernel's nz_cnt, [Mb][nbr]) and at most kFuseSchedRows block rows over all planes: the wave that
+// fills a row's list also writes the row's launch-order record, and the records of its parts if the schedule cuts the row.
+// Everything a wave needs beyond its own row -- the split threshold (a mean over all rows), the parts and cut rows
+// before its own, its rank among the rows of its plane -- it counts itself from `counts` (a few hundred to a few
+// thousand integers), so no wave waits for another.  Same schedule, bit for bit, as sched_kernel writes.
+constexpr int64_t kFuseSchedRows = 4096;
+__global__ __launch_bounds__(kWavesPerWG * 64) void list_fill_sched_kernel(const uint8_t* __restrict__ cls, int Mb, int nbr, int nbc,
+                                                                           int32_t* __restrict__ row_ptr,
+                                                                           const int32_t* __restrict__ counts,
+                                                                           uint32_t* __restrict__ col_idx, int32_t* __restrict__ sched) {
+  using namespace bbm;
+  const int lane = threadIdx.x & 63;
+  const int row = (int)blockIdx.x * kWavesPerWG + (int)(threadIdx.x >> 6);
+  const int nrows = Mb * nbr;
+  if (row >= nrows) return;
+  const int m = row / nbr, i = row - m * nbr;
+  const int32_t* cp = counts + (int64_t)m * nbr;
+  const int c = cp[i];
+
+  // position of the row's list in its plane, and the totals the split threshold is made of
+  int above = 0, total = 0, nonempty = 0;
+  for (int b = lane; b < i; b += 64) above += cp[b];
+  for (int b = lane; b < nrows; b += 64) {
+    const int x = counts[b];
+    total += x;
+    nonempty += x > 0 ? 1 : 0;
+  }
+  const int start = wave_sum(above);
+  total = wave_sum(total);
+  nonempty = wave_sum(nonempty);
+  const int mean = nonempty > 0 ? (total + nonempty - 1) / nonempty : 0;
+  const int T = max(kSchedMinSplit, 2 * mean);
+  if (lane == 0) {
+    row_ptr[(int64_t)m * (nbr + 1) + i] = start;
+    if (i == nbr - 1) row_ptr[(int64_t)m * (nbr + 1) + nbr] = start + c;
+  }
+
+  // parts and cut rows: before this row (rows in (plane, block row) order), and in all
+  int q = 0, rho = 0, all_parts = 0, all_cut = 0;
+  for (int b = lane; b < nrows; b += 64) {
+    const int x = counts[b];
+    const int np_b = x > T ? (x + T - 1) / T : 0;
+    all_parts += np_b;
+    all_cut += np_b > 0 ? 1 : 0;
+    if (b < row) {
+      q += np_b;
+      rho += np_b > 0 ? 1 : 0;
+    }
+  }
+  q = wave_sum(q);
+  rho = wave_sum(rho);
+  if (row == 0) {
+    all_parts = wave_sum(all_parts);
+    all_cut = wave_sum(all_cut);
+    if (lane < kSchedPartBase)
+      sched[lane] = lane == kSchedNParts ? all_parts : lane == kSchedSplitT ? T : lane == kSchedNCutRows ? all_cut : 0;
+  }
+  const int np = c > T ? (c + T - 1) / T : 0;
+  const int chunk = np > 0 ? (c + np - 1) / np : 1;
+  int32_t* const parts = sched + kSchedPartBase + (int64_t)kSchedPartInts * q;
+  for (int k = lane; k < np; k += 64) {
+    int32_t* rec = parts + kSchedPartInts * k;
+    rec[0] = row;
+    rec[1] = start + k * chunk;
+    rec[2] = min(chunk, c - k * chunk);
+    rec[3] = k;
+    rec[4] = np;
+    rec[5] = q;
+    rec[6] = rho;
+  }
+
+  // the list; the lane that writes the entry a part starts with also leaves it in the part's record
+  const uint8_t* cl = cls + (int64_t)row * nbc;
+  uint32_t* out = col_idx + (int64_t)m * nbr * nbc + start;
+  int written = 0, first = -1;
+  for (int base = 0; base < nbc; base += 64) {
+    const uint8_t v = (base + lane < nbc) ? cl[base + lane] : (uint8_t)0;
+    const uint64_t nz = __ballot(v != BBM_BLOCK_EMPTY);
+    const uint64_t full = __ballot(v == BBM_BLOCK_FULL);
+    if (written == 0 && nz != 0) {  // the row's first entry (this happens once: written > 0 from here on)
+      const int bit = ctz64(nz);
+      first = (int)((uint32_t)(base + bit) | (((full >> bit) & 1ull) ? 0x80000000u : 0u));
+    }
+    if (v != BBM_BLOCK_EMPTY) {
+      const int pos = written + __popcll(nz & ((1ull << lane) - 1ull));
+      const uint32_t entry = (uint32_t)(base + lane) | (v == BBM_BLOCK_FULL ? 0x80000000u : 0u);
+      out[pos] = entry;
+      if (np > 0 && pos % chunk == 0 && pos / chunk < np) parts[kSchedPartInts * (pos / chunk) + 7] = (int32_t)entry;
+    }
+    written += __popcll(nz);
+  }
+
+  // launch-order record: rank among the rows of the plane (launch_rank's order, counted over the lanes)
+  const int gsz = launch_group_rows(T);
+  const int ng = (nbr + gsz - 1) / gsz, g = i / gsz;
+  auto group_max = [&](int gg) {
+    int t = 0;
+    for (int j = gg * gsz; j < min(nbr, (gg + 1) * gsz); ++j) t = max(t, cp[j]);
+    return t;
+  };
+  const int mine = group_max(g);
+  int before = 0;
+  for (int gg = lane; gg < ng; gg += 64) {
+    const int t = group_max(gg);
+    before += (t > mine || (t == mine && gg > g)) ? 1 : 0;
+  }
+  before = wave_sum(before);
+  int rank = before * gsz;
+  const int last = ng - 1, last_rows = nbr - last * gsz;
+  if (last != g && group_max(last) >= mine) rank -= gsz - last_rows;
+  for (int j = g * gsz; j < min(nbr, (g + 1) * gsz); ++j) rank += (cp[j] > c || (cp[j] == c && j > i)) ? 1 : 0;
+  if (lane == 0)
+    reinterpret_cast<int4*>(sched + sched_order_base(Mb, nbr))[(int64_t)m * nbr + rank] = make_int4(i, start, c, first);
+}
+
 // Split schedule of LIST mode (layout in bbm_internal.h).  Work-group 0 writes the header and the parts table: every
 // thread owns a contiguous range of block rows; pass 1 counts, per thread, the parts and the cut rows; an exclusive
 // scan over the threads turns the counts into positions; pass 2 writes the parts in (row, part) order, so the
@@ -752,6 +875,10 @@ int launch_list(const uint8_t* blk_class, int64_t Mb, int64_t nbr, int64_t nbc, 
     list_scan_kernel<<<(unsigned)Mb, 64, 0, s>>>(nbr, row_ptr);
     rc = launch_status("bbm_build_sparse_index(scan)");
     if (rc) return rc;
+  }
+  if (scan_in_fill && sched && Mb * nbr <= kFuseSchedRows) {  // list and schedule in one launch
+    list_fill_sched_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, (int)Mb, (int)nbr, (int)nbc, row_ptr, counts, col_idx, sched);
+    return launch_status("bbm_build_sparse_index(fill and schedule)");
   }
   list_fill_kernel<<<grid, kWavesPerWG * 64, 0, s>>>(blk_class, Mb, nbr, nbc, row_ptr, scan_in_fill ? counts : nullptr, col_idx);
   rc = launch_status("bbm_build_sparse_index(fill)");

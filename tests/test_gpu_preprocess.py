@@ -101,3 +101,35 @@ def test_index_bit_exact_full_size(name):
         idx = _run(cfg["mask"], Br, 64, fused=(Br == 128))
         assert_index_equal(index_to_numpy(idx), cfg["mask"], Br, 64)
         del idx
+
+
+@pytest.mark.parametrize("Mb,N,Br,kind", [(3, 6000, 64, "window"), (2, 9000, 128, "packed"), (1, 14000, 128, "graph"), (5, 3333, 32, "window"),
+                                          (2, 8192, 64, "blocks"), (1, 12000, 128, "window")])
+def test_mid_size_class_matrices_list_and_schedule_in_one_launch(Mb, N, Br, kind):
+    """More than 256 (block row, chunk) pairs and at most 1024 block rows per plane: the one-call index stage takes the
+    general path, whose second launch fills the lists and writes the schedule.  Short rows (ranked in groups of four),
+    long rows (ranked singly), rows the schedule cuts, several planes; the two-call stage runs the separate kernels."""
+    rng = np.random.default_rng(N + Br)
+    i, j = np.arange(N)[:, None], np.arange(N)[None, :]
+    mask = np.zeros((Mb, N, N), dtype=np.uint8)
+    for m in range(Mb):
+        if kind == "window":
+            mask[m] = np.abs(i - j) <= 100 + 150 * m
+            mask[m, rng.integers(0, N, 5)] = 1                      # global queries: rows the schedule cuts
+            mask[m][:, rng.integers(0, N, 5)] = 1                   # global keys
+        elif kind == "packed":
+            edges = np.sort(rng.integers(0, N, 40))
+            seg = np.searchsorted(edges, np.arange(N))
+            mask[m] = (seg[:, None] == seg[None, :]) & (j <= i)
+        elif kind == "graph":
+            mask[m] = (rng.random((N, N)) < 0.0005) | (np.abs(i - j) < 3)
+            mask[m, 4000:4040] = 1
+        else:
+            cls = rng.choice(3, size=(-(-N // 64), -(-N // 64)), p=[0.7, 0.2, 0.1])
+            blk = np.kron(cls, np.ones((64, 64), dtype=np.int64))[:N, :N]
+            mask[m] = (blk == 1) | ((blk == 2) & (rng.random((N, N)) < 0.3))
+    for fused in (True, False):
+        idx = _run(mask, Br, 64, fused=fused)
+        got = index_to_numpy(idx)
+        assert_index_equal(got, mask, Br, 64)
+    assert got["sched"][1] >= 32 and (kind != "window" or got["sched"][0] > 0)       # the window masks have cut rows
